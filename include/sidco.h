@@ -1,0 +1,171 @@
+/*
+ * sidco.h - C ABI of the MI355X (gfx950) implementation of the SIDCo gradient
+ * sparsifier (arXiv 2101.10761, "An Efficient Statistical-based Gradient
+ * Compression Technique for Distributed Training Systems").
+ *
+ * What one call computes, on one worker's flat fp32 gradient g of d elements:
+ *   1. error compensation  acc = g + residual           (App. B.2, memory-based compression)
+ *   2. stage-1 fit of a sparsity-inducing distribution to |acc| from the sums
+ *      sum|x|, sum x^2, sum log|x|                        (Corollary 1 / eq. (6); Corollaries 1.2, 1.3)
+ *   3. threshold eta_1 in closed form, refined over M peak-over-threshold
+ *      stages on the exceedances                          (Sec. 2.4: Lemma 2 / eqs. (7)-(9),
+ *                                                          Corollary 2 / eqs. (10)-(11))
+ *   4. C_eta: the pairs (j, acc_j) with |acc_j| > eta_M, their number, and the
+ *      residual update residual_j = 0 for selected j      (Sec. 2.3; Algorithm 1, Sparsify)
+ *
+ * All pointers named "device" are HIP device pointers on the current device;
+ * "host" pointers are ordinary host memory.  No torch types cross this boundary.
+ * Every enqueueing call is asynchronous on `stream` and returns after enqueue;
+ * outputs are valid once the stream reaches that point.  The library never
+ * synchronises with the host inside an enqueueing call, uses no atomics and no
+ * device-side spinning, and its result is deterministic (same inputs -> same
+ * bits, including the order of the output pairs).
+ *
+ * Return value: 0 on success, a negative SIDCO_ERR_* otherwise.  Argument
+ * errors are detected on the host before any HIP call is made.  Conditions
+ * that depend on the data (NaN/Inf input, degenerate fits, output overflow)
+ * never cause out-of-bounds accesses; they are reported in sidco_diag.status.
+ *
+ * Calls that overlap in time on one device share the library's workspace on
+ * that device and race; serialise them (one stream, or events).
+ */
+#ifndef SIDCO_H
+#define SIDCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SIDCO_MAX_STAGES 8
+
+/* `dist`: the first-stage law and with it the chain of later stages
+ * (Sec. 2.4, last paragraph; naming as in App. E/F).                          */
+#define SIDCO_DIST_EXP        0 /* SIDCo-E : exponential, then exponential PoT stages   */
+#define SIDCO_DIST_GAMMA_GPD  1 /* SIDCo-GP: gamma first stage, then GPD PoT stages     */
+#define SIDCO_DIST_GPD        2 /* SIDCo-P : generalized Pareto in every stage          */
+
+/* error codes */
+#define SIDCO_OK              0
+#define SIDCO_ERR_NULL       -1 /* a required pointer is NULL                           */
+#define SIDCO_ERR_SIZE       -2 /* d < 1 or d > 2^31-1, or a capacity < 1               */
+#define SIDCO_ERR_DELTA      -3 /* a ratio is not in (0,1)                              */
+#define SIDCO_ERR_STAGES     -4 /* stages < 1 or > SIDCO_MAX_STAGES                     */
+#define SIDCO_ERR_DIST       -5 /* unknown dist                                         */
+#define SIDCO_ERR_WORKSPACE  -6 /* caller-provided workspace too small or misaligned    */
+#define SIDCO_ERR_HIP        -7 /* a HIP runtime call failed (see sidco_last_hip_error) */
+#define SIDCO_ERR_ALIGN      -8 /* a float/int32 pointer is not 4-byte aligned          */
+#define SIDCO_ERR_ARG        -9 /* any other invalid argument                           */
+
+/* status bits of sidco_diag.status (data-dependent conditions) */
+#define SIDCO_ST_NONFINITE    (1u << 0) /* a stage-1 sum was NaN/Inf: eta = NaN, nothing selected     */
+#define SIDCO_ST_VAR_ZERO     (1u << 1) /* a GPD fit saw variance <= 0: increment = mean             */
+#define SIDCO_ST_GAMMA_S      (1u << 2) /* gamma fit had s <= 0: threshold 0                          */
+#define SIDCO_ST_GAMMA_CLAMP  (1u << 3) /* gamma closed form negative, clamped to 0                    */
+#define SIDCO_ST_STOPPED      (1u << 4) /* an exceedance set was empty: later stages keep eta         */
+#define SIDCO_ST_OVERFLOW     (1u << 5) /* more pairs selected than the output capacity; the excess
+                                           stays in the residual and is not reported                  */
+
+/* Per-call diagnostics, filled on the device by the kernels of the last call. */
+typedef struct sidco_diag {
+    float    eta[SIDCO_MAX_STAGES];      /* eta_m, fp32, m = 1..M (Lemma 2: absolute thresholds)      */
+    int64_t  n[SIDCO_MAX_STAGES];        /* number of elements the stage-m fit ran over (n[0] = d)    */
+    double   stats[SIDCO_MAX_STAGES][3]; /* stage 1: mean|x|, variance (GPD only), mean log|x| (gamma
+                                            only); stage m>=2: mean and variance of |x|-eta_{m-1}
+                                            (variance for GPD chains only); unused entries are 0      */
+    int64_t  selected;                   /* |{j : |acc_j| > eta_M}| before capacity clipping          */
+    int32_t  count;                      /* pairs written = min(selected, capacity)                   */
+    int32_t  stages;                     /* M of the call                                             */
+    uint32_t status;                     /* OR of SIDCO_ST_*                                          */
+    uint32_t reserved;
+} sidco_diag;
+
+/*
+ * The sparsifier (Algorithm 1, function Sparsify, with error compensation).
+ *
+ *  stream     hipStream_t as void*; NULL = the default stream
+ *  grad       device, d floats, read only
+ *  residual   device, d floats, in/out, or NULL.  On entry the error carried
+ *             from the previous iteration; on exit acc = grad + residual with
+ *             zeros at the selected positions (so the next call's step 1 is
+ *             App. B.2's update).  NULL = memoryless variant: acc = grad and
+ *             nothing but out_* is written.  Must not alias grad.
+ *  d          1 <= d <= 2^31-1
+ *  delta      target ratio k/d, 0 < delta < 1 (Sec. 2.3)
+ *  dist       SIDCO_DIST_*
+ *  stages     M, 1..SIDCO_MAX_STAGES.  The ratios are delta_1 = 0.25 (the
+ *             paper's setting, Sec. 4.1) and delta_m = (delta/delta_1)^(1/(M-1))
+ *             for m >= 2, so that their product is delta (Sec. 2.4); if
+ *             delta_1 <= delta or M = 1 a single stage at delta is used.
+ *  out_idx    device, int32, capacity sidco_out_capacity(d, delta)
+ *  out_val    device, float, same capacity: out_val[i] = acc[out_idx[i]]
+ *  out_count  device, 1 int32: number of pairs written (khat)
+ *  out_eta    device, 1 float: eta_M
+ * The pairs are written in a fixed, input-independent traversal order (not
+ * sorted by index).  Buffers are owned by the caller; the library owns only
+ * its workspace, which it allocates on first use per device (hipMalloc) and
+ * grows when d grows, unless sidco_set_workspace was called.
+ */
+int sidco_compress(void *stream, const float *grad, float *residual, int64_t d,
+                   double delta, int dist, int stages,
+                   int32_t *out_idx, float *out_val, int32_t *out_count, float *out_eta);
+
+/*
+ * Same computation with explicit stage ratios delta_1..delta_M (host array,
+ * each in (0,1); the target ratio is their product, Sec. 2.4) and an explicit
+ * capacity of out_idx / out_val in elements.
+ */
+int sidco_compress_ex(void *stream, const float *grad, float *residual, int64_t d,
+                      int dist, const double *ratios, int n_ratios,
+                      int32_t *out_idx, float *out_val, int64_t out_capacity,
+                      int32_t *out_count, float *out_eta);
+
+/* Host helper: the default split of delta over `stages` stages described at
+ * sidco_compress, for a given delta_1.  Writes the ratios to `ratios` (host,
+ * room for SIDCO_MAX_STAGES doubles) and returns their number (>= 1), or a
+ * negative error code.                                                        */
+int sidco_stage_ratios(double delta, int stages, double delta1, double *ratios);
+
+/* Host helper: capacity sidco_compress assumes for out_idx / out_val:
+ * min(d, 4*ceil(delta*d) + 4096).  The paper reports khat/k ~ 1 on average
+ * and at most ~2 for the gamma-GPD chain (App. E); a worse overshoot sets
+ * SIDCO_ST_OVERFLOW and the excess stays in the residual.  Returns a negative
+ * error code for invalid arguments.                                           */
+int64_t sidco_out_capacity(int64_t d, double delta);
+
+/* Host helper: bytes of device workspace a call with this d needs.            */
+size_t sidco_workspace_bytes(int64_t d);
+
+/* Give the library a caller-owned device workspace (256-byte aligned) for the
+ * current device instead of letting it allocate; NULL/0 returns to library
+ * allocation.  The buffer must outlive every call that uses it.               */
+int sidco_set_workspace(void *device_ptr, size_t bytes);
+
+/* Copy the diagnostics of the last call on the current device to host memory.
+ * Synchronises `stream`.                                                      */
+int sidco_read_diag(void *stream, sidco_diag *host_out);
+
+/* Per-kernel timing of the calls that follow (HIP events recorded on the
+ * call's stream around every kernel).  sidco_get_profile synchronises on the
+ * last event and returns the number of kernels of the last call, writing up to
+ * `cap` durations in milliseconds to `ms` and, if names != NULL, pointers to
+ * static kernel-name strings.                                                 */
+int sidco_set_profiling(int enable);
+int sidco_get_profile(float *ms, const char **names, int cap);
+
+/* Text for an error code; the HIP error string of the last SIDCO_ERR_HIP.     */
+const char *sidco_strerror(int code);
+const char *sidco_last_hip_error(void);
+
+/* Library version (major*100 + minor).                                        */
+int sidco_version(void);
+
+/* Free the library-owned workspaces and events of every device.               */
+void sidco_shutdown(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SIDCO_H */

@@ -1,0 +1,207 @@
+"""Thin ctypes binding of libsidco.so: argument marshalling only.
+
+Function names and argument order follow include/sidco.h.  Tensors are torch tensors on the GPU
+(torch is used for device memory and streams, nothing else); every step of the sparsifier runs in
+the library's HIP kernels.  There is no fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsidco.so")
+
+MAX_STAGES = 8
+DIST_EXP, DIST_GAMMA_GPD, DIST_GPD = 0, 1, 2
+ST_NONFINITE, ST_VAR_ZERO, ST_GAMMA_S, ST_GAMMA_CLAMP, ST_STOPPED, ST_OVERFLOW = 1, 2, 4, 8, 16, 32
+
+EXPORTS = [
+    "sidco_compress", "sidco_compress_ex", "sidco_stage_ratios", "sidco_out_capacity",
+    "sidco_workspace_bytes", "sidco_set_workspace", "sidco_read_diag", "sidco_set_profiling",
+    "sidco_get_profile", "sidco_strerror", "sidco_last_hip_error", "sidco_version", "sidco_shutdown",
+]
+
+
+class Diag(C.Structure):
+    """Mirror of struct sidco_diag."""
+    _fields_ = [
+        ("eta", C.c_float * MAX_STAGES),
+        ("n", C.c_int64 * MAX_STAGES),
+        ("stats", (C.c_double * 3) * MAX_STAGES),
+        ("selected", C.c_int64),
+        ("count", C.c_int32),
+        ("stages", C.c_int32),
+        ("status", C.c_uint32),
+        ("reserved", C.c_uint32),
+    ]
+
+
+class SidcoError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        lib = load()
+        msg = lib.sidco_strerror(code).decode()
+        if code == -7:
+            msg += " (" + lib.sidco_last_hip_error().decode() + ")"
+        super().__init__(f"{where}: error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Loads libsidco.so; raises if it has not been built (python -m paper_2101_10761_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2101_10761_amd.build` "
+            "(there is no CPU or PyTorch fallback for the sparsifier)")
+    lib = C.CDLL(LIB_PATH)
+    vp, f32p, i32p, f64p = C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)
+    lib.sidco_compress.argtypes = [vp, f32p, f32p, C.c_int64, C.c_double, C.c_int, C.c_int, i32p, f32p, i32p, f32p]
+    lib.sidco_compress.restype = C.c_int
+    lib.sidco_compress_ex.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int, f64p, C.c_int, i32p, f32p, C.c_int64,
+                                      i32p, f32p]
+    lib.sidco_compress_ex.restype = C.c_int
+    lib.sidco_stage_ratios.argtypes = [C.c_double, C.c_int, C.c_double, f64p]
+    lib.sidco_stage_ratios.restype = C.c_int
+    lib.sidco_out_capacity.argtypes = [C.c_int64, C.c_double]
+    lib.sidco_out_capacity.restype = C.c_int64
+    lib.sidco_workspace_bytes.argtypes = [C.c_int64]
+    lib.sidco_workspace_bytes.restype = C.c_size_t
+    lib.sidco_set_workspace.argtypes = [vp, C.c_size_t]
+    lib.sidco_set_workspace.restype = C.c_int
+    lib.sidco_read_diag.argtypes = [vp, C.POINTER(Diag)]
+    lib.sidco_read_diag.restype = C.c_int
+    lib.sidco_set_profiling.argtypes = [C.c_int]
+    lib.sidco_set_profiling.restype = C.c_int
+    lib.sidco_get_profile.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_char_p), C.c_int]
+    lib.sidco_get_profile.restype = C.c_int
+    lib.sidco_strerror.argtypes = [C.c_int]
+    lib.sidco_strerror.restype = C.c_char_p
+    lib.sidco_last_hip_error.argtypes = []
+    lib.sidco_last_hip_error.restype = C.c_char_p
+    lib.sidco_version.argtypes = []
+    lib.sidco_version.restype = C.c_int
+    lib.sidco_shutdown.argtypes = []
+    lib.sidco_shutdown.restype = None
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise SidcoError(rc, where)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream_handle(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _check_tensor(t, dtype, name, n=None):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous CUDA tensor of dtype {dtype}")
+    if n is not None and t.numel() < n:
+        raise ValueError(f"{name} has {t.numel()} elements, needs {n}")
+
+
+def sidco_stage_ratios(delta: float, stages: int, delta1: float = 0.25) -> list[float]:
+    out = (C.c_double * MAX_STAGES)()
+    m = load().sidco_stage_ratios(delta, stages, delta1, out)
+    if m < 1:
+        raise SidcoError(m, "sidco_stage_ratios")
+    return [out[i] for i in range(m)]
+
+
+def sidco_out_capacity(d: int, delta: float) -> int:
+    cap = load().sidco_out_capacity(d, delta)
+    if cap < 0:
+        raise SidcoError(int(cap), "sidco_out_capacity")
+    return int(cap)
+
+
+def sidco_workspace_bytes(d: int) -> int:
+    return int(load().sidco_workspace_bytes(d))
+
+
+def sidco_set_workspace(buf) -> None:
+    """buf: a CUDA uint8 tensor the caller keeps alive, or None to return to library allocation."""
+    if buf is None:
+        _check(load().sidco_set_workspace(None, 0), "sidco_set_workspace")
+    else:
+        _check(load().sidco_set_workspace(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size()),
+               "sidco_set_workspace")
+
+
+def sidco_compress(grad, residual, delta: float, dist: int, stages: int, out_idx, out_val, out_count, out_eta,
+                   stream=None) -> None:
+    """Enqueues one sparsifier call; see include/sidco.h.  `residual` may be None."""
+    import torch
+    d = grad.numel()
+    _check_tensor(grad, torch.float32, "grad")
+    if residual is not None:
+        _check_tensor(residual, torch.float32, "residual", d)
+    cap = sidco_out_capacity(d, delta)
+    _check_tensor(out_idx, torch.int32, "out_idx", cap)
+    _check_tensor(out_val, torch.float32, "out_val", cap)
+    _check_tensor(out_count, torch.int32, "out_count", 1)
+    _check_tensor(out_eta, torch.float32, "out_eta", 1)
+    _check(load().sidco_compress(_stream_handle(stream), _ptr(grad), _ptr(residual), d, delta, dist, stages,
+                                 _ptr(out_idx), _ptr(out_val), _ptr(out_count), _ptr(out_eta)), "sidco_compress")
+
+
+def sidco_compress_ex(grad, residual, dist: int, ratios, out_idx, out_val, out_count, out_eta, stream=None) -> None:
+    """Explicit stage ratios; the output capacity is min(len(out_idx), len(out_val))."""
+    import torch
+    d = grad.numel()
+    _check_tensor(grad, torch.float32, "grad")
+    if residual is not None:
+        _check_tensor(residual, torch.float32, "residual", d)
+    _check_tensor(out_idx, torch.int32, "out_idx", 1)
+    _check_tensor(out_val, torch.float32, "out_val", 1)
+    _check_tensor(out_count, torch.int32, "out_count", 1)
+    _check_tensor(out_eta, torch.float32, "out_eta", 1)
+    cap = min(out_idx.numel(), out_val.numel())
+    r = (C.c_double * len(ratios))(*ratios)
+    _check(load().sidco_compress_ex(_stream_handle(stream), _ptr(grad), _ptr(residual), d, dist, r, len(ratios),
+                                    _ptr(out_idx), _ptr(out_val), cap, _ptr(out_count), _ptr(out_eta)),
+           "sidco_compress_ex")
+
+
+def sidco_read_diag(stream=None) -> Diag:
+    diag = Diag()
+    _check(load().sidco_read_diag(_stream_handle(stream), C.byref(diag)), "sidco_read_diag")
+    return diag
+
+
+def sidco_set_profiling(enable: bool) -> None:
+    _check(load().sidco_set_profiling(int(bool(enable))), "sidco_set_profiling")
+
+
+def sidco_get_profile() -> list[tuple[str, float]]:
+    """Per-kernel (name, milliseconds) of the last profiled call on the current device."""
+    ms = (C.c_float * 16)()
+    names = (C.c_char_p * 16)()
+    n = load().sidco_get_profile(ms, names, 16)
+    if n < 0:
+        raise SidcoError(n, "sidco_get_profile")
+    return [(names[i].decode(), float(ms[i])) for i in range(n)]
+
+
+def sidco_version() -> int:
+    return load().sidco_version()
+
+
+def sidco_shutdown() -> None:
+    load().sidco_shutdown()

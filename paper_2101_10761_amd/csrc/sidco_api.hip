@@ -1,0 +1,358 @@
+// C ABI of the SIDCo library: argument checks, stage schedule, workspace, kernel sequencing.
+// Declarations and their contracts are in include/sidco.h.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <mutex>
+
+#include "sidco_internal.h"
+
+namespace sidco {
+namespace {
+
+constexpr int kMaxDevices = 16;
+constexpr int kMaxKernels = SIDCO_MAX_STAGES + 2;
+constexpr size_t kAlign = 256;
+
+// Fixed-size head of the workspace; the two survivor-list buffers follow it.
+struct WorkspaceHead {
+    DevState st;
+    alignas(256) double part[2][4 * kMaxBlocks];
+    alignas(256) uint32_t cnt[2][kMaxWaves];
+    alignas(256) uint32_t blk[2][kMaxBlocks];
+};
+
+constexpr size_t head_bytes() { return (sizeof(WorkspaceHead) + kAlign - 1) / kAlign * kAlign; }
+
+size_t seg_bytes(int64_t d)
+{
+    const size_t ntiles = (size_t)((d + kTile - 1) / kTile);
+    return ntiles * kTile * sizeof(int2);  // one slot per element: no list can overflow
+}
+
+struct DeviceCtx {
+    void* ws = nullptr;        // workspace in use
+    size_t ws_bytes = 0;
+    bool ws_owned = false;
+    hipEvent_t ev[kMaxKernels + 1] = {};
+    bool ev_made = false;
+    int prof_n = 0;            // kernels of the last profiled call
+    const char* prof_name[kMaxKernels] = {};
+};
+
+std::mutex g_mu;
+DeviceCtx g_ctx[kMaxDevices];
+bool g_profiling = false;
+thread_local char g_hip_msg[256] = "";
+
+int hip_fail(hipError_t e, const char* what)
+{
+    snprintf(g_hip_msg, sizeof(g_hip_msg), "%s: %s", what, hipGetErrorString(e));
+    return SIDCO_ERR_HIP;
+}
+
+bool aligned4(const void* p) { return ((uintptr_t)p & 3u) == 0; }
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+int check_common(const float* grad, const float* residual, int64_t d, int dist, const int32_t* out_idx,
+                 const float* out_val, const int32_t* out_count, const float* out_eta)
+{
+    if (!grad || !out_idx || !out_val || !out_count || !out_eta) return SIDCO_ERR_NULL;
+    if (d < 1 || d > (int64_t)INT32_MAX) return SIDCO_ERR_SIZE;
+    if (dist != SIDCO_DIST_EXP && dist != SIDCO_DIST_GAMMA_GPD && dist != SIDCO_DIST_GPD) return SIDCO_ERR_DIST;
+    if (!aligned4(grad) || !aligned4(residual) || !aligned4(out_idx) || !aligned4(out_val) || !aligned4(out_count) ||
+        !aligned4(out_eta))
+        return SIDCO_ERR_ALIGN;
+    if (residual && (const void*)residual == (const void*)grad) return SIDCO_ERR_ARG;
+    return SIDCO_OK;
+}
+
+// Makes sure the current device has a workspace of at least `need` bytes.
+int ensure_workspace(DeviceCtx& c, size_t need)
+{
+    if (c.ws && c.ws_bytes >= need) return SIDCO_OK;
+    if (c.ws && !c.ws_owned) return SIDCO_ERR_WORKSPACE;  // caller-provided and too small
+    if (c.ws) {
+        hipError_t e = hipFree(c.ws);  // waits for work that still uses it
+        c.ws = nullptr;
+        c.ws_bytes = 0;
+        if (e != hipSuccess) return hip_fail(e, "hipFree(workspace)");
+    }
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, need);
+    if (e != hipSuccess) return hip_fail(e, "hipMalloc(workspace)");
+    c.ws = p;
+    c.ws_bytes = need;
+    c.ws_owned = true;
+    return SIDCO_OK;
+}
+
+int run(void* stream, const float* grad, float* residual, int64_t d, int dist, const double* ratios, int M,
+        int32_t* out_idx, float* out_val, int64_t out_cap, int32_t* out_count, float* out_eta)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return SIDCO_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx& c = g_ctx[dev];
+    const size_t seg = seg_bytes(d);
+    int rc = ensure_workspace(c, head_bytes() + 2 * seg);
+    if (rc != SIDCO_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+
+    WorkspaceHead* h = (WorkspaceHead*)c.ws;
+    int2* segbuf[2] = {(int2*)((char*)c.ws + head_bytes()), (int2*)((char*)c.ws + head_bytes() + seg)};
+
+    Params p;
+    memset(&p, 0, sizeof(p));
+    p.grad = grad;
+    p.residual = residual;
+    p.acc = residual ? residual : grad;
+    p.d = d;
+    p.ntiles = (uint32_t)((d + kTile - 1) / kTile);
+    p.nfull = (uint32_t)(d / kTile);
+    p.nwaves = p.ntiles < (uint32_t)kMaxWaves ? p.ntiles : (uint32_t)kMaxWaves;
+    p.nblocks = (p.nwaves + kWavesPerBlock - 1) / kWavesPerBlock;
+    p.vec_ok = aligned16(grad) && aligned16(residual);
+    p.dist = dist;
+    p.M = M;
+    for (int m = 0; m < M; ++m) p.L[m] = log(1.0 / ratios[m]);
+    p.st = &h->st;
+    p.out_idx = out_idx;
+    p.out_val = out_val;
+    p.out_count = out_count;
+    p.out_eta = out_eta;
+    p.out_cap = out_cap;
+
+    const bool prof = g_profiling;
+    if (prof && !c.ev_made) {
+        for (int i = 0; i <= kMaxKernels; ++i) {
+            e = hipEventCreate(&c.ev[i]);
+            if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
+        }
+        c.ev_made = true;
+    }
+    int k = 0;
+    auto mark = [&](const char* name) {
+        if (!prof) return;
+        if (name) c.prof_name[k - 1] = name;
+        (void)hipEventRecord(c.ev[k], s);
+    };
+    mark(nullptr);
+
+    // stage-1 sums (and acc) -> part[0]
+    p.part_out = h->part[0];
+    launch_fit(p, s);
+    ++k;
+    mark("k_fit");
+
+    // stage m: threshold from the previous kernel's sums, survivor lists into segbuf[(m-1)&1]
+    for (int m = 1; m <= M; ++m) {
+        const int in = (m - 1) & 1, out = m & 1;
+        p.stage = m;
+        p.part_in = h->part[in];
+        p.part_out = h->part[out];
+        p.cnt_in = h->cnt[in];
+        p.cnt_out = h->cnt[out];
+        p.blk_in = h->blk[in];
+        p.blk_out = h->blk[out];
+        p.seg_in = segbuf[in];
+        p.seg_out = segbuf[out];
+        launch_compact(p, /*dense=*/m == 1, /*stats=*/m < M, s);
+        ++k;
+        mark(m == 1 ? "k_compact_dense" : "k_compact_lists");
+    }
+    {
+        const int in = M & 1;
+        p.cnt_in = h->cnt[in];
+        p.blk_in = h->blk[in];
+        p.seg_in = segbuf[in];
+        launch_gather(p, s);
+        ++k;
+        mark("k_gather");
+    }
+    c.prof_n = prof ? k : 0;
+    e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    return SIDCO_OK;
+}
+
+}  // namespace
+}  // namespace sidco
+
+using namespace sidco;
+
+extern "C" {
+
+int sidco_stage_ratios(double delta, int stages, double delta1, double* ratios)
+{
+    if (!ratios) return SIDCO_ERR_NULL;
+    if (!(delta > 0.0 && delta < 1.0)) return SIDCO_ERR_DELTA;
+    if (stages < 1 || stages > SIDCO_MAX_STAGES) return SIDCO_ERR_STAGES;
+    if (!(delta1 > 0.0 && delta1 < 1.0)) return SIDCO_ERR_DELTA;
+    if (stages == 1 || !(delta1 > delta)) {
+        ratios[0] = delta;
+        return 1;
+    }
+    ratios[0] = delta1;
+    const double rest = pow(delta / delta1, 1.0 / (double)(stages - 1));
+    for (int m = 1; m < stages; ++m) ratios[m] = rest;
+    return stages;
+}
+
+int64_t sidco_out_capacity(int64_t d, double delta)
+{
+    if (d < 1 || d > (int64_t)INT32_MAX) return SIDCO_ERR_SIZE;
+    if (!(delta > 0.0 && delta < 1.0)) return SIDCO_ERR_DELTA;
+    const int64_t k = (int64_t)ceil(delta * (double)d);
+    const int64_t cap = 4 * k + 4096;
+    return cap < d ? cap : d;
+}
+
+size_t sidco_workspace_bytes(int64_t d)
+{
+    if (d < 1 || d > (int64_t)INT32_MAX) return 0;
+    return head_bytes() + 2 * seg_bytes(d);
+}
+
+int sidco_set_workspace(void* device_ptr, size_t bytes)
+{
+    if (device_ptr && ((uintptr_t)device_ptr % kAlign) != 0) return SIDCO_ERR_WORKSPACE;
+    if (device_ptr && bytes < head_bytes()) return SIDCO_ERR_WORKSPACE;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return SIDCO_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx& c = g_ctx[dev];
+    if (c.ws && c.ws_owned) {
+        e = hipFree(c.ws);
+        if (e != hipSuccess) return hip_fail(e, "hipFree(workspace)");
+    }
+    c.ws = device_ptr;
+    c.ws_bytes = device_ptr ? bytes : 0;
+    c.ws_owned = false;
+    return SIDCO_OK;
+}
+
+int sidco_compress_ex(void* stream, const float* grad, float* residual, int64_t d, int dist, const double* ratios,
+                      int n_ratios, int32_t* out_idx, float* out_val, int64_t out_capacity, int32_t* out_count,
+                      float* out_eta)
+{
+    int rc = check_common(grad, residual, d, dist, out_idx, out_val, out_count, out_eta);
+    if (rc != SIDCO_OK) return rc;
+    if (!ratios) return SIDCO_ERR_NULL;
+    if (n_ratios < 1 || n_ratios > SIDCO_MAX_STAGES) return SIDCO_ERR_STAGES;
+    for (int m = 0; m < n_ratios; ++m)
+        if (!(ratios[m] > 0.0 && ratios[m] < 1.0)) return SIDCO_ERR_DELTA;
+    if (out_capacity < 1 || out_capacity > (int64_t)INT32_MAX) return SIDCO_ERR_SIZE;
+    return run(stream, grad, residual, d, dist, ratios, n_ratios, out_idx, out_val, out_capacity, out_count, out_eta);
+}
+
+int sidco_compress(void* stream, const float* grad, float* residual, int64_t d, double delta, int dist, int stages,
+                   int32_t* out_idx, float* out_val, int32_t* out_count, float* out_eta)
+{
+    int rc = check_common(grad, residual, d, dist, out_idx, out_val, out_count, out_eta);
+    if (rc != SIDCO_OK) return rc;
+    if (!(delta > 0.0 && delta < 1.0)) return SIDCO_ERR_DELTA;
+    if (stages < 1 || stages > SIDCO_MAX_STAGES) return SIDCO_ERR_STAGES;
+    double ratios[SIDCO_MAX_STAGES];
+    const int M = sidco_stage_ratios(delta, stages, 0.25, ratios);
+    if (M < 1) return M;
+    return run(stream, grad, residual, d, dist, ratios, M, out_idx, out_val, sidco_out_capacity(d, delta), out_count,
+               out_eta);
+}
+
+int sidco_read_diag(void* stream, sidco_diag* host_out)
+{
+    if (!host_out) return SIDCO_ERR_NULL;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return SIDCO_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx& c = g_ctx[dev];
+    if (!c.ws) return SIDCO_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    e = hipMemcpyAsync(host_out, &((WorkspaceHead*)c.ws)->st.diag, sizeof(sidco_diag), hipMemcpyDeviceToHost, s);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(diag)");
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    const int M = host_out->stages;
+    for (int m = (M < 0 ? 0 : M); m < SIDCO_MAX_STAGES; ++m) {  // entries of earlier, longer calls
+        host_out->eta[m] = 0.0f;
+        host_out->n[m] = 0;
+        host_out->stats[m][0] = host_out->stats[m][1] = host_out->stats[m][2] = 0.0;
+    }
+    return SIDCO_OK;
+}
+
+int sidco_set_profiling(int enable)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_profiling = enable != 0;
+    return SIDCO_OK;
+}
+
+int sidco_get_profile(float* ms, const char** names, int cap)
+{
+    if (!ms || cap < 1) return SIDCO_ERR_NULL;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return SIDCO_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx& c = g_ctx[dev];
+    if (c.prof_n == 0) return 0;
+    e = hipEventSynchronize(c.ev[c.prof_n]);
+    if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+    for (int i = 0; i < c.prof_n && i < cap; ++i) {
+        e = hipEventElapsedTime(&ms[i], c.ev[i], c.ev[i + 1]);
+        if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+        if (names) names[i] = c.prof_name[i];
+    }
+    return c.prof_n;
+}
+
+const char* sidco_strerror(int code)
+{
+    switch (code) {
+        case SIDCO_OK: return "ok";
+        case SIDCO_ERR_NULL: return "a required pointer is NULL";
+        case SIDCO_ERR_SIZE: return "d or a capacity is out of range (1 .. 2^31-1)";
+        case SIDCO_ERR_DELTA: return "a compression ratio is not in (0,1)";
+        case SIDCO_ERR_STAGES: return "number of stages out of range (1 .. SIDCO_MAX_STAGES)";
+        case SIDCO_ERR_DIST: return "unknown distribution";
+        case SIDCO_ERR_WORKSPACE: return "workspace missing, too small or misaligned";
+        case SIDCO_ERR_HIP: return "HIP runtime error";
+        case SIDCO_ERR_ALIGN: return "pointer not 4-byte aligned";
+        case SIDCO_ERR_ARG: return "invalid argument";
+        default: return "unknown error code";
+    }
+}
+
+const char* sidco_last_hip_error(void) { return g_hip_msg; }
+
+int sidco_version(void) { return 100; }
+
+void sidco_shutdown(void)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    int cur = 0;
+    const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+    for (int dev = 0; dev < kMaxDevices; ++dev) {
+        DeviceCtx& c = g_ctx[dev];
+        if (!c.ws && !c.ev_made) continue;
+        if (hipSetDevice(dev) != hipSuccess) continue;
+        if (c.ws && c.ws_owned) (void)hipFree(c.ws);
+        if (c.ev_made)
+            for (int i = 0; i <= kMaxKernels; ++i) (void)hipEventDestroy(c.ev[i]);
+        c = DeviceCtx();
+    }
+    if (have_cur) (void)hipSetDevice(cur);
+}
+
+}  // extern "C"

@@ -1,0 +1,74 @@
+// Internal declarations shared by the kernels and the C-ABI layer of the SIDCo library.
+#ifndef SIDCO_INTERNAL_H
+#define SIDCO_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sidco.h"
+
+namespace sidco {
+
+constexpr int kBlock = 512;                       // threads per block: 8 wave64
+constexpr int kWavesPerBlock = kBlock / 64;
+constexpr int kTile = 256;                        // elements per wave step: 64 lanes x float4
+constexpr int kMaxBlocks = 512;                   // 2 blocks per CU on 256 CUs
+constexpr int kMaxWaves = kMaxBlocks * kWavesPerBlock;
+static_assert(kMaxBlocks <= kBlock, "one thread per producer block in the prologue reductions");
+
+constexpr int kDistExp = SIDCO_DIST_EXP;
+constexpr int kDistGamma = SIDCO_DIST_GAMMA_GPD;
+constexpr int kDistGpd = SIDCO_DIST_GPD;
+
+constexpr uint32_t kStNonfinite = SIDCO_ST_NONFINITE;
+constexpr uint32_t kStVarZero = SIDCO_ST_VAR_ZERO;
+constexpr uint32_t kStGammaS = SIDCO_ST_GAMMA_S;
+constexpr uint32_t kStGammaClamp = SIDCO_ST_GAMMA_CLAMP;
+constexpr uint32_t kStStopped = SIDCO_ST_STOPPED;
+constexpr uint32_t kStOverflow = SIDCO_ST_OVERFLOW;
+
+// Device-resident state of one call.  Stage m's kernel reads the entries stage m-1 wrote and
+// writes its own, so no entry is read and written inside one kernel.
+struct DevState {
+    sidco_diag diag;
+    uint32_t status_after[SIDCO_MAX_STAGES + 1];  // status bits accumulated up to and including stage m
+    uint32_t frozen_after[SIDCO_MAX_STAGES + 1];  // 1 once an empty exceedance set stopped the refinement
+};
+
+// Kernel arguments (passed by value).
+struct Params {
+    const float* grad;
+    float* residual;        // NULL: memoryless
+    const float* acc;       // dense working vector read by stage 1's compaction: residual, else grad
+    int64_t d;
+    uint32_t ntiles;        // ceil(d / kTile)
+    uint32_t nfull;         // d / kTile: tiles below this index are complete
+    uint32_t nwaves;        // waves that own tiles
+    uint32_t nblocks;       // grid size of every kernel of the call
+    int vec_ok;             // all dense buffers 16-byte aligned: float4 accesses allowed
+    int dist;
+    int M;
+    int stage;              // 1-based stage a k_compact launch works for
+    double L[SIDCO_MAX_STAGES];  // log(1/delta_m)
+    DevState* st;
+    const double* part_in;  // [4][kMaxBlocks] partial sums written by the previous kernel
+    double* part_out;
+    const uint32_t* cnt_in; // [kMaxWaves] survivor-list lengths written by the previous kernel
+    uint32_t* cnt_out;
+    const uint32_t* blk_in; // [kMaxBlocks] per-block sums of cnt
+    uint32_t* blk_out;
+    const int2* seg_in;     // survivor lists (index, value bits); wave w's list starts at tile_begin(w)*kTile
+    int2* seg_out;
+    int32_t* out_idx;
+    float* out_val;
+    int32_t* out_count;
+    float* out_eta;
+    int64_t out_cap;
+};
+
+void launch_fit(const Params& p, hipStream_t s);
+void launch_compact(const Params& p, bool dense, bool stats, hipStream_t s);
+void launch_gather(const Params& p, hipStream_t s);
+
+}  // namespace sidco
+#endif

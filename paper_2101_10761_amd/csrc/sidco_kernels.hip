@@ -1,0 +1,545 @@
+// SIDCo gradient sparsifier for MI355X (gfx950): device kernels and their launchers.
+//
+// Pipeline of one call (arXiv 2101.10761; Algorithm 1 "Sparsify", Sec. 2.3-2.4, App. B.2-B.3):
+//
+//   k_fit        acc = g + residual, stored back to residual; per-block fp64 partial sums of
+//                |acc|, acc^2, log2|acc| (whichever the chosen law needs)       [reads 8 B, writes 4 B / element]
+//   k_compact<m> m = 1..M.  Prologue: every block reduces the previous kernel's partial sums in a
+//                fixed order and evaluates the closed-form threshold eta_m in fp64 (identical bits
+//                in every block).  Body: exceedances {|x| > eta_m} of the source (the dense acc
+//                for m = 1, the previous survivor lists afterwards) are appended to per-wave
+//                survivor lists; for m < M the sums of (|x| - eta_m) and its square are formed for
+//                the next stage's fit.
+//   k_gather     exclusive prefix over the per-block survivor counts, copy of the lists into the
+//                contiguous (index, value) output, zeroing of the residual at those indices.
+//
+// Design rules, from measurement on this chip: same-address atomics serialise at ~11 ns each and a
+// device-scope fence in a write-heavy kernel forces an L2 write-back, so the path has neither.
+// Kernel boundaries are the only global synchronisation; every wave owns a contiguous range of
+// 256-element tiles and a survivor list at the same offset, so list positions need no atomics and
+// the whole result (thresholds, order of output pairs) is deterministic.
+//
+// All floating-point accumulation is fp64 (full rate on CDNA4 vector ALUs); comparisons are fp32
+// against the fp32 threshold, so the decision |x| > eta is the same one an fp32 reference takes.
+#include <hip/hip_runtime.h>
+#include <float.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "sidco_internal.h"
+
+namespace sidco {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------------------------
+// small device helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;  // lane 0 holds the sum
+}
+
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;
+}
+
+// number of set bits of `mask` below this lane
+__device__ __forceinline__ uint32_t lane_prefix(unsigned long long mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// first tile of wave w: tiles are split as evenly as possible over the waves
+__device__ __forceinline__ uint32_t tile_begin(uint32_t w, uint32_t ntiles, uint32_t nwaves)
+{
+    return (uint32_t)(((unsigned long long)w * ntiles) / nwaves);
+}
+
+// Sums of `v[q]` over the block, in a fixed order; every thread returns the same values.
+template <int Q>
+__device__ __forceinline__ void block_sum(double (&v)[Q], double (*sh)[4])
+{
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) v[q] = wave_sum(v[q]);
+    __syncthreads();  // protects sh against a previous use
+    if (lane == 0) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q) sh[wib][q] = v[q];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        double t = 0.0;
+#pragma unroll
+        for (int i = 0; i < kWavesPerBlock; ++i) t += sh[i][q];
+        v[q] = t;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// closed-form thresholds (fp64, evaluated redundantly by every thread of every block)
+// ---------------------------------------------------------------------------------------------
+
+// Moment-matched GPD quantile above the location (eqs. (7)-(9); Corollary 1.3):
+// alpha = (1 - mu^2/var)/2, beta = mu (mu^2/var + 1)/2, increment = (beta/alpha)(exp(-alpha log delta) - 1).
+// L = log(1/delta).  alpha == 0 is the exponential limit.
+__device__ __forceinline__ double gpd_increment(double mu, double var, double L)
+{
+    const double q = (mu * mu) / var;
+    const double a = 0.5 * (1.0 - q);
+    const double b = 0.5 * mu * (q + 1.0);
+    if (a == 0.0) return b * L;
+    return (b / a) * expm1(a * L);
+}
+
+// Stage-1 threshold from the sums over all d entries (Corollary 1 / eq. (6); Corollaries 1.2, 1.3).
+// S2 is only used for the GPD law, SL2 (sum of log2 max(|x|, 2^-126)) only for the gamma law.
+__device__ float stage1_eta(int dist, double S1, double S2, double SL2, double d, double L,
+                            uint32_t& status, double stats[3])
+{
+    const double mu = S1 / d;
+    double var = 0.0, mulog = 0.0;
+    bool finite = isfinite(mu);
+    if (dist == kDistGpd) {
+        var = S2 / d - mu * mu;
+        finite = finite && isfinite(var);
+    } else if (dist == kDistGamma) {
+        mulog = (SL2 / d) * 0.6931471805599453094;  // log2 -> natural log
+        finite = finite && isfinite(mulog);
+    }
+    stats[0] = mu;
+    stats[1] = var;
+    stats[2] = mulog;
+    if (!finite) {
+        status |= kStNonfinite;
+        return __builtin_nanf("");
+    }
+    double t;
+    if (dist == kDistExp) {
+        t = mu * L;  // eq. (6)
+    } else if (dist == kDistGpd) {
+        if (!(var > 0.0)) {  // all magnitudes equal: limit of the closed form as var -> 0+
+            status |= kStVarZero;
+            t = mu;
+        } else {
+            t = gpd_increment(mu, var, L);
+        }
+    } else {
+        // gamma law: closed-form shape from s = log(mean) - mean(log), threshold -beta (log delta + log Gamma(alpha))
+        const double s = log(mu) - mulog;
+        if (!(s > 0.0)) {  // the closed form tends to -infinity here and negative thresholds clamp to 0
+            status |= kStGammaS;
+            t = 0.0;
+        } else {
+            const double a = (3.0 - s + sqrt((s - 3.0) * (s - 3.0) + 24.0 * s)) / (12.0 * s);
+            const double b = mu / a;
+            t = -b * (lgamma(a) - L);
+            if (t < 0.0) {
+                status |= kStGammaClamp;
+                t = 0.0;
+            }
+        }
+    }
+    return (float)t;
+}
+
+// Stage m >= 2 threshold from the sums over the n exceedances of eta_prev
+// (Lemma 2 / eqs. (7)-(9) for the GPD chains, Corollary 2 / eqs. (10)-(11) for the exponential chain).
+__device__ float pot_eta(int dist, unsigned long long n, double Sy, double Syy, float eta_prev, double L,
+                         bool frozen_in, bool& frozen_out, uint32_t& status, double stats[3])
+{
+    stats[0] = stats[1] = stats[2] = 0.0;
+    frozen_out = frozen_in;
+    if (frozen_in) return eta_prev;
+    if (n == 0) {  // nothing exceeds eta_prev: keep it for all later stages
+        frozen_out = true;
+        status |= kStStopped;
+        return eta_prev;
+    }
+    const double ybar = Sy / (double)n;
+    stats[0] = ybar;
+    double t;
+    if (dist == kDistExp) {
+        t = ybar * L;
+    } else {
+        const double yvar = Syy / (double)n - ybar * ybar;
+        stats[1] = yvar;
+        if (!(yvar > 0.0)) {
+            status |= kStVarZero;
+            t = ybar;
+        } else {
+            t = gpd_increment(ybar, yvar, L);
+        }
+    }
+    return (float)((double)eta_prev + t);
+}
+
+// Prologue of every k_compact: reduce the producer's per-block partial sums (fixed order) and
+// evaluate eta for stage p.stage.  Returns the same value in every thread of every block.
+// Block 0 records the stage in the diagnostics.
+__device__ float stage_prologue(const Params& p, double (*sh)[4])
+{
+    const int m = p.stage;  // 1-based
+    const uint32_t t = threadIdx.x;
+    const bool have = t < p.nblocks;
+    uint32_t status = 0;
+    double stats[3];
+    float eta;
+    bool frozen = false;
+    unsigned long long n;
+    if (m == 1) {
+        double v[3];
+        v[0] = have ? p.part_in[0 * kMaxBlocks + t] : 0.0;
+        v[1] = (have && p.dist == kDistGpd) ? p.part_in[1 * kMaxBlocks + t] : 0.0;
+        v[2] = (have && p.dist == kDistGamma) ? p.part_in[2 * kMaxBlocks + t] : 0.0;
+        block_sum<3>(v, sh);
+        n = (unsigned long long)p.d;
+        eta = stage1_eta(p.dist, v[0], v[1], v[2], (double)p.d, p.L[0], status, stats);
+    } else {
+        double v[3];
+        v[0] = have ? p.part_in[0 * kMaxBlocks + t] : 0.0;
+        v[1] = (have && p.dist != kDistExp) ? p.part_in[1 * kMaxBlocks + t] : 0.0;
+        v[2] = have ? (double)p.blk_in[t] : 0.0;  // counts < 2^31: exact in fp64
+        block_sum<3>(v, sh);
+        n = (unsigned long long)v[2];
+        const float eta_prev = p.st->diag.eta[m - 2];
+        status = p.st->status_after[m - 1];
+        const bool frozen_in = p.st->frozen_after[m - 1] != 0;
+        eta = pot_eta(p.dist, n, v[0], v[1], eta_prev, p.L[m - 1], frozen_in, frozen, status, stats);
+    }
+    if (blockIdx.x == 0 && t == 0) {
+        p.st->diag.eta[m - 1] = eta;
+        p.st->diag.n[m - 1] = (int64_t)n;
+        p.st->diag.stats[m - 1][0] = stats[0];
+        p.st->diag.stats[m - 1][1] = stats[1];
+        p.st->diag.stats[m - 1][2] = stats[2];
+        p.st->status_after[m] = status;
+        p.st->frozen_after[m] = frozen ? 1u : 0u;
+    }
+    return eta;
+}
+
+// ---------------------------------------------------------------------------------------------
+// k_fit: error-compensation add (App. B.2) fused with the sums of the stage-1 fit
+// ---------------------------------------------------------------------------------------------
+template <int DIST>
+__device__ __forceinline__ void fit_accum(float x, double& s1, double& s2, double& sl, int& se)
+{
+    const float a = __builtin_fabsf(x);
+    const double da = (double)a;
+    s1 += da;
+    if constexpr (DIST == kDistGpd) s2 = __builtin_fma(da, da, s2);  // a*a is exact in fp64
+    if constexpr (DIST == kDistGamma) {
+        // log2 max(|x|, 2^-126) = exponent + log2(mantissa in [0.5,1)): the exponents are summed
+        // exactly as integers, the hardware log2 only sees [0.5,1) where its error is <= 1 ulp of a
+        // value in [-1,0).  NaN compares false and is replaced by 2^-126 here; s1 carries the NaN.
+        const float c = __builtin_fmaxf(a, FLT_MIN);
+        se += __builtin_amdgcn_frexp_expf(c);
+        sl += (double)__builtin_amdgcn_logf(__builtin_amdgcn_frexp_mantf(c));
+    }
+}
+
+// U complete tiles starting at tile t, float4 accesses
+template <int DIST, bool EC, int U>
+__device__ __forceinline__ void fit_tiles(const f4* __restrict__ g4, f4* __restrict__ r4, uint32_t t, int lane,
+                                          double& s1, double& s2, double& sl, int& se)
+{
+    f4 a[U], b[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const size_t i = (size_t)(t + u) * 64 + lane;
+        // the gradient is read once per call when error compensation re-materialises acc in the
+        // residual: keep it out of the caches' way
+        a[u] = EC ? __builtin_nontemporal_load(g4 + i) : g4[i];
+        if (EC) b[u] = r4[i];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        f4 c = a[u];
+        if (EC) {
+            c = a[u] + b[u];
+            r4[(size_t)(t + u) * 64 + lane] = c;
+        }
+        fit_accum<DIST>(c.x, s1, s2, sl, se);
+        fit_accum<DIST>(c.y, s1, s2, sl, se);
+        fit_accum<DIST>(c.z, s1, s2, sl, se);
+        fit_accum<DIST>(c.w, s1, s2, sl, se);
+    }
+}
+
+template <int DIST, bool EC>
+__global__ __launch_bounds__(kBlock) void k_fit(Params p)
+{
+    __shared__ double sh[kWavesPerBlock][4];
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    const uint32_t w = blockIdx.x * kWavesPerBlock + wib;
+    double s1 = 0.0, s2 = 0.0, sl = 0.0;
+    int se = 0;
+    if (w < p.nwaves) {
+        const uint32_t t0 = tile_begin(w, p.ntiles, p.nwaves), t1 = tile_begin(w + 1, p.ntiles, p.nwaves);
+        const uint32_t tf = t1 < p.nfull ? t1 : p.nfull;  // tiles [t0,tf) are complete
+        uint32_t t = t0;
+        if (p.vec_ok) {
+            const f4* __restrict__ g4 = reinterpret_cast<const f4*>(p.grad);
+            f4* __restrict__ r4 = reinterpret_cast<f4*>(p.residual);
+            for (; t + 4 <= tf; t += 4) fit_tiles<DIST, EC, 4>(g4, r4, t, lane, s1, s2, sl, se);
+            for (; t < tf; ++t) fit_tiles<DIST, EC, 1>(g4, r4, t, lane, s1, s2, sl, se);
+        }
+        // unaligned buffers and the ragged last tile: guarded scalar accesses
+        for (; t < t1; ++t) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int64_t i = (int64_t)t * kTile + lane * 4 + j;
+                if (i < p.d) {
+                    float c = p.grad[i];
+                    if (EC) {
+                        c = c + p.residual[i];
+                        p.residual[i] = c;
+                    }
+                    fit_accum<DIST>(c, s1, s2, sl, se);
+                }
+            }
+        }
+    }
+    double v[3] = {s1, s2, sl + (double)se};
+    v[0] = wave_sum(v[0]);
+    v[1] = wave_sum(v[1]);
+    v[2] = wave_sum(v[2]);
+    if (lane == 0) {
+        sh[wib][0] = v[0];
+        sh[wib][1] = v[1];
+        sh[wib][2] = v[2];
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        double tot = 0.0;
+#pragma unroll
+        for (int i = 0; i < kWavesPerBlock; ++i) tot += sh[i][threadIdx.x];
+        p.part_out[threadIdx.x * kMaxBlocks + blockIdx.x] = tot;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        p.st->status_after[0] = 0;
+        p.st->frozen_after[0] = 0;
+        p.st->diag.stages = p.M;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// k_compact: exceedances of eta_m appended to per-wave survivor lists (+ sums for stage m+1)
+// ---------------------------------------------------------------------------------------------
+
+// One component of a tile (64 candidates, one per lane).  `run` is the wave's list length so far.
+template <bool STATS>
+__device__ __forceinline__ void emit(bool valid, float x, int32_t idx, float eta, int2* __restrict__ list,
+                                     uint32_t& run, double& sy, double& syy)
+{
+    const float a = __builtin_fabsf(x);
+    const bool sel = valid && (a > eta);  // strict, fp32; NaN on either side is false
+    const unsigned long long mask = __ballot(sel);
+    if (sel) {
+        list[run + lane_prefix(mask)] = make_int2(idx, __float_as_int(x));
+        if (STATS) {
+            const double y = (double)a - (double)eta;
+            sy += y;
+            syy = __builtin_fma(y, y, syy);
+        }
+    }
+    run += (uint32_t)__popcll(mask);
+}
+
+// U complete tiles of the dense vector starting at tile t, float4 loads
+template <bool STATS, int U>
+__device__ __forceinline__ void compact_tiles(const f4* __restrict__ x4, uint32_t t, int lane, float eta,
+                                              int2* __restrict__ list, uint32_t& run, double& sy, double& syy)
+{
+    f4 a[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) a[u] = x4[(size_t)(t + u) * 64 + lane];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int32_t i0 = (int32_t)((t + u) * kTile + lane * 4);
+        emit<STATS>(true, a[u].x, i0 + 0, eta, list, run, sy, syy);
+        emit<STATS>(true, a[u].y, i0 + 1, eta, list, run, sy, syy);
+        emit<STATS>(true, a[u].z, i0 + 2, eta, list, run, sy, syy);
+        emit<STATS>(true, a[u].w, i0 + 3, eta, list, run, sy, syy);
+    }
+}
+
+template <bool DENSE, bool STATS>
+__global__ __launch_bounds__(kBlock) void k_compact(Params p)
+{
+    __shared__ double sh[kWavesPerBlock][4];
+    __shared__ uint32_t sh_cnt[kWavesPerBlock];
+    const float eta = stage_prologue(p, sh);
+
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    const uint32_t w = blockIdx.x * kWavesPerBlock + wib;
+    uint32_t run = 0;
+    double sy = 0.0, syy = 0.0;
+    if (w < p.nwaves) {
+        const uint32_t t0 = tile_begin(w, p.ntiles, p.nwaves), t1 = tile_begin(w + 1, p.ntiles, p.nwaves);
+        int2* __restrict__ list = p.seg_out + (size_t)t0 * kTile;  // room for every element of the wave's tiles
+        if (DENSE) {
+            const float* __restrict__ x = p.acc;
+            const uint32_t tf = t1 < p.nfull ? t1 : p.nfull;
+            uint32_t t = t0;
+            if (p.vec_ok) {
+                const f4* __restrict__ x4 = reinterpret_cast<const f4*>(x);
+                for (; t + 4 <= tf; t += 4) compact_tiles<STATS, 4>(x4, t, lane, eta, list, run, sy, syy);
+                for (; t < tf; ++t) compact_tiles<STATS, 1>(x4, t, lane, eta, list, run, sy, syy);
+            }
+            for (; t < t1; ++t) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int64_t i = (int64_t)t * kTile + lane * 4 + j;
+                    const bool valid = i < p.d;
+                    const float v = valid ? x[i] : 0.0f;
+                    emit<STATS>(valid, v, (int32_t)i, eta, list, run, sy, syy);
+                }
+            }
+        } else {
+            const int2* __restrict__ src = p.seg_in + (size_t)t0 * kTile;
+            const uint32_t n_in = __builtin_amdgcn_readfirstlane(p.cnt_in[w]);
+            constexpr int U = 4;
+            for (uint32_t c = 0; c < n_in; c += 64 * U) {
+                int2 q[U];
+                bool ok[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t i = c + u * 64 + lane;
+                    ok[u] = i < n_in;
+                    q[u] = ok[u] ? src[i] : make_int2(0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) emit<STATS>(ok[u], __int_as_float(q[u].y), q[u].x, eta, list, run, sy, syy);
+            }
+        }
+        if (lane == 0) p.cnt_out[w] = run;
+    }
+    if (lane == 0) sh_cnt[wib] = run;
+    if (STATS) {
+        sy = wave_sum(sy);
+        syy = wave_sum(syy);
+        __syncthreads();  // the prologue's reads of sh are done
+        if (lane == 0) {
+            sh[wib][0] = sy;
+            sh[wib][1] = syy;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t tot = 0;
+#pragma unroll
+        for (int i = 0; i < kWavesPerBlock; ++i) tot += sh_cnt[i];
+        p.blk_out[blockIdx.x] = tot;
+    }
+    if (STATS && threadIdx.x < 2) {
+        double tot = 0.0;
+#pragma unroll
+        for (int i = 0; i < kWavesPerBlock; ++i) tot += sh[i][threadIdx.x];
+        p.part_out[threadIdx.x * kMaxBlocks + blockIdx.x] = tot;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// k_gather: survivor lists of the last stage -> contiguous (index, value) output; residual update
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_gather(Params p)
+{
+    __shared__ unsigned long long sh_u[kWavesPerBlock][2];
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    const uint32_t t = threadIdx.x;
+    // exclusive prefix of the per-block counts at this block, and their total
+    const unsigned long long c = t < p.nblocks ? (unsigned long long)p.blk_in[t] : 0ull;
+    unsigned long long below = wave_sum_u64(t < blockIdx.x ? c : 0ull);
+    unsigned long long total = wave_sum_u64(c);
+    if (lane == 0) {
+        sh_u[wib][0] = below;
+        sh_u[wib][1] = total;
+    }
+    __syncthreads();
+    below = 0;
+    total = 0;
+#pragma unroll
+    for (int i = 0; i < kWavesPerBlock; ++i) {
+        below += sh_u[i][0];
+        total += sh_u[i][1];
+    }
+    const unsigned long long cap = (unsigned long long)p.out_cap;
+    if (blockIdx.x == 0 && t == 0) {
+        const float eta = p.st->diag.eta[p.M - 1];
+        uint32_t status = p.st->status_after[p.M];
+        if (total > cap) status |= kStOverflow;
+        const int32_t written = (int32_t)(total > cap ? cap : total);
+        *p.out_count = written;
+        *p.out_eta = eta;
+        p.st->diag.selected = (int64_t)total;
+        p.st->diag.count = written;
+        p.st->diag.status = status;
+    }
+    const uint32_t w = blockIdx.x * kWavesPerBlock + wib;
+    if (w >= p.nwaves) return;
+    // offset of this wave inside the block: counts of the block's earlier waves
+    const uint32_t w0 = blockIdx.x * kWavesPerBlock;
+    uint32_t mine = (lane < wib && w0 + lane < p.nwaves) ? p.cnt_in[w0 + lane] : 0u;
+#pragma unroll
+    for (int o = 4; o > 0; o >>= 1) mine += __shfl_down(mine, o, 64);  // lanes 0..7 only carry data
+    const unsigned long long base = below + __builtin_amdgcn_readfirstlane(mine);
+    const uint32_t n_in = __builtin_amdgcn_readfirstlane(p.cnt_in[w]);
+    const int2* __restrict__ src = p.seg_in + (size_t)tile_begin(w, p.ntiles, p.nwaves) * kTile;
+    for (uint32_t i = lane; i < n_in; i += 64) {
+        const unsigned long long pos = base + i;
+        if (pos < cap) {  // pairs beyond the capacity stay in the residual
+            const int2 q = src[i];
+            p.out_idx[pos] = q.x;
+            p.out_val[pos] = __int_as_float(q.y);
+            if (p.residual) p.residual[q.x] = 0.0f;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------------------------
+template <bool EC>
+static void launch_fit_ec(const Params& p, hipStream_t s)
+{
+    const dim3 grid(p.nblocks), block(kBlock);
+    switch (p.dist) {
+        case kDistExp: hipLaunchKernelGGL((k_fit<kDistExp, EC>), grid, block, 0, s, p); break;
+        case kDistGamma: hipLaunchKernelGGL((k_fit<kDistGamma, EC>), grid, block, 0, s, p); break;
+        default: hipLaunchKernelGGL((k_fit<kDistGpd, EC>), grid, block, 0, s, p); break;
+    }
+}
+
+void launch_fit(const Params& p, hipStream_t s)
+{
+    if (p.residual) launch_fit_ec<true>(p, s);
+    else launch_fit_ec<false>(p, s);
+}
+
+void launch_compact(const Params& p, bool dense, bool stats, hipStream_t s)
+{
+    const dim3 grid(p.nblocks), block(kBlock);
+    if (dense) {
+        if (stats) hipLaunchKernelGGL((k_compact<true, true>), grid, block, 0, s, p);
+        else hipLaunchKernelGGL((k_compact<true, false>), grid, block, 0, s, p);
+    } else {
+        if (stats) hipLaunchKernelGGL((k_compact<false, true>), grid, block, 0, s, p);
+        else hipLaunchKernelGGL((k_compact<false, false>), grid, block, 0, s, p);
+    }
+}
+
+void launch_gather(const Params& p, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_gather, dim3(p.nblocks), dim3(kBlock), 0, s, p);
+}
+
+}  // namespace sidco

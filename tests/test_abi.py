@@ -1,0 +1,112 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports what the header declares,
+rejects bad arguments before touching HIP, and its host helpers agree with the oracle's schedule."""
+import ctypes as C
+import math
+import os
+import re
+import subprocess
+
+import pytest
+
+import paper_2101_10761_amd as sidco
+from paper_2101_10761_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "sidco.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2101_10761_amd import build
+        build.build()
+    return sidco.load()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sidco_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert "sidco_compress" in names and len(names) >= 10
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/sidco.h but not exported"
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_diag_struct_layout_matches_header(tmp_path):
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "sidco.h"\n'
+                   'int main(void){printf("%zu %zu %zu %zu %zu %zu %zu\\n", sizeof(sidco_diag),'
+                   'offsetof(sidco_diag,n), offsetof(sidco_diag,stats), offsetof(sidco_diag,selected),'
+                   'offsetof(sidco_diag,count), offsetof(sidco_diag,stages), offsetof(sidco_diag,status));return 0;}\n')
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)], check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    D = binding.Diag
+    assert got == [C.sizeof(D), D.n.offset, D.stats.offset, D.selected.offset, D.count.offset, D.stages.offset,
+                   D.status.offset]
+
+
+def test_argument_errors_are_caught_on_the_host(lib):
+    ok = C.c_void_p(256)   # never dereferenced: every call below must fail before any HIP call
+    f = lib.sidco_compress
+    base = dict(stream=None, grad=ok, residual=None, d=1000, delta=0.01, dist=0, stages=2,
+                out_idx=ok, out_val=ok, out_count=ok, out_eta=ok)
+
+    def call(**kw):
+        a = dict(base, **kw)
+        return f(a["stream"], a["grad"], a["residual"], a["d"], a["delta"], a["dist"], a["stages"],
+                 a["out_idx"], a["out_val"], a["out_count"], a["out_eta"])
+
+    assert call(grad=None) == -1
+    assert call(out_idx=None) == -1 and call(out_val=None) == -1
+    assert call(out_count=None) == -1 and call(out_eta=None) == -1
+    assert call(d=0) == -2 and call(d=-5) == -2 and call(d=2 ** 31) == -2
+    for bad in (0.0, 1.0, -0.1, 1.5, math.nan):
+        assert call(delta=bad) == -3
+    assert call(stages=0) == -4 and call(stages=9) == -4
+    assert call(dist=3) == -5 and call(dist=-1) == -5
+    assert call(grad=C.c_void_p(258)) == -8 and call(residual=C.c_void_p(1026)) == -8
+    assert call(residual=ok) == -9          # residual aliases grad
+    g = lib.sidco_compress_ex
+    r2 = (C.c_double * 2)(0.25, 0.04)
+    assert g(None, ok, None, 1000, 0, None, 2, ok, ok, 100, ok, ok) == -1
+    assert g(None, ok, None, 1000, 0, r2, 0, ok, ok, 100, ok, ok) == -4
+    assert g(None, ok, None, 1000, 0, r2, 9, ok, ok, 100, ok, ok) == -4
+    assert g(None, ok, None, 1000, 0, r2, 2, ok, ok, 0, ok, ok) == -2
+    assert g(None, ok, None, 1000, 0, (C.c_double * 2)(0.25, 1.0), 2, ok, ok, 100, ok, ok) == -3
+    assert lib.sidco_set_workspace(C.c_void_p(100), 1 << 20) == -6      # misaligned
+    assert lib.sidco_set_workspace(C.c_void_p(256), 16) == -6           # too small
+    assert lib.sidco_read_diag(None, None) == -1
+    for code in range(-9, 1):
+        assert lib.sidco_strerror(code)
+    assert lib.sidco_version() >= 100
+
+
+def test_host_helpers(lib, oracle):
+    for delta, stages, d1 in ((0.001, 3, 0.25), (0.001, 2, 0.05), (0.1, 3, 0.25), (0.3, 4, 0.25), (1e-4, 8, 0.25),
+                              (0.01, 1, 0.25)):
+        assert sidco.sidco_stage_ratios(delta, stages, d1) == pytest.approx(oracle.schedule(delta, stages, d1),
+                                                                           rel=1e-15)
+    with pytest.raises(sidco.SidcoError):
+        sidco.sidco_stage_ratios(0.0, 2)
+    with pytest.raises(sidco.SidcoError):
+        sidco.sidco_stage_ratios(0.01, 0)
+    assert sidco.sidco_out_capacity(25_557_032, 0.001) == 4 * 25_558 + 4096
+    assert sidco.sidco_out_capacity(1000, 0.5) == 1000
+    with pytest.raises(sidco.SidcoError):
+        sidco.sidco_out_capacity(0, 0.5)
+    assert sidco.sidco_workspace_bytes(0) == 0
+    w = sidco.sidco_workspace_bytes(25_557_032)
+    assert w % 256 == 0 and w >= 2 * 8 * 25_557_032
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libsidco.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.load()

@@ -1,0 +1,249 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs."""
+import math
+
+import numpy as np
+import pytest
+
+from gpu_harness import check_parity, run_gpu
+from paper_2101_10761_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+DISTS = [0, 1, 2]
+
+
+def _inputs(d, seed, scale=1e-3, heavy=False):
+    rng = np.random.default_rng(seed)
+    if heavy:
+        g = (rng.standard_t(3.0, size=d) * scale).astype(np.float32)
+    else:
+        g = rng.laplace(0, scale, size=d).astype(np.float32)
+    r = rng.laplace(0, 0.3 * scale, size=d).astype(np.float32)
+    return g, r
+
+
+# sizes: below one tile, exact tiles, ragged tails, several tiles per wave, more tiles than waves
+SIZES = [1, 2, 63, 255, 256, 257, 1000, 4099, 70_001, 269_722, 1_048_576, 2_100_003]
+
+
+@pytest.mark.parametrize("d", SIZES)
+@pytest.mark.parametrize("dist", DISTS)
+def test_small_sizes_all_laws(oracle, d, dist):
+    g, r = _inputs(d, 100 + d % 97 + dist, heavy=(dist == 2))
+    for stages, delta in ((1, 0.05), (3, 0.01)):
+        ratios = oracle.schedule(delta, stages, 0.25)
+        for res_in in (r, None):
+            out = run_gpu(g, res_in, dist, ratios)
+            check_parity(oracle, g, res_in, dist, ratios, out, label=f"d={d} dist={dist} M={stages} ec={res_in is not None}")
+
+
+@pytest.mark.parametrize("goff,roff", [(1, 0), (0, 3), (1, 1), (2, 3)])
+def test_unaligned_slices(oracle, goff, roff):
+    """Per-tensor slices of a flat buffer start at any 4-byte boundary."""
+    d = 300_007
+    g, r = _inputs(d, 7)
+    ratios = oracle.schedule(0.001, 2, 0.05)
+    out = run_gpu(g, r, 0, ratios, grad_offset=goff, res_offset=roff)
+    check_parity(oracle, g, r, 0, ratios, out, label=f"offsets {goff},{roff}")
+    out = run_gpu(g, None, 2, ratios, grad_offset=goff)
+    check_parity(oracle, g, None, 2, ratios, out, label=f"offset {goff} no-ec")
+
+
+def test_config1_and_count_band(oracle):
+    w = workloads.config1()
+    out = run_gpu(w.grad, w.residual, w.dist, None, use_default_schedule=(w.delta, w.stages))
+    ratios = oracle.schedule(w.delta, w.stages, 0.25)
+    check_parity(oracle, w.grad, w.residual, w.dist, ratios, out, label="config1")
+    k, sigma = w.delta * w.d, math.sqrt(w.d * w.delta * (1 - w.delta))
+    assert abs(out.count - k) <= 4 * sigma
+    assert out.eta == pytest.approx(1e-3 * math.log(100), rel=4 / math.sqrt(w.d))
+
+
+@pytest.mark.parametrize("clustered", [False, True])
+def test_config2_full_size(oracle, clustered):
+    w = workloads.config2(clustered=clustered)
+    ratios = oracle.schedule(w.delta, w.stages, w.delta1)
+    out = run_gpu(w.grad, w.residual, w.dist, ratios, cap=w.d // 50)
+    check_parity(oracle, w.grad, w.residual, w.dist, ratios, out, label=w.name)
+
+
+def test_config3_full_size_default_schedule(oracle):
+    """The benchmark's headline configuration, through sidco_compress exactly as bench.py calls it."""
+    w = workloads.config3()
+    out = run_gpu(w.grad, w.residual, w.dist, None, use_default_schedule=(w.delta, w.stages))
+    ratios = oracle.schedule(w.delta, w.stages, 0.25)
+    check_parity(oracle, w.grad, w.residual, w.dist, ratios, out, label="config3")
+    assert 0.5 < out.count / (w.delta * w.d) < 1.5
+
+
+def test_config4_whole_vector_and_per_tensor(oracle):
+    w = workloads.config4(d=6_600_000, ragged=True)   # a tenth of the full length, 50 ragged unaligned tensors
+    ratios = oracle.schedule(w.delta, w.stages, 0.25)
+    out = run_gpu(w.grad, w.residual, w.dist, ratios)
+    check_parity(oracle, w.grad, w.residual, w.dist, ratios, out, label="config4 whole")
+    offs = w.tensor_offsets
+    for t in (0, 7, 49):
+        g = np.ascontiguousarray(w.grad[offs[t]:offs[t + 1]])
+        out = run_gpu(g, np.zeros_like(g), w.dist, ratios, grad_offset=int(offs[t] % 4), res_offset=int(offs[t] % 4))
+        check_parity(oracle, g, np.zeros_like(g), w.dist, ratios, out, label=f"config4 tensor {t}")
+
+
+@pytest.mark.parametrize("delta", [0.1, 0.001])
+def test_config5_iterated_with_carried_residual(oracle, delta):
+    d = 13_835_754   # a tenth of the full length; the full length runs in test_config5_full_size
+    r = np.zeros(d, np.float32)
+    ratios = oracle.schedule(delta, 3, 0.25)
+    for it in range(3):
+        g = workloads.config5_grad(it, d)
+        out = run_gpu(g, r, 0, ratios, cap=workloads_cap(d, delta))
+        check_parity(oracle, g, r, 0, ratios, out, label=f"config5 it={it} delta={delta}")
+        assert abs(out.count / (delta * d) - 1) < 0.2     # eq. (12) with the paper's 20 % tolerance
+        r = out.residual
+
+
+def workloads_cap(d, delta):
+    import paper_2101_10761_amd as sidco
+    return sidco.sidco_out_capacity(d, delta)
+
+
+def test_config4_and_config5_full_size(oracle):
+    """Largest configurations at full length, one call each, compared element by element."""
+    w = workloads.config5(delta=0.01)
+    out = run_gpu(w.grad, w.residual, w.dist, None, use_default_schedule=(w.delta, w.stages))
+    check_parity(oracle, w.grad, w.residual, w.dist, oracle.schedule(w.delta, w.stages, 0.25), out, label="config5 full")
+    del w, out
+    w = workloads.config4()
+    out = run_gpu(w.grad, w.residual, w.dist, None, use_default_schedule=(w.delta, w.stages))
+    check_parity(oracle, w.grad, w.residual, w.dist, oracle.schedule(w.delta, w.stages, 0.25), out, label="config4 full")
+
+
+# ----------------------------------------------------------------------------------------------
+# edge and degenerate cases
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dist", DISTS)
+@pytest.mark.parametrize("stages", [1, 3])
+def test_all_zero(oracle, dist, stages):
+    g = np.zeros(5000, np.float32)
+    ratios = oracle.schedule(0.01, stages, 0.25)
+    out = run_gpu(g, g.copy(), dist, ratios)
+    check_parity(oracle, g, g.copy(), dist, ratios, out, label="zeros")
+    assert out.count == 0 and out.eta == 0.0
+
+
+@pytest.mark.parametrize("dist", DISTS)
+def test_constant_magnitude(oracle, dist):
+    for c, n in ((0.25, 4096), (0.1, 77_777)):
+        g = np.full(n, c, np.float32)
+        g[::2] *= -1
+        out = run_gpu(g, None, dist, [0.05])
+        check_parity(oracle, g, None, dist, [0.05], out, label=f"const {c}")
+        assert out.count == {0: 0, 1: n, 2: 0}[dist]
+
+
+@pytest.mark.parametrize("dist", DISTS)
+@pytest.mark.parametrize("bad", [np.nan, np.inf, -np.inf])
+def test_nonfinite_input(oracle, dist, bad):
+    g, r = _inputs(10_000, 5)
+    g[1234] = bad
+    ratios = oracle.schedule(0.01, 2, 0.25)
+    out = run_gpu(g, r, dist, ratios)
+    check_parity(oracle, g, r, dist, ratios, out, label=f"nonfinite {bad}")
+    assert out.count == 0 and math.isnan(out.eta) and out.status & 1
+
+
+def test_planted_tie_on_the_threshold(oracle):
+    """n entries of magnitude a and m entries b with b = L (n a + m b)/(n + m): the exponential threshold
+    lands exactly on b, and the strict comparison must leave all of them out."""
+    n, m, a, delta = 1000, 10, 1.0, 0.5
+    L = math.log(1 / delta)
+    b = np.float32(L * n * a / (n + m - L * m))
+    g = np.concatenate([np.full(n, a, np.float32), np.full(m, b, np.float32)])
+    g[::3] *= -1
+    ref = oracle.compress(g, ratios=[delta], dist=0)
+    assert np.float32(ref.eta) == b, "construction must put the threshold on b"
+    out = run_gpu(g, g * 0, 0, [delta])
+    check_parity(oracle, g, g * 0, 0, [delta], out, label="tie")
+    assert np.float32(out.eta) == b
+    assert out.count == n            # the a's (a > b) are kept, the b's (== eta) are not
+    g2 = g.copy()
+    g2[n] = np.nextafter(b, np.float32(2))   # one entry an ulp above the others: parity must still hold
+    out2 = run_gpu(g2, None, 0, [delta])
+    check_parity(oracle, g2, None, 0, [delta], out2, label="tie+1ulp")
+
+
+def test_gamma_clamp_flag(oracle):
+    """delta_1 * Gamma(alpha) >= 1 (shape ~ 0.2, delta_1 = 0.25): the closed form is clearly negative."""
+    rng = np.random.default_rng(11)
+    g = rng.gamma(0.2, 1e-3, size=200_000).astype(np.float32)
+    out = run_gpu(g, None, 1, [0.25, 0.1])
+    check_parity(oracle, g, None, 1, [0.25, 0.1], out, label="gamma clamp")
+    assert out.status & 8 and out.etas[0] == 0.0
+
+
+def test_refinement_stops(oracle):
+    g = np.full(100_000, 1e-3, np.float32)
+    g[5] = 10.0
+    ratios = oracle.schedule(0.001, 3, 0.25)
+    for dist in DISTS:
+        out = run_gpu(g, None, dist, ratios)
+        check_parity(oracle, g, None, dist, ratios, out, label=f"stop dist={dist}")
+
+
+def test_output_overflow_is_safe(oracle):
+    g, r = _inputs(500_000, 11)
+    ratios = oracle.schedule(0.01, 2, 0.25)
+    for cap in (1, 100, 4999):
+        out = run_gpu(g, r, 0, ratios, cap=cap)
+        check_parity(oracle, g, r, 0, ratios, out, capacity=cap, label=f"overflow cap={cap}")
+
+
+def test_deterministic_and_workspace_reuse(oracle):
+    """Same input twice -> same bits in the same order, also after a larger and a smaller call in between
+    (the workspace keeps stale lists), and with a caller-provided workspace."""
+    import torch
+    import paper_2101_10761_amd as sidco
+    g, r = _inputs(1_500_000, 21, heavy=True)
+    ratios = oracle.schedule(0.001, 3, 0.25)
+    a = run_gpu(g, r, 2, ratios)
+    big, rb = _inputs(3_000_000, 22)
+    run_gpu(big, rb, 0, oracle.schedule(0.1, 2, 0.25))
+    small, rs = _inputs(999, 23)
+    run_gpu(small, rs, 1, [0.05])
+    b = run_gpu(g, r, 2, ratios)
+    np.testing.assert_array_equal(a.idx, b.idx)
+    np.testing.assert_array_equal(a.val.view(np.uint32), b.val.view(np.uint32))
+    assert a.etas.tobytes() == b.etas.tobytes()
+    check_parity(oracle, g, r, 2, ratios, b, label="reuse")
+    ws = torch.empty(sidco.sidco_workspace_bytes(g.size), dtype=torch.uint8, device="cuda:0")
+    assert ws.data_ptr() % 256 == 0
+    sidco.sidco_set_workspace(ws)
+    try:
+        c = run_gpu(g, r, 2, ratios)
+        np.testing.assert_array_equal(a.idx, c.idx)
+        with pytest.raises(sidco.SidcoError) as e:
+            run_gpu(big, rb, 0, ratios)   # needs more than the provided workspace
+        assert e.value.code == -6
+    finally:
+        sidco.sidco_set_workspace(None)
+    d2 = run_gpu(g, r, 2, ratios)
+    np.testing.assert_array_equal(a.idx, d2.idx)
+
+
+def test_eight_stages(oracle):
+    g, r = _inputs(2_000_000, 31)
+    ratios = oracle.schedule(1e-4, 8, 0.25)
+    out = run_gpu(g, r, 0, ratios)
+    check_parity(oracle, g, r, 0, ratios, out, label="M=8")
+
+
+def test_profile_hooks():
+    import paper_2101_10761_amd as sidco
+    g, r = _inputs(1_000_000, 41)
+    sidco.sidco_set_profiling(True)
+    try:
+        run_gpu(g, r, 0, [0.25, 0.04])
+        prof = sidco.sidco_get_profile()
+    finally:
+        sidco.sidco_set_profiling(False)
+    assert [n for n, _ in prof] == ["k_fit", "k_compact_dense", "k_compact_lists", "k_gather"]
+    assert all(0 < ms < 50 for _, ms in prof)
