@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the SIDCo sparsifier on one MI355X.
+
+A step is one pass of the whole hot path (error-compensation add, stage-1 fit, threshold refinement,
+final compaction and residual update = one sidco_compress call) over one synthetic gradient that is
+already resident in HBM.  The default workload is the configuration the headline metric is quoted on:
+d = 25,557,032 fp32, Student-t(3) values, delta = 0.001, three generalized-Pareto stages, error feedback.
+
+Several distinct gradient buffers (more than the 256 MB of memory-side cache) are used in rotation, so
+every step reads its gradient from HBM, and the residual is carried from step to step as in training.
+
+Prints ONE JSON line on stdout; everything else goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X published HBM3E peak
+ROTATE_BYTES = 768 << 20     # distinct gradient data kept in rotation (> memory-side cache)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def make_workload(name: str):
+    from paper_2101_10761_amd import workloads
+    table = {
+        "cfg1": workloads.config1, "cfg2": workloads.config2, "cfg3": workloads.config3,
+        "cfg4": workloads.config4, "cfg5": workloads.config5,
+    }
+    return table[name]()
+
+
+def algorithmic_bytes(d, ec, n_stage, khat):
+    """Bytes the method itself must move: gradient (+ residual read and acc write), the second pass over
+    acc, every intermediate survivor list written once and read once (8 B pairs), output pairs and
+    residual zero-stores."""
+    b = 4 * d * (3 if ec else 1) + 4 * d
+    b += sum(16 * int(n) for n in n_stage[1:])
+    b += 12 * khat
+    return b
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--profile-steps", type=int, default=50, help="steps timed kernel by kernel with HIP events")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline leg")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (the sparsifier is local to a worker: no collectives, "
+            "no sharding); --gpus must be 1")
+        sys.exit(2)
+
+    import torch
+    import paper_2101_10761_amd as sidco
+
+    sidco.load()  # fails loudly when the HIP library has not been built
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t0 = time.time()
+    w = make_workload(args.workload)
+    d = w.d
+    log(f"workload {w.name}: d={d} delta={w.delta} dist={w.dist} stages={w.stages} delta1={w.delta1} "
+        f"(generated in {time.time() - t0:.1f}s)")
+    ratios = sidco.sidco_stage_ratios(w.delta, w.stages, w.delta1)
+    g0 = torch.from_numpy(w.grad).to(dev)
+    nbuf = max(2, min(16, ROTATE_BYTES // (4 * d) + 1))
+    # further gradients of the same distribution: rolled, sign-flipped copies of the seeded one
+    grads = [g0] + [torch.roll(g0, 7919 * (i + 1) + 1) * (-1.0 if i % 2 else 1.0) for i in range(nbuf - 1)]
+    ec = w.residual is not None
+    residual = torch.from_numpy(w.residual).to(dev) if ec else None
+    cap = max(sidco.sidco_out_capacity(d, w.delta), 1)
+    out_idx = torch.empty(cap, dtype=torch.int32, device=dev)
+    out_val = torch.empty(cap, dtype=torch.float32, device=dev)
+    out_count = torch.zeros(1, dtype=torch.int32, device=dev)
+    out_eta = torch.zeros(1, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        sidco.sidco_compress_ex(grads[i % nbuf], residual, w.dist, ratios, out_idx, out_val, out_count, out_eta,
+                                stream=stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    ms_per_step = (t_end - t_start) * 1e3 / args.steps
+    value = d / (ms_per_step * 1e-3) / 1e9
+    log(f"timed {args.steps} steps: {ms_per_step * 1e3:.1f} us/step -> {value:.1f} G elem/s")
+
+    # kernel-by-kernel timing with HIP events on the same stream
+    sidco.sidco_set_profiling(True)
+    per_kernel: dict[str, list[float]] = {}
+    order: list[str] = []
+    n_stage = None
+    khat = []
+    for i in range(args.profile_steps):
+        step(args.warmup + args.steps + i)
+        prof = sidco.sidco_get_profile()
+        seen: dict[str, int] = {}
+        for name, ms in prof:
+            seen[name] = seen.get(name, 0) + 1
+            key = name if seen[name] == 1 else f"{name}#{seen[name]}"
+            if key not in per_kernel:
+                per_kernel[key] = []
+                order.append(key)
+            per_kernel[key].append(ms)
+        diag = sidco.sidco_read_diag(stream)
+        n_stage = [diag.n[m] for m in range(diag.stages)]
+        khat.append(diag.count)
+    sidco.sidco_set_profiling(False)
+    kern_us = {k: float(np.mean(v)) * 1e3 for k, v in per_kernel.items()}
+    log("per-kernel average (HIP events): " + ", ".join(f"{k} {kern_us[k]:.1f} us" for k in order))
+    log(f"last step: n per stage {n_stage}, khat {khat[-1]} (target {w.delta * d:.0f})")
+
+    fit_bytes = (12 if ec else 4) * d
+    fit_us = kern_us["k_fit"]
+    achieved = fit_bytes / (fit_us * 1e-6) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload, {}).get("k_fit")
+        except Exception:
+            traffic = None
+    roofline = {
+        "kernel": "k_fit", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+        "bytes_per_elem": 12 if ec else 4, "elems_per_launch": d, "avg_launch_us": round(fit_us, 2),
+    }
+    path_bytes = algorithmic_bytes(d, ec, n_stage, int(np.mean(khat)))
+    path = {
+        "algorithmic_bytes": path_bytes, "bytes_per_elem": round(path_bytes / d, 2),
+        "achieved": round(path_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
+        "frac": round(path_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "kernels_us": {k: round(kern_us[k], 2) for k in order},
+    }
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        oratios = oracle.schedule(w.delta, w.stages, w.delta1)
+        # bounded sample: the first `ns` elements of the same vector, repeated until the time budget is used
+        ns = min(d, 26_000_000)
+        gs = np.ascontiguousarray(w.grad[:ns])
+        rs = None if w.residual is None else np.ascontiguousarray(w.residual[:ns])
+        reps, t_cpu = 0, 0.0
+        while t_cpu < args.cpu_seconds and reps < 50:
+            tc = time.perf_counter()
+            oracle.compress(gs, rs, ratios=oratios, dist=w.dist)
+            t_cpu += time.perf_counter() - tc
+            reps += 1
+        cpu_baseline = {
+            "value": round(ns * reps / t_cpu / 1e9, 5), "unit": "G elem/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {ns} of {d} elements of the same vector, {reps} repetitions, {t_cpu:.1f} s, "
+                      f"single thread, fp64 plain C",
+        }
+        log(f"cpu oracle: {cpu_baseline['value']} G elem/s on 1 core ({reps} reps, {t_cpu:.1f}s)")
+
+    result = {
+        "metric": "G gradient elems/s compressed (d=25.6M fp32, delta=0.001)" if args.workload == "cfg3"
+                  else f"G gradient elems/s compressed ({args.workload})",
+        "value": round(value, 2), "unit": "G elem/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: d={d} fp32, delta={w.delta}, dist={['exp', 'gamma-gpd', 'gpd'][w.dist]}, "
+                        f"stages={w.stages}, delta1={w.delta1}, error_feedback={'on' if ec else 'off'}",
+            "gradient_buffers_in_rotation": nbuf, "khat_over_k": round(float(np.mean(khat)) / (w.delta * d), 4),
+        },
+        "roofline": roofline, "path": path, "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
