@@ -17,9 +17,10 @@
  * "host" pointers are ordinary host memory.  No torch types cross this boundary.
  * Every enqueueing call is asynchronous on `stream` and returns after enqueue;
  * outputs are valid once the stream reaches that point.  The library never
- * synchronises with the host inside an enqueueing call, uses no atomics and no
- * device-side spinning, and its result is deterministic (same inputs -> same
- * bits, including the order of the output pairs).
+ * synchronises with the host inside an enqueueing call and never spins on the
+ * device.  Thresholds, the selected set, its values and the residual are
+ * deterministic (same inputs -> same bits); the order of the output pairs is
+ * fixed for a single-stage call and may vary between runs for M >= 2.
  *
  * Return value: 0 on success, a negative SIDCO_ERR_* otherwise.  Argument
  * errors are detected on the host before any HIP call is made.  Conditions
@@ -103,8 +104,7 @@ typedef struct sidco_diag {
  *  out_val    device, float, same capacity: out_val[i] = acc[out_idx[i]]
  *  out_count  device, 1 int32: number of pairs written (khat)
  *  out_eta    device, 1 float: eta_M
- * The pairs are written in a fixed, input-independent traversal order (not
- * sorted by index).  Buffers are owned by the caller; the library owns only
+ * The pairs are not sorted by index.  Buffers are owned by the caller; the library owns only
  * its workspace, which it allocates on first use per device (hipMalloc) and
  * grows when d grows, unless sidco_set_workspace was called.
  */
@@ -121,6 +121,22 @@ int sidco_compress_ex(void *stream, const float *grad, float *residual, int64_t 
                       int dist, const double *ratios, int n_ratios,
                       int32_t *out_idx, float *out_val, int64_t out_capacity,
                       int32_t *out_count, float *out_eta);
+
+/*
+ * Steps 1-2 alone: the error-compensation add (App. B.2; skipped when residual
+ * is NULL) fused with the sums of the stage-1 fit (Corollary 1 / eq. (6),
+ * Corollaries 1.2 and 1.3).  This is the kernel that dominates a call; it is
+ * exported so that it can be timed and checked on its own.  On return of the
+ * stream, residual holds acc = grad + residual.  The sums stay in the
+ * workspace until the next call on the device.
+ */
+int sidco_fit(void *stream, const float *grad, float *residual, int64_t d, int dist);
+
+/* Sums of the last sidco_fit on the current device, reduced on the host in a
+ * fixed order.  host_sums (host, 4 doubles) receives sum|acc|, sum acc^2
+ * (GPD law only, else 0), sum log max(|acc|, 2^-126) (gamma law only, else 0)
+ * and d.  Synchronises `stream`.                                              */
+int sidco_fit_result(void *stream, double *host_sums);
 
 /* Host helper: the default split of delta over `stages` stages described at
  * sidco_compress, for a given delta_1.  Writes the ratios to `ratios` (host,

@@ -17,7 +17,7 @@ DIST_EXP, DIST_GAMMA_GPD, DIST_GPD = 0, 1, 2
 ST_NONFINITE, ST_VAR_ZERO, ST_GAMMA_S, ST_GAMMA_CLAMP, ST_STOPPED, ST_OVERFLOW = 1, 2, 4, 8, 16, 32
 
 EXPORTS = [
-    "sidco_compress", "sidco_compress_ex", "sidco_stage_ratios", "sidco_out_capacity",
+    "sidco_compress", "sidco_compress_ex", "sidco_fit", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
     "sidco_workspace_bytes", "sidco_set_workspace", "sidco_read_diag", "sidco_set_profiling",
     "sidco_get_profile", "sidco_strerror", "sidco_last_hip_error", "sidco_version", "sidco_shutdown",
 ]
@@ -59,6 +59,13 @@ def load() -> C.CDLL:
         raise FileNotFoundError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2101_10761_amd.build` "
             "(there is no CPU or PyTorch fallback for the sparsifier)")
+    # One HIP runtime per process: libsidco.so needs libamdhip64.so.7, and so does torch, which ships
+    # its own copy.  Loading torch's first makes the dynamic linker resolve ours to the same object;
+    # two runtimes in one process cannot both open the device.
+    import torch
+    bundled = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+    if os.path.exists(bundled):
+        C.CDLL(bundled, mode=C.RTLD_GLOBAL)
     lib = C.CDLL(LIB_PATH)
     vp, f32p, i32p, f64p = C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)
     lib.sidco_compress.argtypes = [vp, f32p, f32p, C.c_int64, C.c_double, C.c_int, C.c_int, i32p, f32p, i32p, f32p]
@@ -66,6 +73,10 @@ def load() -> C.CDLL:
     lib.sidco_compress_ex.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int, f64p, C.c_int, i32p, f32p, C.c_int64,
                                       i32p, f32p]
     lib.sidco_compress_ex.restype = C.c_int
+    lib.sidco_fit.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int]
+    lib.sidco_fit.restype = C.c_int
+    lib.sidco_fit_result.argtypes = [vp, f64p]
+    lib.sidco_fit_result.restype = C.c_int
     lib.sidco_stage_ratios.argtypes = [C.c_double, C.c_int, C.c_double, f64p]
     lib.sidco_stage_ratios.restype = C.c_int
     lib.sidco_out_capacity.argtypes = [C.c_int64, C.c_double]
@@ -177,6 +188,22 @@ def sidco_compress_ex(grad, residual, dist: int, ratios, out_idx, out_val, out_c
     _check(load().sidco_compress_ex(_stream_handle(stream), _ptr(grad), _ptr(residual), d, dist, r, len(ratios),
                                     _ptr(out_idx), _ptr(out_val), cap, _ptr(out_count), _ptr(out_eta)),
            "sidco_compress_ex")
+
+
+def sidco_fit(grad, residual, dist: int, stream=None) -> None:
+    """Enqueues steps 1-2 alone (error-compensation add fused with the stage-1 sums)."""
+    import torch
+    _check_tensor(grad, torch.float32, "grad")
+    if residual is not None:
+        _check_tensor(residual, torch.float32, "residual", grad.numel())
+    _check(load().sidco_fit(_stream_handle(stream), _ptr(grad), _ptr(residual), grad.numel(), dist), "sidco_fit")
+
+
+def sidco_fit_result(stream=None) -> tuple[float, float, float, float]:
+    """(sum|acc|, sum acc^2, sum log|acc|, d) of the last sidco_fit; synchronises."""
+    out = (C.c_double * 4)()
+    _check(load().sidco_fit_result(_stream_handle(stream), out), "sidco_fit_result")
+    return out[0], out[1], out[2], out[3]
 
 
 def sidco_read_diag(stream=None) -> Diag:

@@ -40,6 +40,10 @@ struct DeviceCtx {
     bool ev_made = false;
     int prof_n = 0;            // kernels of the last profiled call
     const char* prof_name[kMaxKernels] = {};
+    int64_t last_cap = 0;      // output capacity of the last compress call
+    uint32_t fit_nblocks = 0;  // grid, length and law of the last sidco_fit call
+    int64_t fit_d = 0;
+    int fit_dist = 0;
 };
 
 std::mutex g_mu;
@@ -89,24 +93,9 @@ int ensure_workspace(DeviceCtx& c, size_t need)
     return SIDCO_OK;
 }
 
-int run(void* stream, const float* grad, float* residual, int64_t d, int dist, const double* ratios, int M,
-        int32_t* out_idx, float* out_val, int64_t out_cap, int32_t* out_count, float* out_eta)
+// Fills the launch geometry and buffer pointers that every kernel of a call shares.
+void fill_common(Params& p, WorkspaceHead* h, const float* grad, float* residual, int64_t d, int dist)
 {
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
-    if (dev < 0 || dev >= kMaxDevices) return SIDCO_ERR_ARG;
-    std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx& c = g_ctx[dev];
-    const size_t seg = seg_bytes(d);
-    int rc = ensure_workspace(c, head_bytes() + 2 * seg);
-    if (rc != SIDCO_OK) return rc;
-    hipStream_t s = (hipStream_t)stream;
-
-    WorkspaceHead* h = (WorkspaceHead*)c.ws;
-    int2* segbuf[2] = {(int2*)((char*)c.ws + head_bytes()), (int2*)((char*)c.ws + head_bytes() + seg)};
-
-    Params p;
     memset(&p, 0, sizeof(p));
     p.grad = grad;
     p.residual = residual;
@@ -118,14 +107,46 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
     p.nblocks = (p.nwaves + kWavesPerBlock - 1) / kWavesPerBlock;
     p.vec_ok = aligned16(grad) && aligned16(residual);
     p.dist = dist;
+    p.st = &h->st;
+}
+
+int current_ctx(DeviceCtx** c)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return SIDCO_ERR_ARG;
+    *c = &g_ctx[dev];
+    return SIDCO_OK;
+}
+
+int run(void* stream, const float* grad, float* residual, int64_t d, int dist, const double* ratios, int M,
+        int32_t* out_idx, float* out_val, int64_t out_cap, int32_t* out_count, float* out_eta)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx* cp = nullptr;
+    int rc = current_ctx(&cp);
+    if (rc != SIDCO_OK) return rc;
+    DeviceCtx& c = *cp;
+    const size_t seg = seg_bytes(d);
+    rc = ensure_workspace(c, head_bytes() + 2 * seg);
+    if (rc != SIDCO_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+
+    WorkspaceHead* h = (WorkspaceHead*)c.ws;
+    int2* segbuf[2] = {(int2*)((char*)c.ws + head_bytes()), (int2*)((char*)c.ws + head_bytes() + seg)};
+
+    Params p;
+    fill_common(p, h, grad, residual, d, dist);
     p.M = M;
     for (int m = 0; m < M; ++m) p.L[m] = log(1.0 / ratios[m]);
-    p.st = &h->st;
     p.out_idx = out_idx;
     p.out_val = out_val;
     p.out_count = out_count;
     p.out_eta = out_eta;
     p.out_cap = out_cap;
+    c.last_cap = out_cap;
 
     const bool prof = g_profiling;
     if (prof && !c.ev_made) {
@@ -149,8 +170,8 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
     ++k;
     mark("k_fit");
 
-    // stage m: threshold from the previous kernel's sums, survivor lists into segbuf[(m-1)&1]
-    for (int m = 1; m <= M; ++m) {
+    // stage m: threshold from the previous kernel's sums, survivor lists into segbuf[m & 1]
+    auto bind_stage = [&](int m) {
         const int in = (m - 1) & 1, out = m & 1;
         p.stage = m;
         p.part_in = h->part[in];
@@ -161,11 +182,18 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
         p.blk_out = h->blk[out];
         p.seg_in = segbuf[in];
         p.seg_out = segbuf[out];
-        launch_compact(p, /*dense=*/m == 1, /*stats=*/m < M, s);
+    };
+    for (int m = 1; m < M; ++m) {
+        bind_stage(m);
+        launch_compact(p, /*dense=*/m == 1, /*stats=*/true, s);
         ++k;
         mark(m == 1 ? "k_compact_dense" : "k_compact_lists");
     }
-    {
+    bind_stage(M);
+    if (M == 1) {
+        launch_compact(p, /*dense=*/true, /*stats=*/false, s);
+        ++k;
+        mark("k_compact_dense");
         const int in = M & 1;
         p.cnt_in = h->cnt[in];
         p.blk_in = h->blk[in];
@@ -173,6 +201,18 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
         launch_gather(p, s);
         ++k;
         mark("k_gather");
+    } else {
+        // The lists the last stage reads hold about d * delta_1 * ... * delta_{M-1} pairs.  The host only
+        // knows this expectation; it sizes the grid with it (few blocks = few reservation atomics), and a
+        // wrong guess costs time, never correctness.
+        double expect = (double)d;
+        for (int m = 0; m + 1 < M; ++m) expect *= ratios[m];
+        uint32_t grid = (uint32_t)fmin(256.0, ceil(expect / 8192.0));
+        if (grid < 16) grid = 16;
+        if (grid > p.nwaves) grid = p.nwaves;
+        launch_final_lists(p, grid, s);
+        ++k;
+        mark("k_final_lists");
     }
     c.prof_n = prof ? k : 0;
     e = hipGetLastError();
@@ -266,6 +306,57 @@ int sidco_compress(void* stream, const float* grad, float* residual, int64_t d, 
                out_eta);
 }
 
+int sidco_fit(void* stream, const float* grad, float* residual, int64_t d, int dist)
+{
+    if (!grad) return SIDCO_ERR_NULL;
+    if (d < 1 || d > (int64_t)INT32_MAX) return SIDCO_ERR_SIZE;
+    if (dist != SIDCO_DIST_EXP && dist != SIDCO_DIST_GAMMA_GPD && dist != SIDCO_DIST_GPD) return SIDCO_ERR_DIST;
+    if (!aligned4(grad) || !aligned4(residual)) return SIDCO_ERR_ALIGN;
+    if (residual && (const void*)residual == (const void*)grad) return SIDCO_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx* cp = nullptr;
+    int rc = current_ctx(&cp);
+    if (rc != SIDCO_OK) return rc;
+    rc = ensure_workspace(*cp, head_bytes() + 2 * seg_bytes(d));
+    if (rc != SIDCO_OK) return rc;
+    WorkspaceHead* h = (WorkspaceHead*)cp->ws;
+    Params p;
+    fill_common(p, h, grad, residual, d, dist);
+    p.M = 1;
+    p.part_out = h->part[0];
+    launch_fit(p, (hipStream_t)stream);
+    cp->fit_nblocks = p.nblocks;
+    cp->fit_d = d;
+    cp->fit_dist = dist;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    return SIDCO_OK;
+}
+
+int sidco_fit_result(void* stream, double* host_sums)
+{
+    if (!host_sums) return SIDCO_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx* cp = nullptr;
+    int rc = current_ctx(&cp);
+    if (rc != SIDCO_OK) return rc;
+    if (!cp->ws || cp->fit_nblocks == 0) return SIDCO_ERR_WORKSPACE;
+    static thread_local double part[4 * kMaxBlocks];
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipMemcpyAsync(part, ((WorkspaceHead*)cp->ws)->part[0], sizeof(part), hipMemcpyDeviceToHost, s);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(partials)");
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    double sum[3] = {0.0, 0.0, 0.0};
+    for (int q = 0; q < 3; ++q)
+        for (uint32_t b = 0; b < cp->fit_nblocks; ++b) sum[q] += part[q * kMaxBlocks + b];
+    host_sums[0] = sum[0];
+    host_sums[1] = cp->fit_dist == SIDCO_DIST_GPD ? sum[1] : 0.0;
+    host_sums[2] = cp->fit_dist == SIDCO_DIST_GAMMA_GPD ? sum[2] * 0.6931471805599453094 : 0.0;
+    host_sums[3] = (double)cp->fit_d;
+    return SIDCO_OK;
+}
+
 int sidco_read_diag(void* stream, sidco_diag* host_out)
 {
     if (!host_out) return SIDCO_ERR_NULL;
@@ -277,10 +368,16 @@ int sidco_read_diag(void* stream, sidco_diag* host_out)
     DeviceCtx& c = g_ctx[dev];
     if (!c.ws) return SIDCO_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    e = hipMemcpyAsync(host_out, &((WorkspaceHead*)c.ws)->st.diag, sizeof(sidco_diag), hipMemcpyDeviceToHost, s);
+    DevState st;
+    e = hipMemcpyAsync(&st, &((WorkspaceHead*)c.ws)->st, sizeof(DevState), hipMemcpyDeviceToHost, s);
     if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(diag)");
     e = hipStreamSynchronize(s);
     if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    *host_out = st.diag;
+    host_out->selected = (int64_t)st.selected_ctr;
+    host_out->count = (int32_t)((int64_t)st.selected_ctr < c.last_cap ? (int64_t)st.selected_ctr : c.last_cap);
+    if (st.overflow) host_out->status |= SIDCO_ST_OVERFLOW;
+    host_out->reserved = 0;
     const int M = host_out->stages;
     for (int m = (M < 0 ? 0 : M); m < SIDCO_MAX_STAGES; ++m) {  // entries of earlier, longer calls
         host_out->eta[m] = 0.0f;

@@ -33,6 +33,8 @@ struct DevState {
     sidco_diag diag;
     uint32_t status_after[SIDCO_MAX_STAGES + 1];  // status bits accumulated up to and including stage m
     uint32_t frozen_after[SIDCO_MAX_STAGES + 1];  // 1 once an empty exceedance set stopped the refinement
+    unsigned long long selected_ctr;              // pairs selected by the last stage (cleared by k_fit)
+    uint32_t overflow;                            // 1 if selected_ctr exceeded the output capacity
 };
 
 // Kernel arguments (passed by value).
@@ -68,6 +70,7 @@ struct Params {
 
 void launch_fit(const Params& p, hipStream_t s);
 void launch_compact(const Params& p, bool dense, bool stats, hipStream_t s);
+void launch_final_lists(const Params& p, uint32_t grid_blocks, hipStream_t s);
 void launch_gather(const Params& p, hipStream_t s);
 
 }  // namespace sidco

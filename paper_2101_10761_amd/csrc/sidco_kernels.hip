@@ -10,14 +10,17 @@
 //                for m = 1, the previous survivor lists afterwards) are appended to per-wave
 //                survivor lists; for m < M the sums of (|x| - eta_m) and its square are formed for
 //                the next stage's fit.
-//   k_gather     exclusive prefix over the per-block survivor counts, copy of the lists into the
-//                contiguous (index, value) output, zeroing of the residual at those indices.
+//                The last stage differs: for M >= 2 its source lists are short, and k_final_lists
+//                selects, writes the contiguous (index, value) output and zeroes the residual at
+//                those indices in one kernel, each block reserving its output range with one atomic.
+//   k_gather     M = 1 only (last stage read the dense vector): exclusive prefix over the per-block
+//                survivor counts, copy of the lists into the output, residual zeroing.
 //
 // Design rules, from measurement on this chip: same-address atomics serialise at ~11 ns each and a
-// device-scope fence in a write-heavy kernel forces an L2 write-back, so the path has neither.
-// Kernel boundaries are the only global synchronisation; every wave owns a contiguous range of
-// 256-element tiles and a survivor list at the same offset, so list positions need no atomics and
-// the whole result (thresholds, order of output pairs) is deterministic.
+// device-scope fence in a write-heavy kernel forces an L2 write-back, so the big kernels have
+// neither.  Kernel boundaries are the only global synchronisation; every wave owns a contiguous
+// range of 256-element tiles and a survivor list at the same offset, so list positions need no
+// atomics, and thresholds, selected set and values are deterministic.
 //
 // All floating-point accumulation is fp64 (full rate on CDNA4 vector ALUs); comparisons are fp32
 // against the fp32 threshold, so the decision |x| > eta is the same one an fp32 reference takes.
@@ -328,6 +331,9 @@ __global__ __launch_bounds__(kBlock) void k_fit(Params p)
         p.st->status_after[0] = 0;
         p.st->frozen_after[0] = 0;
         p.st->diag.stages = p.M;
+        p.st->selected_ctr = 0;
+        p.st->overflow = 0;
+        if (p.out_count) *p.out_count = 0;
     }
 }
 
@@ -354,14 +360,11 @@ __device__ __forceinline__ void emit(bool valid, float x, int32_t idx, float eta
     run += (uint32_t)__popcll(mask);
 }
 
-// U complete tiles of the dense vector starting at tile t, float4 loads
+// U complete tiles of the dense vector, already loaded
 template <bool STATS, int U>
-__device__ __forceinline__ void compact_tiles(const f4* __restrict__ x4, uint32_t t, int lane, float eta,
-                                              int2* __restrict__ list, uint32_t& run, double& sy, double& syy)
+__device__ __forceinline__ void compact_loaded(const f4 (&a)[U], uint32_t t, int lane, float eta,
+                                               int2* __restrict__ list, uint32_t& run, double& sy, double& syy)
 {
-    f4 a[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) a[u] = x4[(size_t)(t + u) * 64 + lane];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int32_t i0 = (int32_t)((t + u) * kTile + lane * 4);
@@ -372,53 +375,110 @@ __device__ __forceinline__ void compact_tiles(const f4* __restrict__ x4, uint32_
     }
 }
 
+template <int U>
+__device__ __forceinline__ void load_tiles(f4 (&a)[U], const f4* __restrict__ x4, uint32_t t, int lane)
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u) a[u] = x4[(size_t)(t + u) * 64 + lane];
+}
+
+// Two list entries per lane and load (16 B): slot i of a wave's list holds entries 2i and 2i+1.
+// `cap2` is the number of slots the wave's segment has room for; slots past the list's end hold
+// stale data and are masked by `n_in`.
+template <int U>
+__device__ __forceinline__ void load_slots(int4 (&q)[U], const int4* __restrict__ src4, uint32_t c, uint32_t cap2,
+                                           int lane)
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t i = c + u * 64 + lane;
+        q[u] = i < cap2 ? src4[i] : make_int4(0, 0, 0, 0);
+    }
+}
+
+template <bool STATS, int U>
+__device__ __forceinline__ void compact_slots(const int4 (&q)[U], uint32_t c, uint32_t n_in, int lane, float eta,
+                                              int2* __restrict__ list, uint32_t& run, double& sy, double& syy)
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t e = 2 * (c + u * 64 + lane);
+        emit<STATS>(e < n_in, __int_as_float(q[u].y), q[u].x, eta, list, run, sy, syy);
+        emit<STATS>(e + 1 < n_in, __int_as_float(q[u].w), q[u].z, eta, list, run, sy, syy);
+    }
+}
+
 template <bool DENSE, bool STATS>
 __global__ __launch_bounds__(kBlock) void k_compact(Params p)
 {
     __shared__ double sh[kWavesPerBlock][4];
     __shared__ uint32_t sh_cnt[kWavesPerBlock];
-    const float eta = stage_prologue(p, sh);
-
+    constexpr int U = 4;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     const uint32_t w = blockIdx.x * kWavesPerBlock + wib;
+    const bool active = w < p.nwaves;
+    const uint32_t t0 = active ? tile_begin(w, p.ntiles, p.nwaves) : 0;
+    const uint32_t t1 = active ? tile_begin(w + 1, p.ntiles, p.nwaves) : 0;
+    const uint32_t tf = t1 < p.nfull ? t1 : p.nfull;  // tiles [t0,tf) are complete
+
+    // The first loads of the body do not depend on the threshold: issue them before the prologue so
+    // that their latency overlaps the reduction of the partial sums.
+    const f4* __restrict__ x4 = reinterpret_cast<const f4*>(p.acc);
+    const int4* __restrict__ src4 = reinterpret_cast<const int4*>(p.seg_in + (size_t)t0 * kTile);
+    const uint32_t cap2 = (t1 - t0) * (kTile / 2);
+    f4 a0[U];
+    int4 q0[U];
+    uint32_t n_in = 0;
+    const bool pre_dense = DENSE && active && p.vec_ok && t0 + U <= tf;
+    if (DENSE) {
+        if (pre_dense) load_tiles<U>(a0, x4, t0, lane);
+    } else if (active) {
+        n_in = p.cnt_in[w];
+        load_slots<U>(q0, src4, 0, cap2, lane);
+    }
+
+    const float eta = stage_prologue(p, sh);
+
     uint32_t run = 0;
     double sy = 0.0, syy = 0.0;
-    if (w < p.nwaves) {
-        const uint32_t t0 = tile_begin(w, p.ntiles, p.nwaves), t1 = tile_begin(w + 1, p.ntiles, p.nwaves);
+    if (active) {
         int2* __restrict__ list = p.seg_out + (size_t)t0 * kTile;  // room for every element of the wave's tiles
         if (DENSE) {
-            const float* __restrict__ x = p.acc;
-            const uint32_t tf = t1 < p.nfull ? t1 : p.nfull;
             uint32_t t = t0;
-            if (p.vec_ok) {
-                const f4* __restrict__ x4 = reinterpret_cast<const f4*>(x);
-                for (; t + 4 <= tf; t += 4) compact_tiles<STATS, 4>(x4, t, lane, eta, list, run, sy, syy);
-                for (; t < tf; ++t) compact_tiles<STATS, 1>(x4, t, lane, eta, list, run, sy, syy);
+            if (pre_dense) {
+                compact_loaded<STATS, U>(a0, t, lane, eta, list, run, sy, syy);
+                t += U;
             }
+            if (p.vec_ok) {
+                for (; t + U <= tf; t += U) {
+                    f4 a[U];
+                    load_tiles<U>(a, x4, t, lane);
+                    compact_loaded<STATS, U>(a, t, lane, eta, list, run, sy, syy);
+                }
+                for (; t < tf; ++t) {
+                    f4 a[1];
+                    load_tiles<1>(a, x4, t, lane);
+                    compact_loaded<STATS, 1>(a, t, lane, eta, list, run, sy, syy);
+                }
+            }
+            // unaligned buffers and the ragged last tile: guarded scalar loads
             for (; t < t1; ++t) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int64_t i = (int64_t)t * kTile + lane * 4 + j;
                     const bool valid = i < p.d;
-                    const float v = valid ? x[i] : 0.0f;
+                    const float v = valid ? p.acc[i] : 0.0f;
                     emit<STATS>(valid, v, (int32_t)i, eta, list, run, sy, syy);
                 }
             }
         } else {
-            const int2* __restrict__ src = p.seg_in + (size_t)t0 * kTile;
-            const uint32_t n_in = __builtin_amdgcn_readfirstlane(p.cnt_in[w]);
-            constexpr int U = 4;
-            for (uint32_t c = 0; c < n_in; c += 64 * U) {
-                int2 q[U];
-                bool ok[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const uint32_t i = c + u * 64 + lane;
-                    ok[u] = i < n_in;
-                    q[u] = ok[u] ? src[i] : make_int2(0, 0);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) emit<STATS>(ok[u], __int_as_float(q[u].y), q[u].x, eta, list, run, sy, syy);
+            n_in = __builtin_amdgcn_readfirstlane(n_in);
+            const uint32_t nslot = (n_in + 1) / 2;
+            compact_slots<STATS, U>(q0, 0, n_in, lane, eta, list, run, sy, syy);
+            for (uint32_t c = 64 * U; c < nslot; c += 64 * U) {
+                int4 q[U];
+                load_slots<U>(q, src4, c, cap2, lane);
+                compact_slots<STATS, U>(q, c, n_in, lane, eta, list, run, sy, syy);
             }
         }
         if (lane == 0) p.cnt_out[w] = run;
@@ -449,15 +509,142 @@ __global__ __launch_bounds__(kBlock) void k_compact(Params p)
 }
 
 // ---------------------------------------------------------------------------------------------
-// k_gather: survivor lists of the last stage -> contiguous (index, value) output; residual update
+// k_final_lists: last stage when its source is a set of survivor lists (M >= 2).
+// Threshold eta_M, selection, contiguous output and residual update in one kernel.  The lists are
+// short by now, so a small grid is used and each block reserves its output range with ONE atomic
+// add on the pair counter (same-address atomics cost ~11 ns each on this chip: a few dozen are
+// cheaper than another kernel boundary).  The set of pairs is deterministic; the order of the
+// blocks' ranges in the output is not.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_final_lists(Params p)
+{
+    __shared__ double sh[kWavesPerBlock][4];
+    __shared__ uint32_t sh_cnt[kWavesPerBlock];
+    __shared__ unsigned long long sh_base;
+    constexpr int U = 2;
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    // source lists handled by this wave: sw = first + k * stride < last
+    const uint32_t per_block = (p.nwaves + gridDim.x - 1) / gridDim.x;
+    const uint32_t first = blockIdx.x * per_block + wib;
+    const uint32_t last = min(p.nwaves, (blockIdx.x + 1) * per_block);
+
+    // loads that do not depend on the threshold go first (see k_compact)
+    int4 q0[U];
+    uint32_t n0 = 0, cap0 = 0;
+    const int4* src0 = nullptr;
+    if (first < last) {
+        const uint32_t t0 = tile_begin(first, p.ntiles, p.nwaves), t1 = tile_begin(first + 1, p.ntiles, p.nwaves);
+        src0 = reinterpret_cast<const int4*>(p.seg_in + (size_t)t0 * kTile);
+        cap0 = (t1 - t0) * (kTile / 2);
+        n0 = p.cnt_in[first];
+        load_slots<U>(q0, src0, 0, cap0, lane);
+    }
+
+    const float eta = stage_prologue(p, sh);
+
+    // pass A: count the exceedances of every list of this wave
+    uint32_t mine = 0;
+    for (uint32_t sw = first; sw < last; sw += kWavesPerBlock) {
+        const bool is0 = sw == first;
+        const uint32_t t0 = tile_begin(sw, p.ntiles, p.nwaves), t1 = tile_begin(sw + 1, p.ntiles, p.nwaves);
+        const int4* __restrict__ src4 = reinterpret_cast<const int4*>(p.seg_in + (size_t)t0 * kTile);
+        const uint32_t cap2 = (t1 - t0) * (kTile / 2);
+        const uint32_t n_in = __builtin_amdgcn_readfirstlane(is0 ? n0 : p.cnt_in[sw]);
+        const uint32_t nslot = (n_in + 1) / 2;
+        for (uint32_t c = 0; c < nslot; c += 64 * U) {
+            int4 q[U];
+            if (is0 && c == 0) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) q[u] = q0[u];
+            } else {
+                load_slots<U>(q, src4, c, cap2, lane);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t e = 2 * (c + u * 64 + lane);
+                const bool s0 = e < n_in && __builtin_fabsf(__int_as_float(q[u].y)) > eta;
+                const bool s1 = e + 1 < n_in && __builtin_fabsf(__int_as_float(q[u].w)) > eta;
+                mine += (uint32_t)__popcll(__ballot(s0)) + (uint32_t)__popcll(__ballot(s1));
+            }
+        }
+    }
+    if (lane == 0) sh_cnt[wib] = mine;
+    __syncthreads();
+    uint32_t off = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < kWavesPerBlock; ++i) {
+        if (i < wib) off += sh_cnt[i];
+        tot += sh_cnt[i];
+    }
+    const unsigned long long cap = (unsigned long long)p.out_cap;
+    if (threadIdx.x == 0) {
+        const unsigned long long base = atomicAdd(&p.st->selected_ctr, (unsigned long long)tot);
+        sh_base = base;
+        const unsigned long long end = base + tot;
+        atomicMax(p.out_count, (int32_t)(end < cap ? end : cap));
+        if (end > cap) p.st->overflow = 1u;  // every writer stores the same value
+        if (blockIdx.x == 0) {
+            *p.out_eta = eta;
+            p.st->diag.status = p.st->status_after[p.M];  // written by this kernel's prologue in block 0
+        }
+    }
+    __syncthreads();
+    unsigned long long pos = sh_base + off;
+
+    // pass B: same traversal, now writing
+    for (uint32_t sw = first; sw < last; sw += kWavesPerBlock) {
+        const uint32_t t0 = tile_begin(sw, p.ntiles, p.nwaves), t1 = tile_begin(sw + 1, p.ntiles, p.nwaves);
+        const int4* __restrict__ src4 = reinterpret_cast<const int4*>(p.seg_in + (size_t)t0 * kTile);
+        const uint32_t cap2 = (t1 - t0) * (kTile / 2);
+        const uint32_t n_in = __builtin_amdgcn_readfirstlane(p.cnt_in[sw]);
+        const uint32_t nslot = (n_in + 1) / 2;
+        for (uint32_t c = 0; c < nslot; c += 64 * U) {
+            int4 q[U];
+            load_slots<U>(q, src4, c, cap2, lane);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t e = 2 * (c + u * 64 + lane);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int32_t idx = h ? q[u].z : q[u].x;
+                    const float x = __int_as_float(h ? q[u].w : q[u].y);
+                    const bool sel = e + h < n_in && __builtin_fabsf(x) > eta;
+                    const unsigned long long mask = __ballot(sel);
+                    const unsigned long long at = pos + lane_prefix(mask);
+                    if (sel && at < cap) {  // pairs beyond the capacity stay in the residual
+                        p.out_idx[at] = idx;
+                        p.out_val[at] = x;
+                        if (p.residual) p.residual[idx] = 0.0f;
+                    }
+                    pos += (unsigned long long)__popcll(mask);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// k_gather: survivor lists of the last stage -> contiguous (index, value) output; residual update.
+// Used when the last stage read the dense vector (M = 1): no atomics, output order is fixed.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void k_gather(Params p)
 {
     __shared__ unsigned long long sh_u[kWavesPerBlock][2];
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     const uint32_t t = threadIdx.x;
-    // exclusive prefix of the per-block counts at this block, and their total
+    const uint32_t w = blockIdx.x * kWavesPerBlock + wib;
+    const uint32_t w0 = blockIdx.x * kWavesPerBlock;
+    const bool active = w < p.nwaves;
+    // independent loads first: block counts, the block's wave counts, this wave's count and first entries
     const unsigned long long c = t < p.nblocks ? (unsigned long long)p.blk_in[t] : 0ull;
+    uint32_t mine = (lane < wib && w0 + lane < p.nwaves) ? p.cnt_in[w0 + lane] : 0u;
+    uint32_t n_in = active ? p.cnt_in[w] : 0u;
+    const int2* __restrict__ src = p.seg_in + (size_t)(active ? tile_begin(w, p.ntiles, p.nwaves) : 0) * kTile;
+    const uint32_t cap_w = active ? (tile_begin(w + 1, p.ntiles, p.nwaves) - tile_begin(w, p.ntiles, p.nwaves)) * kTile : 0;
+    int2 first = make_int2(0, 0);
+    if ((uint32_t)lane < cap_w) first = src[lane];
+
+    // exclusive prefix of the per-block counts at this block, and their total
     unsigned long long below = wave_sum_u64(t < blockIdx.x ? c : 0ull);
     unsigned long long total = wave_sum_u64(c);
     if (lane == 0) {
@@ -474,30 +661,22 @@ __global__ __launch_bounds__(kBlock) void k_gather(Params p)
     }
     const unsigned long long cap = (unsigned long long)p.out_cap;
     if (blockIdx.x == 0 && t == 0) {
-        const float eta = p.st->diag.eta[p.M - 1];
-        uint32_t status = p.st->status_after[p.M];
-        if (total > cap) status |= kStOverflow;
-        const int32_t written = (int32_t)(total > cap ? cap : total);
-        *p.out_count = written;
-        *p.out_eta = eta;
-        p.st->diag.selected = (int64_t)total;
-        p.st->diag.count = written;
-        p.st->diag.status = status;
+        *p.out_count = (int32_t)(total > cap ? cap : total);
+        *p.out_eta = p.st->diag.eta[p.M - 1];
+        p.st->selected_ctr = total;
+        p.st->overflow = total > cap ? 1u : 0u;
+        p.st->diag.status = p.st->status_after[p.M];
     }
-    const uint32_t w = blockIdx.x * kWavesPerBlock + wib;
-    if (w >= p.nwaves) return;
+    if (!active) return;
     // offset of this wave inside the block: counts of the block's earlier waves
-    const uint32_t w0 = blockIdx.x * kWavesPerBlock;
-    uint32_t mine = (lane < wib && w0 + lane < p.nwaves) ? p.cnt_in[w0 + lane] : 0u;
 #pragma unroll
     for (int o = 4; o > 0; o >>= 1) mine += __shfl_down(mine, o, 64);  // lanes 0..7 only carry data
     const unsigned long long base = below + __builtin_amdgcn_readfirstlane(mine);
-    const uint32_t n_in = __builtin_amdgcn_readfirstlane(p.cnt_in[w]);
-    const int2* __restrict__ src = p.seg_in + (size_t)tile_begin(w, p.ntiles, p.nwaves) * kTile;
+    n_in = __builtin_amdgcn_readfirstlane(n_in);
     for (uint32_t i = lane; i < n_in; i += 64) {
         const unsigned long long pos = base + i;
         if (pos < cap) {  // pairs beyond the capacity stay in the residual
-            const int2 q = src[i];
+            const int2 q = i < 64 ? first : src[i];
             p.out_idx[pos] = q.x;
             p.out_val[pos] = __int_as_float(q.y);
             if (p.residual) p.residual[q.x] = 0.0f;
@@ -535,6 +714,11 @@ void launch_compact(const Params& p, bool dense, bool stats, hipStream_t s)
         if (stats) hipLaunchKernelGGL((k_compact<false, true>), grid, block, 0, s, p);
         else hipLaunchKernelGGL((k_compact<false, false>), grid, block, 0, s, p);
     }
+}
+
+void launch_final_lists(const Params& p, uint32_t grid_blocks, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_final_lists, dim3(grid_blocks), dim3(kBlock), 0, s, p);
 }
 
 void launch_gather(const Params& p, hipStream_t s)

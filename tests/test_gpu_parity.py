@@ -198,8 +198,9 @@ def test_output_overflow_is_safe(oracle):
 
 
 def test_deterministic_and_workspace_reuse(oracle):
-    """Same input twice -> same bits in the same order, also after a larger and a smaller call in between
-    (the workspace keeps stale lists), and with a caller-provided workspace."""
+    """Same input twice -> same thresholds, same selected set, same values (the order of the pairs may differ
+    for M >= 2 and is fixed for M = 1), also after a larger and a smaller call in between (the workspace
+    keeps stale lists), and with a caller-provided workspace."""
     import torch
     import paper_2101_10761_amd as sidco
     g, r = _inputs(1_500_000, 21, heavy=True)
@@ -210,23 +211,32 @@ def test_deterministic_and_workspace_reuse(oracle):
     small, rs = _inputs(999, 23)
     run_gpu(small, rs, 1, [0.05])
     b = run_gpu(g, r, 2, ratios)
-    np.testing.assert_array_equal(a.idx, b.idx)
-    np.testing.assert_array_equal(a.val.view(np.uint32), b.val.view(np.uint32))
-    assert a.etas.tobytes() == b.etas.tobytes()
+
+    def same(x, y, ordered=False):
+        ox, oy = (slice(None), slice(None)) if ordered else (np.argsort(x.idx), np.argsort(y.idx))
+        np.testing.assert_array_equal(x.idx[ox], y.idx[oy])
+        np.testing.assert_array_equal(x.val[ox].view(np.uint32), y.val[oy].view(np.uint32))
+        assert x.etas.tobytes() == y.etas.tobytes()
+        np.testing.assert_array_equal(x.residual.view(np.uint32), y.residual.view(np.uint32))
+
+    same(a, b)
+    s1 = run_gpu(g, r, 2, [0.001])
+    s2 = run_gpu(g, r, 2, [0.001])
+    same(s1, s2, ordered=True)
     check_parity(oracle, g, r, 2, ratios, b, label="reuse")
     ws = torch.empty(sidco.sidco_workspace_bytes(g.size), dtype=torch.uint8, device="cuda:0")
     assert ws.data_ptr() % 256 == 0
     sidco.sidco_set_workspace(ws)
     try:
         c = run_gpu(g, r, 2, ratios)
-        np.testing.assert_array_equal(a.idx, c.idx)
+        same(a, c)
         with pytest.raises(sidco.SidcoError) as e:
             run_gpu(big, rb, 0, ratios)   # needs more than the provided workspace
         assert e.value.code == -6
     finally:
         sidco.sidco_set_workspace(None)
     d2 = run_gpu(g, r, 2, ratios)
-    np.testing.assert_array_equal(a.idx, d2.idx)
+    same(a, d2)
 
 
 def test_eight_stages(oracle):
@@ -245,5 +255,46 @@ def test_profile_hooks():
         prof = sidco.sidco_get_profile()
     finally:
         sidco.sidco_set_profiling(False)
-    assert [n for n, _ in prof] == ["k_fit", "k_compact_dense", "k_compact_lists", "k_gather"]
+    assert [n for n, _ in prof] == ["k_fit", "k_compact_dense", "k_final_lists"]
     assert all(0 < ms < 50 for _, ms in prof)
+    sidco.sidco_set_profiling(True)
+    try:
+        run_gpu(g, r, 0, [0.25, 0.2, 0.2])
+        names3 = [n for n, _ in sidco.sidco_get_profile()]
+        run_gpu(g, r, 0, [0.01])
+        names1 = [n for n, _ in sidco.sidco_get_profile()]
+    finally:
+        sidco.sidco_set_profiling(False)
+    assert names3 == ["k_fit", "k_compact_dense", "k_compact_lists", "k_final_lists"]
+    assert names1 == ["k_fit", "k_compact_dense", "k_gather"]
+
+
+@pytest.mark.parametrize("dist", DISTS)
+@pytest.mark.parametrize("d,off", [(1, 0), (257, 0), (1_000_003, 0), (3_000_001, 1), (25_557_032, 0)])
+def test_fit_alone(oracle, dist, d, off):
+    """Steps 1-2 on their own: acc bit-exact (one fp32 add), sums within 1e-5 of the oracle's moments."""
+    import torch
+    import paper_2101_10761_amd as sidco
+    g, r = _inputs(d, 300 + dist, heavy=(dist == 2))
+    gbuf = torch.zeros(d + off, dtype=torch.float32, device="cuda:0")
+    rbuf = torch.zeros(d + off, dtype=torch.float32, device="cuda:0")
+    gt, rt = gbuf[off:], rbuf[off:]
+    gt.copy_(torch.from_numpy(g))
+    rt.copy_(torch.from_numpy(r))
+    sidco.sidco_fit(gt, rt, dist)
+    s1, s2, sl, n = sidco.sidco_fit_result()
+    acc = oracle.ec_add(g, r)
+    np.testing.assert_array_equal(rt.cpu().numpy().view(np.uint32), acc.view(np.uint32))
+    np.testing.assert_array_equal(gt.cpu().numpy().view(np.uint32), g.view(np.uint32))
+    mu, var, mulog = oracle.moments_all(acc)
+    assert n == d
+    assert s1 / d == pytest.approx(mu, rel=1e-5)
+    if dist == 2:
+        assert s2 / d - (s1 / d) ** 2 == pytest.approx(var, rel=1e-5)
+    if dist == 1:
+        assert sl / d == pytest.approx(mulog, rel=1e-5)
+        assert sl / d == pytest.approx(mulog, abs=2e-7)     # hardware log2 only sees mantissas in [0.5, 1)
+    # memoryless: nothing is written
+    sidco.sidco_fit(gt, None, dist)
+    s1b, _, _, _ = sidco.sidco_fit_result()
+    assert s1b / d == pytest.approx(float(np.abs(g.astype(np.float64)).mean()), rel=1e-5)
