@@ -134,6 +134,10 @@ def main():
     sidco.sidco_set_profiling(False)
     kern_us = {k: float(np.mean(v)) * 1e3 for k, v in per_kernel.items()}
     log("per-kernel average (HIP events): " + ", ".join(f"{k} {kern_us[k]:.1f} us" for k in order))
+    if not khat:   # no profiled steps asked for: take the diagnostics of the last timed step
+        diag = sidco.sidco_read_diag(stream)
+        n_stage = [diag.n[m] for m in range(diag.stages)]
+        khat.append(diag.count)
     log(f"last step: n per stage {n_stage}, khat {khat[-1]} (target {w.delta * d:.0f})")
 
     # Dominant kernel on its own: batches of back-to-back k_fit launches (sidco_fit) between two HIP

@@ -170,9 +170,13 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
     ++k;
     mark("k_fit");
 
-    // stage m: threshold from the previous kernel's sums, survivor lists into segbuf[m & 1]
-    auto bind_stage = [&](int m) {
-        const int in = (m - 1) & 1, out = m & 1;
+    // Stage m: threshold from the previous kernel's sums.  Buffers alternate with the kernel number.
+    // `dense` stays true until a stage has materialised survivor lists.
+    bool dense = true;
+    double cum = 1.0;
+    int sel = 0;  // which half of the double buffers the last kernel wrote
+    auto bind = [&](int m) {
+        const int in = sel, out = sel ^ 1;
         p.stage = m;
         p.part_in = h->part[in];
         p.part_out = h->part[out];
@@ -182,22 +186,31 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
         p.blk_out = h->blk[out];
         p.seg_in = segbuf[in];
         p.seg_out = segbuf[out];
+        sel = out;
     };
     for (int m = 1; m < M; ++m) {
-        bind_stage(m);
-        launch_compact(p, /*dense=*/m == 1, /*stats=*/true, s);
-        ++k;
-        mark(m == 1 ? "k_compact_dense" : "k_compact_lists");
+        cum *= ratios[m - 1];
+        bind(m);
+        if (dense) {
+            const bool write = cum <= kMaterializeBelow;
+            launch_compact(p, /*dense=*/true, /*stats=*/true, write, s);
+            ++k;
+            mark(write ? "k_compact_dense" : "k_scan_dense");
+            if (write) dense = false;
+        } else {
+            launch_compact(p, /*dense=*/false, /*stats=*/true, /*write=*/true, s);
+            ++k;
+            mark("k_compact_lists");
+        }
     }
-    bind_stage(M);
-    if (M == 1) {
-        launch_compact(p, /*dense=*/true, /*stats=*/false, s);
+    bind(M);
+    if (dense) {
+        launch_compact(p, /*dense=*/true, /*stats=*/false, /*write=*/true, s);
         ++k;
         mark("k_compact_dense");
-        const int in = M & 1;
-        p.cnt_in = h->cnt[in];
-        p.blk_in = h->blk[in];
-        p.seg_in = segbuf[in];
+        p.cnt_in = h->cnt[sel];
+        p.blk_in = h->blk[sel];
+        p.seg_in = segbuf[sel];
         launch_gather(p, s);
         ++k;
         mark("k_gather");
@@ -205,11 +218,11 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
         // The lists the last stage reads hold about d * delta_1 * ... * delta_{M-1} pairs.  The host only
         // knows this expectation; it sizes the grid with it (few blocks = few reservation atomics), and a
         // wrong guess costs time, never correctness.
-        double expect = (double)d;
-        for (int m = 0; m + 1 < M; ++m) expect *= ratios[m];
-        uint32_t grid = (uint32_t)fmin(256.0, ceil(expect / 8192.0));
-        if (grid < 16) grid = 16;
-        if (grid > p.nwaves) grid = p.nwaves;
+        const double expect = (double)d * cum;
+        // short lists: 4 lists per wave (one group, everything prefetched); long lists: more blocks
+        uint32_t grid = expect > 4.0e6 ? 256u : (p.nwaves + 31) / 32;
+        if (grid > p.nblocks) grid = p.nblocks;
+        if (grid < 1) grid = 1;
         launch_final_lists(p, grid, s);
         ++k;
         mark("k_final_lists");

@@ -14,6 +14,10 @@ constexpr int kWavesPerBlock = kBlock / 64;
 constexpr int kTile = 256;                        // elements per wave step: 64 lanes x float4
 constexpr int kMaxBlocks = 512;                   // 2 blocks per CU on 256 CUs
 constexpr int kMaxWaves = kMaxBlocks * kWavesPerBlock;
+// A non-final stage whose source is still the dense vector materialises its survivor lists only if
+// the expected surviving fraction is at most this; otherwise it only counts and sums, and the next
+// stage scans the dense vector again (4 B/element read, against 16 B per survivor written + read).
+constexpr double kMaterializeBelow = 0.125;
 static_assert(kMaxBlocks <= kBlock, "one thread per producer block in the prologue reductions");
 
 constexpr int kDistExp = SIDCO_DIST_EXP;
@@ -69,7 +73,7 @@ struct Params {
 };
 
 void launch_fit(const Params& p, hipStream_t s);
-void launch_compact(const Params& p, bool dense, bool stats, hipStream_t s);
+void launch_compact(const Params& p, bool dense, bool stats, bool write, hipStream_t s);
 void launch_final_lists(const Params& p, uint32_t grid_blocks, hipStream_t s);
 void launch_gather(const Params& p, hipStream_t s);
 

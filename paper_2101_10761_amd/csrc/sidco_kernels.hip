@@ -210,11 +210,12 @@ __device__ float stage_prologue(const Params& p, double (*sh)[4])
         v[0] = have ? p.part_in[0 * kMaxBlocks + t] : 0.0;
         v[1] = (have && p.dist != kDistExp) ? p.part_in[1 * kMaxBlocks + t] : 0.0;
         v[2] = have ? (double)p.blk_in[t] : 0.0;  // counts < 2^31: exact in fp64
-        block_sum<3>(v, sh);
-        n = (unsigned long long)v[2];
+        // the previous stage's record, loaded together with the partial sums (one round trip)
         const float eta_prev = p.st->diag.eta[m - 2];
         status = p.st->status_after[m - 1];
         const bool frozen_in = p.st->frozen_after[m - 1] != 0;
+        block_sum<3>(v, sh);
+        n = (unsigned long long)v[2];
         eta = pot_eta(p.dist, n, v[0], v[1], eta_prev, p.L[m - 1], frozen_in, frozen, status, stats);
     }
     if (blockIdx.x == 0 && t == 0) {
@@ -342,7 +343,7 @@ __global__ __launch_bounds__(kBlock) void k_fit(Params p)
 // ---------------------------------------------------------------------------------------------
 
 // One component of a tile (64 candidates, one per lane).  `run` is the wave's list length so far.
-template <bool STATS>
+template <bool STATS, bool WRITE = true>
 __device__ __forceinline__ void emit(bool valid, float x, int32_t idx, float eta, int2* __restrict__ list,
                                      uint32_t& run, double& sy, double& syy)
 {
@@ -350,7 +351,7 @@ __device__ __forceinline__ void emit(bool valid, float x, int32_t idx, float eta
     const bool sel = valid && (a > eta);  // strict, fp32; NaN on either side is false
     const unsigned long long mask = __ballot(sel);
     if (sel) {
-        list[run + lane_prefix(mask)] = make_int2(idx, __float_as_int(x));
+        if (WRITE) list[run + lane_prefix(mask)] = make_int2(idx, __float_as_int(x));
         if (STATS) {
             const double y = (double)a - (double)eta;
             sy += y;
@@ -361,17 +362,17 @@ __device__ __forceinline__ void emit(bool valid, float x, int32_t idx, float eta
 }
 
 // U complete tiles of the dense vector, already loaded
-template <bool STATS, int U>
+template <bool STATS, bool WRITE, int U>
 __device__ __forceinline__ void compact_loaded(const f4 (&a)[U], uint32_t t, int lane, float eta,
                                                int2* __restrict__ list, uint32_t& run, double& sy, double& syy)
 {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int32_t i0 = (int32_t)((t + u) * kTile + lane * 4);
-        emit<STATS>(true, a[u].x, i0 + 0, eta, list, run, sy, syy);
-        emit<STATS>(true, a[u].y, i0 + 1, eta, list, run, sy, syy);
-        emit<STATS>(true, a[u].z, i0 + 2, eta, list, run, sy, syy);
-        emit<STATS>(true, a[u].w, i0 + 3, eta, list, run, sy, syy);
+        emit<STATS, WRITE>(true, a[u].x, i0 + 0, eta, list, run, sy, syy);
+        emit<STATS, WRITE>(true, a[u].y, i0 + 1, eta, list, run, sy, syy);
+        emit<STATS, WRITE>(true, a[u].z, i0 + 2, eta, list, run, sy, syy);
+        emit<STATS, WRITE>(true, a[u].w, i0 + 3, eta, list, run, sy, syy);
     }
 }
 
@@ -408,7 +409,11 @@ __device__ __forceinline__ void compact_slots(const int4 (&q)[U], uint32_t c, ui
     }
 }
 
-template <bool DENSE, bool STATS>
+// DENSE: the source is the dense vector, else the previous survivor lists.  STATS: form the sums for
+// the next stage's fit.  WRITE: append the exceedances to this stage's lists; a dense stage that keeps
+// a large fraction (delta_1 = 0.25) only counts and sums, and the next stage reads the dense vector
+// again, which moves fewer bytes than writing and re-reading 8-byte pairs for a quarter of it.
+template <bool DENSE, bool STATS, bool WRITE>
 __global__ __launch_bounds__(kBlock) void k_compact(Params p)
 {
     __shared__ double sh[kWavesPerBlock][4];
@@ -446,19 +451,19 @@ __global__ __launch_bounds__(kBlock) void k_compact(Params p)
         if (DENSE) {
             uint32_t t = t0;
             if (pre_dense) {
-                compact_loaded<STATS, U>(a0, t, lane, eta, list, run, sy, syy);
+                compact_loaded<STATS, WRITE, U>(a0, t, lane, eta, list, run, sy, syy);
                 t += U;
             }
             if (p.vec_ok) {
                 for (; t + U <= tf; t += U) {
                     f4 a[U];
                     load_tiles<U>(a, x4, t, lane);
-                    compact_loaded<STATS, U>(a, t, lane, eta, list, run, sy, syy);
+                    compact_loaded<STATS, WRITE, U>(a, t, lane, eta, list, run, sy, syy);
                 }
                 for (; t < tf; ++t) {
                     f4 a[1];
                     load_tiles<1>(a, x4, t, lane);
-                    compact_loaded<STATS, 1>(a, t, lane, eta, list, run, sy, syy);
+                    compact_loaded<STATS, WRITE, 1>(a, t, lane, eta, list, run, sy, syy);
                 }
             }
             // unaligned buffers and the ragged last tile: guarded scalar loads
@@ -468,17 +473,21 @@ __global__ __launch_bounds__(kBlock) void k_compact(Params p)
                     const int64_t i = (int64_t)t * kTile + lane * 4 + j;
                     const bool valid = i < p.d;
                     const float v = valid ? p.acc[i] : 0.0f;
-                    emit<STATS>(valid, v, (int32_t)i, eta, list, run, sy, syy);
+                    emit<STATS, WRITE>(valid, v, (int32_t)i, eta, list, run, sy, syy);
                 }
             }
         } else {
             n_in = __builtin_amdgcn_readfirstlane(n_in);
             const uint32_t nslot = (n_in + 1) / 2;
-            compact_slots<STATS, U>(q0, 0, n_in, lane, eta, list, run, sy, syy);
-            for (uint32_t c = 64 * U; c < nslot; c += 64 * U) {
-                int4 q[U];
-                load_slots<U>(q, src4, c, cap2, lane);
-                compact_slots<STATS, U>(q, c, n_in, lane, eta, list, run, sy, syy);
+            // two register buffers: the loads of the next step are in flight while this one is compacted
+            constexpr uint32_t S = 64 * U;
+            int4 q1[U];
+            for (uint32_t c = 0; c < nslot; c += 2 * S) {
+                const bool more1 = c + S < nslot;
+                if (more1) load_slots<U>(q1, src4, c + S, cap2, lane);
+                compact_slots<STATS, U>(q0, c, n_in, lane, eta, list, run, sy, syy);
+                if (c + 2 * S < nslot) load_slots<U>(q0, src4, c + 2 * S, cap2, lane);
+                if (more1) compact_slots<STATS, U>(q1, c + S, n_in, lane, eta, list, run, sy, syy);
             }
         }
         if (lane == 0) p.cnt_out[w] = run;
@@ -511,60 +520,116 @@ __global__ __launch_bounds__(kBlock) void k_compact(Params p)
 // ---------------------------------------------------------------------------------------------
 // k_final_lists: last stage when its source is a set of survivor lists (M >= 2).
 // Threshold eta_M, selection, contiguous output and residual update in one kernel.  The lists are
-// short by now, so a small grid is used and each block reserves its output range with ONE atomic
-// add on the pair counter (same-address atomics cost ~11 ns each on this chip: a few dozen are
+// short by now and the kernel is bound by memory latency, not bandwidth: every wave takes up to
+// kFinalGroup lists at a time and issues all their loads together, before the prologue, so that the
+// whole kernel is a few dependent round trips.  Each block reserves its output range with ONE atomic
+// add on the pair counter (same-address atomics cost ~11 ns each on this chip: a hundred of them are
 // cheaper than another kernel boundary).  The set of pairs is deterministic; the order of the
 // blocks' ranges in the output is not.
 // ---------------------------------------------------------------------------------------------
+constexpr int kFinalGroup = 4;
+
+struct FinalList {
+    const int4* src4;  // the list, two entries per slot
+    uint32_t cap2;     // slots the segment has room for
+    uint32_t n;        // entries
+};
+
+__device__ __forceinline__ FinalList final_list(const Params& p, uint32_t sw, bool valid)
+{
+    FinalList l;
+    const uint32_t t0 = valid ? tile_begin(sw, p.ntiles, p.nwaves) : 0;
+    const uint32_t t1 = valid ? tile_begin(sw + 1, p.ntiles, p.nwaves) : 0;
+    l.src4 = reinterpret_cast<const int4*>(p.seg_in + (size_t)t0 * kTile);
+    l.cap2 = (t1 - t0) * (kTile / 2);
+    l.n = valid ? p.cnt_in[sw] : 0u;
+    return l;
+}
+
+// exceedances among the two entries of this lane's slot `slot` (wave-wide count)
+__device__ __forceinline__ uint32_t final_count(int4 q, uint32_t slot, uint32_t n, float eta)
+{
+    const uint32_t e = 2 * slot;
+    const bool s0 = e < n && __builtin_fabsf(__int_as_float(q.y)) > eta;
+    const bool s1 = e + 1 < n && __builtin_fabsf(__int_as_float(q.w)) > eta;
+    return (uint32_t)__popcll(__ballot(s0)) + (uint32_t)__popcll(__ballot(s1));
+}
+
+// writes the exceedances of this lane's slot at the wave's running position `pos`
+__device__ __forceinline__ void final_emit(const Params& p, int4 q, uint32_t slot, uint32_t n, float eta,
+                                           unsigned long long cap, unsigned long long& pos)
+{
+    const uint32_t e = 2 * slot;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int32_t idx = h ? q.z : q.x;
+        const float x = __int_as_float(h ? q.w : q.y);
+        const bool sel = e + h < n && __builtin_fabsf(x) > eta;
+        const unsigned long long mask = __ballot(sel);
+        const unsigned long long at = pos + lane_prefix(mask);
+        if (sel && at < cap) {  // pairs beyond the capacity stay in the residual
+            p.out_idx[at] = idx;
+            p.out_val[at] = x;
+            if (p.residual) p.residual[idx] = 0.0f;
+        }
+        pos += (unsigned long long)__popcll(mask);
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void k_final_lists(Params p)
 {
     __shared__ double sh[kWavesPerBlock][4];
     __shared__ uint32_t sh_cnt[kWavesPerBlock];
     __shared__ unsigned long long sh_base;
-    constexpr int U = 2;
+    constexpr int K = kFinalGroup;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    // source lists handled by this wave: sw = first + k * stride < last
+    // source lists of this wave: first, first + 8, first + 16, ... below last
     const uint32_t per_block = (p.nwaves + gridDim.x - 1) / gridDim.x;
     const uint32_t first = blockIdx.x * per_block + wib;
     const uint32_t last = min(p.nwaves, (blockIdx.x + 1) * per_block);
 
-    // loads that do not depend on the threshold go first (see k_compact)
-    int4 q0[U];
-    uint32_t n0 = 0, cap0 = 0;
-    const int4* src0 = nullptr;
-    if (first < last) {
-        const uint32_t t0 = tile_begin(first, p.ntiles, p.nwaves), t1 = tile_begin(first + 1, p.ntiles, p.nwaves);
-        src0 = reinterpret_cast<const int4*>(p.seg_in + (size_t)t0 * kTile);
-        cap0 = (t1 - t0) * (kTile / 2);
-        n0 = p.cnt_in[first];
-        load_slots<U>(q0, src0, 0, cap0, lane);
+    // first group of lists: counts and first 64 slots of each, all loads issued together and before
+    // the prologue (none depends on the threshold)
+    FinalList l0[K];
+    int4 q0[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t sw = first + k * kWavesPerBlock;
+        l0[k] = final_list(p, sw, sw < last);
+        q0[k] = (uint32_t)lane < l0[k].cap2 ? l0[k].src4[lane] : make_int4(0, 0, 0, 0);
     }
 
     const float eta = stage_prologue(p, sh);
 
-    // pass A: count the exceedances of every list of this wave
+    // pass A: count
     uint32_t mine = 0;
-    for (uint32_t sw = first; sw < last; sw += kWavesPerBlock) {
-        const bool is0 = sw == first;
-        const uint32_t t0 = tile_begin(sw, p.ntiles, p.nwaves), t1 = tile_begin(sw + 1, p.ntiles, p.nwaves);
-        const int4* __restrict__ src4 = reinterpret_cast<const int4*>(p.seg_in + (size_t)t0 * kTile);
-        const uint32_t cap2 = (t1 - t0) * (kTile / 2);
-        const uint32_t n_in = __builtin_amdgcn_readfirstlane(is0 ? n0 : p.cnt_in[sw]);
-        const uint32_t nslot = (n_in + 1) / 2;
-        for (uint32_t c = 0; c < nslot; c += 64 * U) {
-            int4 q[U];
-            if (is0 && c == 0) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) q[u] = q0[u];
-            } else {
-                load_slots<U>(q, src4, c, cap2, lane);
-            }
+    for (int k = 0; k < K; ++k) {
+        const uint32_t n = __builtin_amdgcn_readfirstlane(l0[k].n);
+        mine += final_count(q0[k], lane, n, eta);
+        for (uint32_t c = 64; c < (n + 1) / 2; c += 64) {
+            const uint32_t i = c + lane;
+            const int4 q = i < l0[k].cap2 ? l0[k].src4[i] : make_int4(0, 0, 0, 0);
+            mine += final_count(q, i, n, eta);
+        }
+    }
+    for (uint32_t g = first + K * kWavesPerBlock; g < last; g += K * kWavesPerBlock) {
+        FinalList l[K];
+        int4 q[K];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t e = 2 * (c + u * 64 + lane);
-                const bool s0 = e < n_in && __builtin_fabsf(__int_as_float(q[u].y)) > eta;
-                const bool s1 = e + 1 < n_in && __builtin_fabsf(__int_as_float(q[u].w)) > eta;
-                mine += (uint32_t)__popcll(__ballot(s0)) + (uint32_t)__popcll(__ballot(s1));
+        for (int k = 0; k < K; ++k) {
+            const uint32_t sw = g + k * kWavesPerBlock;
+            l[k] = final_list(p, sw, sw < last);
+            q[k] = (uint32_t)lane < l[k].cap2 ? l[k].src4[lane] : make_int4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const uint32_t n = __builtin_amdgcn_readfirstlane(l[k].n);
+            mine += final_count(q[k], lane, n, eta);
+            for (uint32_t c = 64; c < (n + 1) / 2; c += 64) {
+                const uint32_t i = c + lane;
+                const int4 qq = i < l[k].cap2 ? l[k].src4[i] : make_int4(0, 0, 0, 0);
+                mine += final_count(qq, i, n, eta);
             }
         }
     }
@@ -585,39 +650,40 @@ __global__ __launch_bounds__(kBlock) void k_final_lists(Params p)
         if (end > cap) p.st->overflow = 1u;  // every writer stores the same value
         if (blockIdx.x == 0) {
             *p.out_eta = eta;
-            p.st->diag.status = p.st->status_after[p.M];  // written by this kernel's prologue in block 0
+            p.st->diag.status = p.st->status_after[p.M];  // written by this thread in the prologue
         }
     }
     __syncthreads();
     unsigned long long pos = sh_base + off;
 
-    // pass B: same traversal, now writing
-    for (uint32_t sw = first; sw < last; sw += kWavesPerBlock) {
-        const uint32_t t0 = tile_begin(sw, p.ntiles, p.nwaves), t1 = tile_begin(sw + 1, p.ntiles, p.nwaves);
-        const int4* __restrict__ src4 = reinterpret_cast<const int4*>(p.seg_in + (size_t)t0 * kTile);
-        const uint32_t cap2 = (t1 - t0) * (kTile / 2);
-        const uint32_t n_in = __builtin_amdgcn_readfirstlane(p.cnt_in[sw]);
-        const uint32_t nslot = (n_in + 1) / 2;
-        for (uint32_t c = 0; c < nslot; c += 64 * U) {
-            int4 q[U];
-            load_slots<U>(q, src4, c, cap2, lane);
+    // pass B: same traversal, now writing; the first group is still in registers
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const uint32_t e = 2 * (c + u * 64 + lane);
+    for (int k = 0; k < K; ++k) {
+        const uint32_t n = __builtin_amdgcn_readfirstlane(l0[k].n);
+        final_emit(p, q0[k], lane, n, eta, cap, pos);
+        for (uint32_t c = 64; c < (n + 1) / 2; c += 64) {
+            const uint32_t i = c + lane;
+            const int4 q = i < l0[k].cap2 ? l0[k].src4[i] : make_int4(0, 0, 0, 0);
+            final_emit(p, q, i, n, eta, cap, pos);
+        }
+    }
+    for (uint32_t g = first + K * kWavesPerBlock; g < last; g += K * kWavesPerBlock) {
+        FinalList l[K];
+        int4 q[K];
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int32_t idx = h ? q[u].z : q[u].x;
-                    const float x = __int_as_float(h ? q[u].w : q[u].y);
-                    const bool sel = e + h < n_in && __builtin_fabsf(x) > eta;
-                    const unsigned long long mask = __ballot(sel);
-                    const unsigned long long at = pos + lane_prefix(mask);
-                    if (sel && at < cap) {  // pairs beyond the capacity stay in the residual
-                        p.out_idx[at] = idx;
-                        p.out_val[at] = x;
-                        if (p.residual) p.residual[idx] = 0.0f;
-                    }
-                    pos += (unsigned long long)__popcll(mask);
-                }
+        for (int k = 0; k < K; ++k) {
+            const uint32_t sw = g + k * kWavesPerBlock;
+            l[k] = final_list(p, sw, sw < last);
+            q[k] = (uint32_t)lane < l[k].cap2 ? l[k].src4[lane] : make_int4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const uint32_t n = __builtin_amdgcn_readfirstlane(l[k].n);
+            final_emit(p, q[k], lane, n, eta, cap, pos);
+            for (uint32_t c = 64; c < (n + 1) / 2; c += 64) {
+                const uint32_t i = c + lane;
+                const int4 qq = i < l[k].cap2 ? l[k].src4[i] : make_int4(0, 0, 0, 0);
+                final_emit(p, qq, i, n, eta, cap, pos);
             }
         }
     }
@@ -704,15 +770,16 @@ void launch_fit(const Params& p, hipStream_t s)
     else launch_fit_ec<false>(p, s);
 }
 
-void launch_compact(const Params& p, bool dense, bool stats, hipStream_t s)
+void launch_compact(const Params& p, bool dense, bool stats, bool write, hipStream_t s)
 {
     const dim3 grid(p.nblocks), block(kBlock);
     if (dense) {
-        if (stats) hipLaunchKernelGGL((k_compact<true, true>), grid, block, 0, s, p);
-        else hipLaunchKernelGGL((k_compact<true, false>), grid, block, 0, s, p);
+        if (stats && write) hipLaunchKernelGGL((k_compact<true, true, true>), grid, block, 0, s, p);
+        else if (stats) hipLaunchKernelGGL((k_compact<true, true, false>), grid, block, 0, s, p);
+        else hipLaunchKernelGGL((k_compact<true, false, true>), grid, block, 0, s, p);
     } else {
-        if (stats) hipLaunchKernelGGL((k_compact<false, true>), grid, block, 0, s, p);
-        else hipLaunchKernelGGL((k_compact<false, false>), grid, block, 0, s, p);
+        if (stats) hipLaunchKernelGGL((k_compact<false, true, true>), grid, block, 0, s, p);
+        else hipLaunchKernelGGL((k_compact<false, false, true>), grid, block, 0, s, p);
     }
 }
 

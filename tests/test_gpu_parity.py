@@ -30,8 +30,8 @@ SIZES = [1, 2, 63, 255, 256, 257, 1000, 4099, 70_001, 269_722, 1_048_576, 2_100_
 @pytest.mark.parametrize("dist", DISTS)
 def test_small_sizes_all_laws(oracle, d, dist):
     g, r = _inputs(d, 100 + d % 97 + dist, heavy=(dist == 2))
-    for stages, delta in ((1, 0.05), (3, 0.01)):
-        ratios = oracle.schedule(delta, stages, 0.25)
+    for stages, delta, delta1 in ((1, 0.05, 0.25), (3, 0.01, 0.25), (3, 0.002, 0.1)):
+        ratios = oracle.schedule(delta, stages, delta1)
         for res_in in (r, None):
             out = run_gpu(g, res_in, dist, ratios)
             check_parity(oracle, g, res_in, dist, ratios, out, label=f"d={d} dist={dist} M={stages} ec={res_in is not None}")
@@ -255,18 +255,21 @@ def test_profile_hooks():
         prof = sidco.sidco_get_profile()
     finally:
         sidco.sidco_set_profiling(False)
-    assert [n for n, _ in prof] == ["k_fit", "k_compact_dense", "k_final_lists"]
+    # delta_1 = 0.25 keeps too much to be worth writing out: stage 1 only counts and sums, the last stage
+    # reads the dense vector again
+    assert [n for n, _ in prof] == ["k_fit", "k_scan_dense", "k_compact_dense", "k_gather"]
     assert all(0 < ms < 50 for _, ms in prof)
+    seen = {}
     sidco.sidco_set_profiling(True)
     try:
-        run_gpu(g, r, 0, [0.25, 0.2, 0.2])
-        names3 = [n for n, _ in sidco.sidco_get_profile()]
-        run_gpu(g, r, 0, [0.01])
-        names1 = [n for n, _ in sidco.sidco_get_profile()]
+        for ratios in ([0.25, 0.2, 0.2], [0.1, 0.3, 0.3], [0.01]):
+            run_gpu(g, r, 0, ratios)
+            seen[tuple(ratios)] = [n for n, _ in sidco.sidco_get_profile()]
     finally:
         sidco.sidco_set_profiling(False)
-    assert names3 == ["k_fit", "k_compact_dense", "k_compact_lists", "k_final_lists"]
-    assert names1 == ["k_fit", "k_compact_dense", "k_gather"]
+    assert seen[(0.25, 0.2, 0.2)] == ["k_fit", "k_scan_dense", "k_compact_dense", "k_final_lists"]
+    assert seen[(0.1, 0.3, 0.3)] == ["k_fit", "k_compact_dense", "k_compact_lists", "k_final_lists"]
+    assert seen[(0.01,)] == ["k_fit", "k_compact_dense", "k_gather"]
 
 
 @pytest.mark.parametrize("dist", DISTS)
