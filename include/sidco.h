@@ -68,6 +68,10 @@ extern "C" {
 #define SIDCO_ST_STOPPED      (1u << 4) /* an exceedance set was empty: later stages keep eta         */
 #define SIDCO_ST_OVERFLOW     (1u << 5) /* more pairs selected than the output capacity; the excess
                                            stays in the residual and is not reported                  */
+#define SIDCO_ST_FALLBACK     (1u << 6) /* performance only: a stage found the candidate lists of the
+                                           stage before it too short for its threshold and read the
+                                           dense vector again (see sidco_set_speculation); the result
+                                           is the same either way                                     */
 
 /* Per-call diagnostics, filled on the device by the kernels of the last call. */
 typedef struct sidco_diag {
@@ -158,6 +162,20 @@ size_t sidco_workspace_bytes(int64_t d);
  * current device instead of letting it allocate; NULL/0 returns to library
  * allocation.  The buffer must outlive every call that uses it.               */
 int sidco_set_workspace(void *device_ptr, size_t bytes);
+
+/*
+ * Tuning knob, no effect on results.  A stage m < M that reads the dense vector
+ * (Sec. 2.4: every stage after the first only needs the exceedances of the stage
+ * before it) hands the next stage a list of candidates instead of all its
+ * exceedances: the entries above the quantile of stage m's fitted law at
+ * log(1/ratio) = log(1/delta_m) + theta * log(1/delta_{m+1}).  The next stage
+ * uses the list if its own threshold, computed from the exact statistics of all
+ * exceedances, is at or above the candidate threshold, and reads the dense
+ * vector again otherwise (SIDCO_ST_FALLBACK).  theta in [0, 1]; 0 = the list
+ * holds all exceedances of eta_m and is always usable; default 0.5.  Applies
+ * to the calls that follow, on every device.
+ */
+int sidco_set_speculation(double theta);
 
 /* Copy the diagnostics of the last call on the current device to host memory.
  * Synchronises `stream`.                                                      */

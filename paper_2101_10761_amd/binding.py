@@ -14,11 +14,11 @@ LIB_PATH = os.path.join(HERE, "libsidco.so")
 
 MAX_STAGES = 8
 DIST_EXP, DIST_GAMMA_GPD, DIST_GPD = 0, 1, 2
-ST_NONFINITE, ST_VAR_ZERO, ST_GAMMA_S, ST_GAMMA_CLAMP, ST_STOPPED, ST_OVERFLOW = 1, 2, 4, 8, 16, 32
+ST_NONFINITE, ST_VAR_ZERO, ST_GAMMA_S, ST_GAMMA_CLAMP, ST_STOPPED, ST_OVERFLOW, ST_FALLBACK = 1, 2, 4, 8, 16, 32, 64
 
 EXPORTS = [
     "sidco_compress", "sidco_compress_ex", "sidco_fit", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
-    "sidco_workspace_bytes", "sidco_set_workspace", "sidco_read_diag", "sidco_set_profiling",
+    "sidco_workspace_bytes", "sidco_set_workspace", "sidco_set_speculation", "sidco_read_diag", "sidco_set_profiling",
     "sidco_get_profile", "sidco_strerror", "sidco_last_hip_error", "sidco_version", "sidco_shutdown",
 ]
 
@@ -85,6 +85,8 @@ def load() -> C.CDLL:
     lib.sidco_workspace_bytes.restype = C.c_size_t
     lib.sidco_set_workspace.argtypes = [vp, C.c_size_t]
     lib.sidco_set_workspace.restype = C.c_int
+    lib.sidco_set_speculation.argtypes = [C.c_double]
+    lib.sidco_set_speculation.restype = C.c_int
     lib.sidco_read_diag.argtypes = [vp, C.POINTER(Diag)]
     lib.sidco_read_diag.restype = C.c_int
     lib.sidco_set_profiling.argtypes = [C.c_int]
@@ -204,6 +206,11 @@ def sidco_fit_result(stream=None) -> tuple[float, float, float, float]:
     out = (C.c_double * 4)()
     _check(load().sidco_fit_result(_stream_handle(stream), out), "sidco_fit_result")
     return out[0], out[1], out[2], out[3]
+
+
+def sidco_set_speculation(theta: float) -> None:
+    """Position of a dense stage's candidate threshold (0 = lists of all exceedances); see include/sidco.h."""
+    _check(load().sidco_set_speculation(float(theta)), "sidco_set_speculation")
 
 
 def sidco_read_diag(stream=None) -> Diag:

@@ -49,6 +49,7 @@ struct DeviceCtx {
 std::mutex g_mu;
 DeviceCtx g_ctx[kMaxDevices];
 bool g_profiling = false;
+double g_speculation = kSpeculation;
 thread_local char g_hip_msg[256] = "";
 
 int hip_fail(hipError_t e, const char* what)
@@ -171,13 +172,17 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
     mark("k_fit");
 
     // Stage m: threshold from the previous kernel's sums.  Buffers alternate with the kernel number.
-    // `dense` stays true until a stage has materialised survivor lists.
-    bool dense = true;
-    double cum = 1.0;
-    int sel = 0;  // which half of the double buffers the last kernel wrote
+    // `lists` turns true once a stage has written survivor lists (candidates or exceedances).
+    bool lists = false;
+    double cum = 1.0;      // delta_1 ... delta_{m-1}
+    double list_frac = 1;  // expected fraction of the vector in the current lists
+    int sel = 0;           // which half of the double buffers the last kernel wrote
+    bool reverse = true;   // direction of the next dense pass: k_fit walked forward, so the first one walks back
+    const double theta = g_speculation;
     auto bind = [&](int m) {
         const int in = sel, out = sel ^ 1;
         p.stage = m;
+        p.Lw = 0.0;
         p.part_in = h->part[in];
         p.part_out = h->part[out];
         p.cnt_in = h->cnt[in];
@@ -189,23 +194,34 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
         sel = out;
     };
     for (int m = 1; m < M; ++m) {
-        cum *= ratios[m - 1];
         bind(m);
-        if (dense) {
-            const bool write = cum <= kMaterializeBelow;
-            launch_compact(p, /*dense=*/true, /*stats=*/true, write, s);
+        if (!lists) {
+            // dense source: statistics at eta_m, lists of candidates for stage m+1 (see stage_prologue)
+            const double Lw = p.L[m - 1] + theta * p.L[m];
+            const double frac = cum * exp(-Lw);
+            const bool write = frac <= kMaterializeBelow;
+            if (write && theta > 0.0) p.Lw = Lw;
+            p.reverse = reverse;
+            reverse = !reverse;
+            launch_compact(p, /*auto_src=*/false, /*stats=*/true, write, s);
             ++k;
             mark(write ? "k_compact_dense" : "k_scan_dense");
-            if (write) dense = false;
+            if (write) {
+                lists = true;
+                list_frac = frac;
+            }
         } else {
-            launch_compact(p, /*dense=*/false, /*stats=*/true, /*write=*/true, s);
+            launch_compact(p, /*auto_src=*/true, /*stats=*/true, /*write=*/true, s);
             ++k;
             mark("k_compact_lists");
+            list_frac = cum * ratios[m - 1];
         }
+        cum *= ratios[m - 1];
     }
     bind(M);
-    if (dense) {
-        launch_compact(p, /*dense=*/true, /*stats=*/false, /*write=*/true, s);
+    if (!lists) {
+        p.reverse = reverse;
+        launch_compact(p, /*auto_src=*/false, /*stats=*/false, /*write=*/true, s);
         ++k;
         mark("k_compact_dense");
         p.cnt_in = h->cnt[sel];
@@ -215,10 +231,9 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
         ++k;
         mark("k_gather");
     } else {
-        // The lists the last stage reads hold about d * delta_1 * ... * delta_{M-1} pairs.  The host only
-        // knows this expectation; it sizes the grid with it (few blocks = few reservation atomics), and a
-        // wrong guess costs time, never correctness.
-        const double expect = (double)d * cum;
+        // The host only knows the expected length of the lists the last stage reads; it sizes the grid
+        // with it (few blocks = few reservation atomics), and a wrong guess costs time, never correctness.
+        const double expect = (double)d * list_frac;
         // short lists: 4 lists per wave (one group, everything prefetched); long lists: more blocks
         uint32_t grid = expect > 4.0e6 ? 256u : (p.nwaves + 31) / 32;
         if (grid > p.nblocks) grid = p.nblocks;
@@ -397,6 +412,14 @@ int sidco_read_diag(void* stream, sidco_diag* host_out)
         host_out->n[m] = 0;
         host_out->stats[m][0] = host_out->stats[m][1] = host_out->stats[m][2] = 0.0;
     }
+    return SIDCO_OK;
+}
+
+int sidco_set_speculation(double theta)
+{
+    if (!(theta >= 0.0 && theta <= 1.0)) return SIDCO_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_speculation = theta;
     return SIDCO_OK;
 }
 

@@ -14,10 +14,18 @@ constexpr int kWavesPerBlock = kBlock / 64;
 constexpr int kTile = 256;                        // elements per wave step: 64 lanes x float4
 constexpr int kMaxBlocks = 512;                   // 2 blocks per CU on 256 CUs
 constexpr int kMaxWaves = kMaxBlocks * kWavesPerBlock;
-// A non-final stage whose source is still the dense vector materialises its survivor lists only if
-// the expected surviving fraction is at most this; otherwise it only counts and sums, and the next
-// stage scans the dense vector again (4 B/element read, against 16 B per survivor written + read).
-constexpr double kMaterializeBelow = 0.125;
+// A non-final stage whose source is still the dense vector writes survivor lists only if the expected
+// fraction of the vector that goes into them is at most this; otherwise it only counts and sums, and
+// the next stage scans the dense vector again (4 B/element read, against 16 B per list entry written
+// + read, writes being the dearer half).
+constexpr double kMaterializeBelow = 0.16;
+// Default position of a dense stage's candidate threshold between this stage's target ratio and the
+// next one's, on the log scale: log(1/ratio_w) = L_m + kSpeculation * L_{m+1}.  At 0.5 the candidate
+// lists serve the next stage as long as the mean excess over eta_m is at least about half of what the
+// fitted law predicts (a Gaussian tail under an exponential fit still passes).
+constexpr double kSpeculation = 0.5;
+constexpr int kSrcDense = 0;  // a stage kernel reads the dense vector
+constexpr int kSrcAuto = 1;   // ... the producer's lists if they reach down to its threshold, else the dense vector
 static_assert(kMaxBlocks <= kBlock, "one thread per producer block in the prologue reductions");
 
 constexpr int kDistExp = SIDCO_DIST_EXP;
@@ -30,6 +38,7 @@ constexpr uint32_t kStGammaS = SIDCO_ST_GAMMA_S;
 constexpr uint32_t kStGammaClamp = SIDCO_ST_GAMMA_CLAMP;
 constexpr uint32_t kStStopped = SIDCO_ST_STOPPED;
 constexpr uint32_t kStOverflow = SIDCO_ST_OVERFLOW;
+constexpr uint32_t kStFallback = SIDCO_ST_FALLBACK;
 
 // Device-resident state of one call.  Stage m's kernel reads the entries stage m-1 wrote and
 // writes its own, so no entry is read and written inside one kernel.
@@ -37,6 +46,7 @@ struct DevState {
     sidco_diag diag;
     uint32_t status_after[SIDCO_MAX_STAGES + 1];  // status bits accumulated up to and including stage m
     uint32_t frozen_after[SIDCO_MAX_STAGES + 1];  // 1 once an empty exceedance set stopped the refinement
+    float list_eta[SIDCO_MAX_STAGES + 1];         // the lists written by stage m's kernel hold every entry above this
     unsigned long long selected_ctr;              // pairs selected by the last stage (cleared by k_fit)
     uint32_t overflow;                            // 1 if selected_ctr exceeded the output capacity
 };
@@ -52,10 +62,12 @@ struct Params {
     uint32_t nwaves;        // waves that own tiles
     uint32_t nblocks;       // grid size of every kernel of the call
     int vec_ok;             // all dense buffers 16-byte aligned: float4 accesses allowed
+    int reverse;            // a dense stage kernel walks every wave's tiles from the last to the first
     int dist;
     int M;
     int stage;              // 1-based stage a k_compact launch works for
     double L[SIDCO_MAX_STAGES];  // log(1/delta_m)
+    double Lw;              // > L[stage-1]: the lists of this kernel are candidate lists at this log-ratio; else 0
     DevState* st;
     const double* part_in;  // [4][kMaxBlocks] partial sums written by the previous kernel
     double* part_out;
@@ -73,7 +85,7 @@ struct Params {
 };
 
 void launch_fit(const Params& p, hipStream_t s);
-void launch_compact(const Params& p, bool dense, bool stats, bool write, hipStream_t s);
+void launch_compact(const Params& p, bool auto_src, bool stats, bool write, hipStream_t s);
 void launch_final_lists(const Params& p, uint32_t grid_blocks, hipStream_t s);
 void launch_gather(const Params& p, hipStream_t s);
 

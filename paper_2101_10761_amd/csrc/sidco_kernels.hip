@@ -102,101 +102,78 @@ __device__ __forceinline__ double gpd_increment(double mu, double var, double L)
     return (b / a) * expm1(a * L);
 }
 
-// Stage-1 threshold from the sums over all d entries (Corollary 1 / eq. (6); Corollaries 1.2, 1.3).
-// S2 is only used for the GPD law, SL2 (sum of log2 max(|x|, 2^-126)) only for the gamma law.
-__device__ float stage1_eta(int dist, double S1, double S2, double SL2, double d, double L,
-                            uint32_t& status, double stats[3])
+// Stage-1 threshold above 0 for the fitted law at L = log(1/ratio) (Corollary 1 / eq. (6); Corollaries
+// 1.2, 1.3).  `var` is only used for the GPD law, `mulog` only for the gamma law.
+__device__ double stage1_threshold(int dist, double mu, double var, double mulog, double L, uint32_t& status)
 {
-    const double mu = S1 / d;
-    double var = 0.0, mulog = 0.0;
-    bool finite = isfinite(mu);
+    if (dist == kDistExp) return mu * L;  // eq. (6)
     if (dist == kDistGpd) {
-        var = S2 / d - mu * mu;
-        finite = finite && isfinite(var);
-    } else if (dist == kDistGamma) {
-        mulog = (SL2 / d) * 0.6931471805599453094;  // log2 -> natural log
-        finite = finite && isfinite(mulog);
-    }
-    stats[0] = mu;
-    stats[1] = var;
-    stats[2] = mulog;
-    if (!finite) {
-        status |= kStNonfinite;
-        return __builtin_nanf("");
-    }
-    double t;
-    if (dist == kDistExp) {
-        t = mu * L;  // eq. (6)
-    } else if (dist == kDistGpd) {
         if (!(var > 0.0)) {  // all magnitudes equal: limit of the closed form as var -> 0+
             status |= kStVarZero;
-            t = mu;
-        } else {
-            t = gpd_increment(mu, var, L);
+            return mu;
         }
-    } else {
-        // gamma law: closed-form shape from s = log(mean) - mean(log), threshold -beta (log delta + log Gamma(alpha))
-        const double s = log(mu) - mulog;
-        if (!(s > 0.0)) {  // the closed form tends to -infinity here and negative thresholds clamp to 0
-            status |= kStGammaS;
-            t = 0.0;
-        } else {
-            const double a = (3.0 - s + sqrt((s - 3.0) * (s - 3.0) + 24.0 * s)) / (12.0 * s);
-            const double b = mu / a;
-            t = -b * (lgamma(a) - L);
-            if (t < 0.0) {
-                status |= kStGammaClamp;
-                t = 0.0;
-            }
-        }
+        return gpd_increment(mu, var, L);
     }
-    return (float)t;
+    // gamma law: closed-form shape from s = log(mean) - mean(log), threshold -beta (log delta + log Gamma(alpha))
+    const double s = log(mu) - mulog;
+    if (!(s > 0.0)) {  // the closed form tends to -infinity here and negative thresholds clamp to 0
+        status |= kStGammaS;
+        return 0.0;
+    }
+    const double a = (3.0 - s + sqrt((s - 3.0) * (s - 3.0) + 24.0 * s)) / (12.0 * s);
+    const double b = mu / a;
+    const double t = -b * (lgamma(a) - L);
+    if (t < 0.0) {
+        status |= kStGammaClamp;
+        return 0.0;
+    }
+    return t;
 }
 
-// Stage m >= 2 threshold from the sums over the n exceedances of eta_prev
+// Stage m >= 2 increment above eta_{m-1} from the moments of the exceedances
 // (Lemma 2 / eqs. (7)-(9) for the GPD chains, Corollary 2 / eqs. (10)-(11) for the exponential chain).
-__device__ float pot_eta(int dist, unsigned long long n, double Sy, double Syy, float eta_prev, double L,
-                         bool frozen_in, bool& frozen_out, uint32_t& status, double stats[3])
+__device__ double pot_increment(int dist, double ybar, double yvar, double L, uint32_t& status)
 {
-    stats[0] = stats[1] = stats[2] = 0.0;
-    frozen_out = frozen_in;
-    if (frozen_in) return eta_prev;
-    if (n == 0) {  // nothing exceeds eta_prev: keep it for all later stages
-        frozen_out = true;
-        status |= kStStopped;
-        return eta_prev;
+    if (dist == kDistExp) return ybar * L;
+    if (!(yvar > 0.0)) {
+        status |= kStVarZero;
+        return ybar;
     }
-    const double ybar = Sy / (double)n;
-    stats[0] = ybar;
-    double t;
-    if (dist == kDistExp) {
-        t = ybar * L;
-    } else {
-        const double yvar = Syy / (double)n - ybar * ybar;
-        stats[1] = yvar;
-        if (!(yvar > 0.0)) {
-            status |= kStVarZero;
-            t = ybar;
-        } else {
-            t = gpd_increment(ybar, yvar, L);
-        }
-    }
-    return (float)((double)eta_prev + t);
+    return gpd_increment(ybar, yvar, L);
 }
 
-// Prologue of every k_compact: reduce the producer's per-block partial sums (fixed order) and
-// evaluate eta for stage p.stage.  Returns the same value in every thread of every block.
+// What the prologue of a stage's kernel hands to its body.
+struct StageEta {
+    float eta;      // eta_m: the stage's threshold (statistics of the next fit; selection in the last stage)
+    float eta_w;    // the lists this kernel writes hold every entry above eta_w (eta_w >= eta)
+    bool lists_ok;  // the producer's lists hold every entry above eta: they can stand in for the dense vector
+};
+
+// Prologue of every stage kernel: reduce the producer's per-block partial sums (fixed order) and
+// evaluate eta for stage p.stage.  Returns the same values in every thread of every block.
 // Block 0 records the stage in the diagnostics.
-__device__ float stage_prologue(const Params& p, double (*sh)[4])
+//
+// Speculative candidate lists.  A stage that reads the dense vector and keeps a large fraction
+// (delta_1 = 0.25) would have to write a quarter of it as 8-byte pairs, or make the next stage read the
+// dense vector again.  Instead it evaluates the SAME fitted law a second time at a smaller ratio
+// (p.Lw > p.L[m-1], chosen by the host between this stage's and the next stage's target) and writes only
+// the entries above that candidate threshold eta_w.  The next stage's eta is computed from the exact
+// statistics as always; if it lands at or above eta_w (the fitted tail was not lighter than half of
+// what the model says) the candidate lists contain every entry it can select and replace the dense
+// vector, else that kernel falls back to the dense vector.  Either way the result is the same.
+__device__ StageEta stage_prologue(const Params& p, bool auto_src, double (*sh)[4])
 {
     const int m = p.stage;  // 1-based
     const uint32_t t = threadIdx.x;
     const bool have = t < p.nblocks;
+    const double L = p.L[m - 1];
     uint32_t status = 0;
-    double stats[3];
-    float eta;
+    double stats[3] = {0.0, 0.0, 0.0};
+    StageEta r;
     bool frozen = false;
     unsigned long long n;
+    // the producer's list threshold, loaded together with the partial sums (one round trip)
+    const float list_eta = auto_src ? p.st->list_eta[m - 1] : 0.0f;
     if (m == 1) {
         double v[3];
         v[0] = have ? p.part_in[0 * kMaxBlocks + t] : 0.0;
@@ -204,7 +181,31 @@ __device__ float stage_prologue(const Params& p, double (*sh)[4])
         v[2] = (have && p.dist == kDistGamma) ? p.part_in[2 * kMaxBlocks + t] : 0.0;
         block_sum<3>(v, sh);
         n = (unsigned long long)p.d;
-        eta = stage1_eta(p.dist, v[0], v[1], v[2], (double)p.d, p.L[0], status, stats);
+        const double d = (double)p.d;
+        const double mu = v[0] / d;
+        double var = 0.0, mulog = 0.0;
+        bool finite = isfinite(mu);
+        if (p.dist == kDistGpd) {
+            var = v[1] / d - mu * mu;
+            finite = finite && isfinite(var);
+        } else if (p.dist == kDistGamma) {
+            mulog = (v[2] / d) * 0.6931471805599453094;  // log2 -> natural log
+            finite = finite && isfinite(mulog);
+        }
+        stats[0] = mu;
+        stats[1] = var;
+        stats[2] = mulog;
+        if (!finite) {
+            status |= kStNonfinite;
+            r.eta = r.eta_w = __builtin_nanf("");
+        } else {
+            r.eta = r.eta_w = (float)stage1_threshold(p.dist, mu, var, mulog, L, status);
+            if (p.Lw > L) {
+                uint32_t ignored = 0;
+                const float c = (float)stage1_threshold(p.dist, mu, var, mulog, p.Lw, ignored);
+                if (c > r.eta) r.eta_w = c;
+            }
+        }
     } else {
         double v[3];
         v[0] = have ? p.part_in[0 * kMaxBlocks + t] : 0.0;
@@ -213,21 +214,41 @@ __device__ float stage_prologue(const Params& p, double (*sh)[4])
         // the previous stage's record, loaded together with the partial sums (one round trip)
         const float eta_prev = p.st->diag.eta[m - 2];
         status = p.st->status_after[m - 1];
-        const bool frozen_in = p.st->frozen_after[m - 1] != 0;
+        frozen = p.st->frozen_after[m - 1] != 0;
         block_sum<3>(v, sh);
         n = (unsigned long long)v[2];
-        eta = pot_eta(p.dist, n, v[0], v[1], eta_prev, p.L[m - 1], frozen_in, frozen, status, stats);
+        r.eta = r.eta_w = eta_prev;
+        if (!frozen) {
+            if (n == 0) {  // nothing exceeds eta_prev: keep it for all later stages
+                frozen = true;
+                status |= kStStopped;
+            } else {
+                const double ybar = v[0] / (double)n;
+                const double yvar = p.dist == kDistExp ? 0.0 : v[1] / (double)n - ybar * ybar;
+                stats[0] = ybar;
+                stats[1] = yvar;
+                r.eta = r.eta_w = (float)((double)eta_prev + pot_increment(p.dist, ybar, yvar, L, status));
+                if (p.Lw > L) {
+                    uint32_t ignored = 0;
+                    const float c = (float)((double)eta_prev + pot_increment(p.dist, ybar, yvar, p.Lw, ignored));
+                    if (c > r.eta) r.eta_w = c;
+                }
+            }
+        }
     }
+    r.lists_ok = auto_src && (r.eta >= list_eta);  // false for a NaN threshold, which selects nothing anyway
+    if (auto_src && !r.lists_ok) status |= kStFallback;
     if (blockIdx.x == 0 && t == 0) {
-        p.st->diag.eta[m - 1] = eta;
+        p.st->diag.eta[m - 1] = r.eta;
         p.st->diag.n[m - 1] = (int64_t)n;
         p.st->diag.stats[m - 1][0] = stats[0];
         p.st->diag.stats[m - 1][1] = stats[1];
         p.st->diag.stats[m - 1][2] = stats[2];
         p.st->status_after[m] = status;
         p.st->frozen_after[m] = frozen ? 1u : 0u;
+        p.st->list_eta[m] = r.eta_w;
     }
-    return eta;
+    return r;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -339,48 +360,149 @@ __global__ __launch_bounds__(kBlock) void k_fit(Params p)
 }
 
 // ---------------------------------------------------------------------------------------------
-// k_compact: exceedances of eta_m appended to per-wave survivor lists (+ sums for stage m+1)
+// k_compact: statistics of the exceedances of eta_m for the next fit, and per-wave survivor lists
 // ---------------------------------------------------------------------------------------------
 
-// One component of a tile (64 candidates, one per lane).  `run` is the wave's list length so far.
-template <bool STATS, bool WRITE = true>
-__device__ __forceinline__ void emit(bool valid, float x, int32_t idx, float eta, int2* __restrict__ list,
-                                     uint32_t& run, double& sy, double& syy)
+// A wave's survivor list under construction.  Entries are collected in LDS and written out in long
+// contiguous runs: global stores complete in order with the wave's loads, so a store issued between
+// two batches of streaming loads holds the next batch back by its own round trip; few, large,
+// full-line stores cost a fraction of one small partial-line store per tile component (measured:
+// 1.6 M entries out of 25.6 M elements add 9 us as they come and 3 us staged).
+constexpr uint32_t kRingFlush = 512;                // staged entries that trigger a write-out
+constexpr uint32_t kRingSize = kRingFlush + kTile;  // a whole tile can arrive between two checks
+struct ListWriter {
+    int2* __restrict__ list;  // the wave's list in global memory (room for every element of its tiles)
+    int2* ring;               // the wave's staging area in LDS, kRingSize entries
+    uint32_t run;             // entries already written to `list` (wave-uniform)
+    uint32_t fill;            // entries staged in `ring` (wave-uniform, < kRingFlush after list_flush)
+};
+
+__device__ __forceinline__ void list_push(ListWriter& lw, bool keep, int32_t idx, float x, int lane)
+{
+    const unsigned long long mask = __ballot(keep);
+    if (keep) lw.ring[lw.fill + lane_prefix(mask)] = make_int2(idx, __float_as_int(x));
+    lw.fill += (uint32_t)__popcll(mask);
+}
+
+// After at most kTile pushes: writes out kRingFlush entries at a time while that many are staged.
+__device__ __forceinline__ void list_flush(ListWriter& lw, int lane)
+{
+    if (lw.fill < kRingFlush) return;  // wave-uniform
+    const uint32_t whole = lw.fill & ~(kRingFlush - 1);
+#pragma unroll 1
+    for (uint32_t c = 0; c < whole; c += 64) lw.list[lw.run + c + lane] = lw.ring[c + lane];
+    // the leftover (fewer than kRingFlush entries) moves to the front; LDS accesses of a wave stay in order
+    const uint32_t left = lw.fill - whole;
+#pragma unroll 1
+    for (uint32_t c = 0; c < left; c += 64)
+        if (c + lane < left) lw.ring[c + lane] = lw.ring[whole + c + lane];  // source and destination are disjoint
+    lw.run += whole;
+    lw.fill = left;
+}
+
+// writes out what is still staged; returns the list's length
+__device__ __forceinline__ uint32_t list_finish(ListWriter& lw, int lane)
+{
+#pragma unroll 1
+    for (uint32_t c = 0; c < lw.fill; c += 64)
+        if (c + lane < lw.fill) lw.list[lw.run + c + lane] = lw.ring[c + lane];
+    lw.run += lw.fill;
+    lw.fill = 0;
+    return lw.run;
+}
+
+// One component of a tile (64 candidates, one per lane).  Entries above eta_w go to the wave's list;
+// entries above eta_s are counted (`ns`, wave-uniform) and enter the sums of y = |x| - eta_s.
+// Comparisons are strict and fp32; NaN on either side is false.
+template <bool STATS, bool WRITE>
+__device__ __forceinline__ void emit(bool valid, float x, int32_t idx, float eta_s, float eta_w, ListWriter& lw,
+                                     int lane, uint32_t& ns, double& sy, double& syy)
 {
     const float a = __builtin_fabsf(x);
-    const bool sel = valid && (a > eta);  // strict, fp32; NaN on either side is false
-    const unsigned long long mask = __ballot(sel);
-    if (sel) {
-        if (WRITE) list[run + lane_prefix(mask)] = make_int2(idx, __float_as_int(x));
-        if (STATS) {
-            const double y = (double)a - (double)eta;
-            sy += y;
-            syy = __builtin_fma(y, y, syy);
-        }
+    if (WRITE) list_push(lw, valid && (a > eta_w), idx, x, lane);
+    if (STATS) {
+        const bool sel = valid && (a > eta_s);
+        ns += (uint32_t)__popcll(__ballot(sel));
+        const double y = sel ? (double)a - (double)eta_s : 0.0;
+        sy += y;
+        syy = __builtin_fma(y, y, syy);
     }
-    run += (uint32_t)__popcll(mask);
 }
 
 // U complete tiles of the dense vector, already loaded
 template <bool STATS, bool WRITE, int U>
-__device__ __forceinline__ void compact_loaded(const f4 (&a)[U], uint32_t t, int lane, float eta,
-                                               int2* __restrict__ list, uint32_t& run, double& sy, double& syy)
+__device__ __forceinline__ void compact_loaded(const f4 (&a)[U], uint32_t t, int lane, float eta_s, float eta_w,
+                                               ListWriter& lw, uint32_t& ns, double& sy, double& syy)
 {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int32_t i0 = (int32_t)((t + u) * kTile + lane * 4);
-        emit<STATS, WRITE>(true, a[u].x, i0 + 0, eta, list, run, sy, syy);
-        emit<STATS, WRITE>(true, a[u].y, i0 + 1, eta, list, run, sy, syy);
-        emit<STATS, WRITE>(true, a[u].z, i0 + 2, eta, list, run, sy, syy);
-        emit<STATS, WRITE>(true, a[u].w, i0 + 3, eta, list, run, sy, syy);
+        emit<STATS, WRITE>(true, a[u].x, i0 + 0, eta_s, eta_w, lw, lane, ns, sy, syy);
+        emit<STATS, WRITE>(true, a[u].y, i0 + 1, eta_s, eta_w, lw, lane, ns, sy, syy);
+        emit<STATS, WRITE>(true, a[u].z, i0 + 2, eta_s, eta_w, lw, lane, ns, sy, syy);
+        emit<STATS, WRITE>(true, a[u].w, i0 + 3, eta_s, eta_w, lw, lane, ns, sy, syy);
+        if (WRITE) list_flush(lw, lane);
     }
 }
 
+// Plain (L2-allocating) loads: the next pass over the dense vector, if any, starts with what this one read last.
 template <int U>
 __device__ __forceinline__ void load_tiles(f4 (&a)[U], const f4* __restrict__ x4, uint32_t t, int lane)
 {
 #pragma unroll
     for (int u = 0; u < U; ++u) a[u] = x4[(size_t)(t + u) * 64 + lane];
+}
+
+// Tiles [t0, t1) of the dense vector (complete below tf).  p.reverse walks them from the last to the
+// first: the kernel before this one left the end of what it touched last in L2 (32 MB over the chip),
+// and the host alternates the direction from pass to pass so that each pass starts where the one
+// before it stopped (measured: 15.5 us instead of 18.3 us for 102 MB right after k_fit).
+// With `pre`, a0 already holds the first batch of U tiles (see dense_first_batch).
+// Plain load-then-process steps: with 16 waves per CU in flight, a second register buffer per wave
+// gained nothing for the statistics alone and lost 2-3 us once list entries are staged as well (measured).
+__device__ __forceinline__ uint32_t dense_first_batch(const Params& p, uint32_t t0, uint32_t tf, uint32_t U)
+{
+    return p.reverse ? tf - U : t0;
+}
+
+template <bool STATS, bool WRITE, int U>
+__device__ __forceinline__ void compact_dense(const Params& p, f4 (&a0)[U], bool pre, uint32_t t0, uint32_t t1,
+                                              uint32_t tf, int lane, float eta_s, float eta_w, ListWriter& lw,
+                                              uint32_t& ns, double& sy, double& syy)
+{
+    const f4* __restrict__ x4 = reinterpret_cast<const f4*>(p.acc);
+    uint32_t ts = t0;  // tiles [ts, t1) take guarded scalar loads: unaligned buffers, the ragged last tile
+    if (p.vec_ok) {
+        const uint32_t nb = (tf - t0) / U, rem = (tf - t0) - nb * U;
+#pragma unroll 1  // unrolled, the batches' loads pile up in registers and halve the occupancy
+        for (uint32_t k = 0; k < nb; ++k) {
+            const uint32_t t = p.reverse ? tf - (k + 1) * U : t0 + k * U;
+            if (k == 0 && pre) {
+                compact_loaded<STATS, WRITE, U>(a0, t, lane, eta_s, eta_w, lw, ns, sy, syy);
+            } else {
+                f4 a[U];
+                load_tiles<U>(a, x4, t, lane);
+                compact_loaded<STATS, WRITE, U>(a, t, lane, eta_s, eta_w, lw, ns, sy, syy);
+            }
+        }
+        const uint32_t tr = p.reverse ? t0 : t0 + nb * U;
+        for (uint32_t t = tr; t < tr + rem; ++t) {
+            f4 a[1];
+            load_tiles<1>(a, x4, t, lane);
+            compact_loaded<STATS, WRITE, 1>(a, t, lane, eta_s, eta_w, lw, ns, sy, syy);
+        }
+        ts = tf;
+    }
+    for (uint32_t t = ts; t < t1; ++t) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t i = (int64_t)t * kTile + lane * 4 + j;
+            const bool valid = i < p.d;
+            const float v = valid ? p.acc[i] : 0.0f;
+            emit<STATS, WRITE>(valid, v, (int32_t)i, eta_s, eta_w, lw, lane, ns, sy, syy);
+        }
+        if (WRITE) list_flush(lw, lane);
+    }
 }
 
 // Two list entries per lane and load (16 B): slot i of a wave's list holds entries 2i and 2i+1.
@@ -399,25 +521,29 @@ __device__ __forceinline__ void load_slots(int4 (&q)[U], const int4* __restrict_
 
 template <bool STATS, int U>
 __device__ __forceinline__ void compact_slots(const int4 (&q)[U], uint32_t c, uint32_t n_in, int lane, float eta,
-                                              int2* __restrict__ list, uint32_t& run, double& sy, double& syy)
+                                              ListWriter& lw, uint32_t& ns, double& sy, double& syy)
 {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t e = 2 * (c + u * 64 + lane);
-        emit<STATS>(e < n_in, __int_as_float(q[u].y), q[u].x, eta, list, run, sy, syy);
-        emit<STATS>(e + 1 < n_in, __int_as_float(q[u].w), q[u].z, eta, list, run, sy, syy);
+        emit<STATS, true>(e < n_in, __int_as_float(q[u].y), q[u].x, eta, eta, lw, lane, ns, sy, syy);
+        emit<STATS, true>(e + 1 < n_in, __int_as_float(q[u].w), q[u].z, eta, eta, lw, lane, ns, sy, syy);
+        if (u & 1) list_flush(lw, lane);  // every 4 components = at most kTile entries
     }
+    static_assert(U % 2 == 0, "flush check after every second slot group");
 }
 
-// DENSE: the source is the dense vector, else the previous survivor lists.  STATS: form the sums for
-// the next stage's fit.  WRITE: append the exceedances to this stage's lists; a dense stage that keeps
-// a large fraction (delta_1 = 0.25) only counts and sums, and the next stage reads the dense vector
-// again, which moves fewer bytes than writing and re-reading 8-byte pairs for a quarter of it.
-template <bool DENSE, bool STATS, bool WRITE>
-__global__ __launch_bounds__(kBlock) void k_compact(Params p)
+// SRC: kSrcDense - the source is the dense vector; kSrcAuto - the producer's survivor lists if they
+// hold every entry above this stage's threshold (see stage_prologue), else the dense vector.
+// STATS: form the sums for the next stage's fit.  WRITE: append the entries above eta_w to this
+// stage's lists (eta_w = eta_m, or a candidate threshold above it for a dense source); a dense stage
+// whose candidates would still be a large fraction only counts and sums.
+template <int SRC, bool STATS, bool WRITE>
+__global__ __launch_bounds__(kBlock, 4) void k_compact(Params p)
 {
     __shared__ double sh[kWavesPerBlock][4];
     __shared__ uint32_t sh_cnt[kWavesPerBlock];
+    __shared__ int2 ring[WRITE ? kWavesPerBlock : 1][kRingSize];
     constexpr int U = 4;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     const uint32_t w = blockIdx.x * kWavesPerBlock + wib;
@@ -428,54 +554,33 @@ __global__ __launch_bounds__(kBlock) void k_compact(Params p)
 
     // The first loads of the body do not depend on the threshold: issue them before the prologue so
     // that their latency overlaps the reduction of the partial sums.
-    const f4* __restrict__ x4 = reinterpret_cast<const f4*>(p.acc);
     const int4* __restrict__ src4 = reinterpret_cast<const int4*>(p.seg_in + (size_t)t0 * kTile);
     const uint32_t cap2 = (t1 - t0) * (kTile / 2);
     f4 a0[U];
     int4 q0[U];
     uint32_t n_in = 0;
-    const bool pre_dense = DENSE && active && p.vec_ok && t0 + U <= tf;
-    if (DENSE) {
-        if (pre_dense) load_tiles<U>(a0, x4, t0, lane);
+    const bool pre_dense = SRC == kSrcDense && active && p.vec_ok && t0 + U <= tf;
+    if (SRC == kSrcDense) {
+        if (pre_dense) load_tiles<U>(a0, reinterpret_cast<const f4*>(p.acc), dense_first_batch(p, t0, tf, U), lane);
     } else if (active) {
         n_in = p.cnt_in[w];
         load_slots<U>(q0, src4, 0, cap2, lane);
     }
 
-    const float eta = stage_prologue(p, sh);
+    const StageEta se = stage_prologue(p, SRC == kSrcAuto, sh);
+    const float eta = se.eta;
 
-    uint32_t run = 0;
+    uint32_t run = 0, ns = 0;
     double sy = 0.0, syy = 0.0;
     if (active) {
-        int2* __restrict__ list = p.seg_out + (size_t)t0 * kTile;  // room for every element of the wave's tiles
-        if (DENSE) {
-            uint32_t t = t0;
-            if (pre_dense) {
-                compact_loaded<STATS, WRITE, U>(a0, t, lane, eta, list, run, sy, syy);
-                t += U;
-            }
-            if (p.vec_ok) {
-                for (; t + U <= tf; t += U) {
-                    f4 a[U];
-                    load_tiles<U>(a, x4, t, lane);
-                    compact_loaded<STATS, WRITE, U>(a, t, lane, eta, list, run, sy, syy);
-                }
-                for (; t < tf; ++t) {
-                    f4 a[1];
-                    load_tiles<1>(a, x4, t, lane);
-                    compact_loaded<STATS, WRITE, 1>(a, t, lane, eta, list, run, sy, syy);
-                }
-            }
-            // unaligned buffers and the ragged last tile: guarded scalar loads
-            for (; t < t1; ++t) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int64_t i = (int64_t)t * kTile + lane * 4 + j;
-                    const bool valid = i < p.d;
-                    const float v = valid ? p.acc[i] : 0.0f;
-                    emit<STATS, WRITE>(valid, v, (int32_t)i, eta, list, run, sy, syy);
-                }
-            }
+        ListWriter lw;
+        lw.list = p.seg_out + (size_t)t0 * kTile;  // room for every element of the wave's tiles
+        lw.ring = ring[WRITE ? wib : 0];
+        lw.run = lw.fill = 0;
+        if (SRC == kSrcDense || !se.lists_ok) {
+            // a fallback from unusable lists writes this stage's exceedances, not candidates
+            const float eta_w = SRC == kSrcDense ? se.eta_w : eta;
+            compact_dense<STATS, WRITE, U>(p, a0, pre_dense, t0, t1, tf, lane, eta, eta_w, lw, ns, sy, syy);
         } else {
             n_in = __builtin_amdgcn_readfirstlane(n_in);
             const uint32_t nslot = (n_in + 1) / 2;
@@ -485,14 +590,17 @@ __global__ __launch_bounds__(kBlock) void k_compact(Params p)
             for (uint32_t c = 0; c < nslot; c += 2 * S) {
                 const bool more1 = c + S < nslot;
                 if (more1) load_slots<U>(q1, src4, c + S, cap2, lane);
-                compact_slots<STATS, U>(q0, c, n_in, lane, eta, list, run, sy, syy);
+                compact_slots<STATS, U>(q0, c, n_in, lane, eta, lw, ns, sy, syy);
                 if (c + 2 * S < nslot) load_slots<U>(q0, src4, c + 2 * S, cap2, lane);
-                if (more1) compact_slots<STATS, U>(q1, c + S, n_in, lane, eta, list, run, sy, syy);
+                if (more1) compact_slots<STATS, U>(q1, c + S, n_in, lane, eta, lw, ns, sy, syy);
             }
         }
+        if (WRITE) run = list_finish(lw, lane);
         if (lane == 0) p.cnt_out[w] = run;
     }
-    if (lane == 0) sh_cnt[wib] = run;
+    // per block: the number of exceedances of eta_m (the n of the next fit), or, without statistics
+    // (dense last stage), the number of list entries (k_gather's prefix)
+    if (lane == 0) sh_cnt[wib] = STATS ? ns : run;
     if (STATS) {
         sy = wave_sum(sy);
         syy = wave_sum(syy);
@@ -519,7 +627,9 @@ __global__ __launch_bounds__(kBlock) void k_compact(Params p)
 
 // ---------------------------------------------------------------------------------------------
 // k_final_lists: last stage when its source is a set of survivor lists (M >= 2).
-// Threshold eta_M, selection, contiguous output and residual update in one kernel.  The lists are
+// Threshold eta_M, selection, contiguous output and residual update in one kernel.  If the lists are
+// candidate lists that turn out not to reach down to eta_M (see stage_prologue), the same two passes
+// run over the dense vector instead: slower, same result.  The lists are
 // short by now and the kernel is bound by memory latency, not bandwidth: every wave takes up to
 // kFinalGroup lists at a time and issues all their loads together, before the prologue, so that the
 // whole kernel is a few dependent round trips.  Each block reserves its output range with ONE atomic
@@ -576,6 +686,40 @@ __device__ __forceinline__ void final_emit(const Params& p, int4 q, uint32_t slo
     }
 }
 
+// Dense fallback of the two passes: the elements of source wave sw's tiles, 64 consecutive ones per step.
+__device__ __forceinline__ uint32_t final_count_dense(const Params& p, uint32_t sw, int lane, float eta)
+{
+    const int64_t b0 = (int64_t)tile_begin(sw, p.ntiles, p.nwaves) * kTile;
+    const int64_t b1 = (int64_t)tile_begin(sw + 1, p.ntiles, p.nwaves) * kTile;
+    uint32_t c = 0;
+    for (int64_t b = b0; b < b1 && b < p.d; b += 64) {
+        const int64_t i = b + lane;
+        const bool sel = i < p.d && __builtin_fabsf(p.acc[i < p.d ? i : 0]) > eta;
+        c += (uint32_t)__popcll(__ballot(sel));
+    }
+    return c;
+}
+
+__device__ __forceinline__ void final_emit_dense(const Params& p, uint32_t sw, int lane, float eta,
+                                                 unsigned long long cap, unsigned long long& pos)
+{
+    const int64_t b0 = (int64_t)tile_begin(sw, p.ntiles, p.nwaves) * kTile;
+    const int64_t b1 = (int64_t)tile_begin(sw + 1, p.ntiles, p.nwaves) * kTile;
+    for (int64_t b = b0; b < b1 && b < p.d; b += 64) {
+        const int64_t i = b + lane;
+        const float x = i < p.d ? p.acc[i] : 0.0f;
+        const bool sel = i < p.d && __builtin_fabsf(x) > eta;
+        const unsigned long long mask = __ballot(sel);
+        const unsigned long long at = pos + lane_prefix(mask);
+        if (sel && at < cap) {  // pairs beyond the capacity stay in the residual
+            p.out_idx[at] = (int32_t)i;
+            p.out_val[at] = x;
+            if (p.residual) p.residual[i] = 0.0f;
+        }
+        pos += (unsigned long long)__popcll(mask);
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void k_final_lists(Params p)
 {
     __shared__ double sh[kWavesPerBlock][4];
@@ -599,10 +743,14 @@ __global__ __launch_bounds__(kBlock) void k_final_lists(Params p)
         q0[k] = (uint32_t)lane < l0[k].cap2 ? l0[k].src4[lane] : make_int4(0, 0, 0, 0);
     }
 
-    const float eta = stage_prologue(p, sh);
+    const StageEta se = stage_prologue(p, true, sh);
+    const float eta = se.eta;
 
     // pass A: count
     uint32_t mine = 0;
+    if (!se.lists_ok) {
+        for (uint32_t sw = first; sw < last; sw += kWavesPerBlock) mine += final_count_dense(p, sw, lane, eta);
+    } else {
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const uint32_t n = __builtin_amdgcn_readfirstlane(l0[k].n);
@@ -633,6 +781,7 @@ __global__ __launch_bounds__(kBlock) void k_final_lists(Params p)
             }
         }
     }
+    }
     if (lane == 0) sh_cnt[wib] = mine;
     __syncthreads();
     uint32_t off = 0, tot = 0;
@@ -657,6 +806,10 @@ __global__ __launch_bounds__(kBlock) void k_final_lists(Params p)
     unsigned long long pos = sh_base + off;
 
     // pass B: same traversal, now writing; the first group is still in registers
+    if (!se.lists_ok) {
+        for (uint32_t sw = first; sw < last; sw += kWavesPerBlock) final_emit_dense(p, sw, lane, eta, cap, pos);
+        return;
+    }
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         const uint32_t n = __builtin_amdgcn_readfirstlane(l0[k].n);
@@ -770,16 +923,15 @@ void launch_fit(const Params& p, hipStream_t s)
     else launch_fit_ec<false>(p, s);
 }
 
-void launch_compact(const Params& p, bool dense, bool stats, bool write, hipStream_t s)
+void launch_compact(const Params& p, bool auto_src, bool stats, bool write, hipStream_t s)
 {
     const dim3 grid(p.nblocks), block(kBlock);
-    if (dense) {
-        if (stats && write) hipLaunchKernelGGL((k_compact<true, true, true>), grid, block, 0, s, p);
-        else if (stats) hipLaunchKernelGGL((k_compact<true, true, false>), grid, block, 0, s, p);
-        else hipLaunchKernelGGL((k_compact<true, false, true>), grid, block, 0, s, p);
+    if (!auto_src) {
+        if (stats && write) hipLaunchKernelGGL((k_compact<kSrcDense, true, true>), grid, block, 0, s, p);
+        else if (stats) hipLaunchKernelGGL((k_compact<kSrcDense, true, false>), grid, block, 0, s, p);
+        else hipLaunchKernelGGL((k_compact<kSrcDense, false, true>), grid, block, 0, s, p);
     } else {
-        if (stats) hipLaunchKernelGGL((k_compact<false, true, true>), grid, block, 0, s, p);
-        else hipLaunchKernelGGL((k_compact<false, false, true>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((k_compact<kSrcAuto, true, true>), grid, block, 0, s, p);
     }
 }
 

@@ -82,6 +82,9 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert lib.sidco_set_workspace(C.c_void_p(100), 1 << 20) == -6      # misaligned
     assert lib.sidco_set_workspace(C.c_void_p(256), 16) == -6           # too small
     assert lib.sidco_read_diag(None, None) == -1
+    for bad in (-0.1, 1.5, math.nan):
+        assert lib.sidco_set_speculation(C.c_double(bad)) == -9
+    assert lib.sidco_set_speculation(C.c_double(0.5)) == 0
     for code in range(-9, 1):
         assert lib.sidco_strerror(code)
     assert lib.sidco_version() >= 100

@@ -255,21 +255,80 @@ def test_profile_hooks():
         prof = sidco.sidco_get_profile()
     finally:
         sidco.sidco_set_profiling(False)
-    # delta_1 = 0.25 keeps too much to be worth writing out: stage 1 only counts and sums, the last stage
-    # reads the dense vector again
-    assert [n for n, _ in prof] == ["k_fit", "k_scan_dense", "k_compact_dense", "k_gather"]
+    # delta_1 = 0.25 keeps too much to be worth writing out, but the candidates for the next stage
+    # (quantile of the same fit at 0.25 * sqrt(0.04) = 0.05) are: stage 1 sums over the exceedances of
+    # eta_1 and writes the candidate lists, the last stage reads those
+    assert [n for n, _ in prof] == ["k_fit", "k_compact_dense", "k_final_lists"]
     assert all(0 < ms < 50 for _, ms in prof)
     seen = {}
     sidco.sidco_set_profiling(True)
     try:
-        for ratios in ([0.25, 0.2, 0.2], [0.1, 0.3, 0.3], [0.01]):
+        for ratios in ([0.25, 0.2, 0.2], [0.5, 0.5, 0.5, 0.02], [0.1, 0.3, 0.3], [0.01]):
             run_gpu(g, r, 0, ratios)
             seen[tuple(ratios)] = [n for n, _ in sidco.sidco_get_profile()]
     finally:
         sidco.sidco_set_profiling(False)
-    assert seen[(0.25, 0.2, 0.2)] == ["k_fit", "k_scan_dense", "k_compact_dense", "k_final_lists"]
+    assert seen[(0.25, 0.2, 0.2)] == ["k_fit", "k_compact_dense", "k_compact_lists", "k_final_lists"]
+    assert seen[(0.5, 0.5, 0.5, 0.02)] == ["k_fit", "k_scan_dense", "k_scan_dense", "k_compact_dense", "k_final_lists"]
     assert seen[(0.1, 0.3, 0.3)] == ["k_fit", "k_compact_dense", "k_compact_lists", "k_final_lists"]
     assert seen[(0.01,)] == ["k_fit", "k_compact_dense", "k_gather"]
+
+
+def _light_tailed(d, seed, lo=0.0, hi=2e-3):
+    """Magnitudes uniform on [lo, hi]: far lighter-tailed than an exponential law.  On [0, 2e-3] the mean is
+    1e-3, the exponential eta_1 at delta_1 = 0.25 is 1.386e-3, and the mean excess over it is 0.31e-3, under
+    a third of the 1e-3 the fit predicts: the next threshold lands below the candidate threshold.  On a narrow
+    band such as [0.9e-3, 1.1e-3] nothing exceeds eta_1 at all."""
+    rng = np.random.default_rng(seed)
+    g = (rng.uniform(lo, hi, size=d) * rng.choice([-1.0, 1.0], size=d)).astype(np.float32)
+    return g
+
+
+@pytest.mark.parametrize("dist", DISTS)
+@pytest.mark.parametrize("ratios", [[0.25, 0.2], [0.25, 0.2, 0.2], [0.05, 0.2]])
+@pytest.mark.parametrize("band", [(0.0, 2e-3), (0.9e-3, 1.1e-3)])
+def test_candidate_lists_fall_back_to_the_dense_vector(oracle, dist, ratios, band):
+    """Speculative candidate lists (see sidco_set_speculation) never change the result: on light-tailed input
+    the next threshold lands below the candidate threshold and the stage reads the dense vector again; on
+    well-modelled input it does not; with theta = 0 it never does.  Parity holds in all three."""
+    import paper_2101_10761_amd as sidco
+    d = 700_001
+    g = _light_tailed(d, 51, *band)
+    r = np.zeros(d, np.float32)
+    out = run_gpu(g, r, dist, ratios)
+    check_parity(oracle, g, r, dist, ratios, out, label=f"light tail dist={dist} {ratios}")
+    if dist == 0:   # exponential chain: the mean excess is under half of the model's, or nothing exceeds eta_1
+        assert out.status & sidco.ST_FALLBACK
+        if band[0] == 0.0 and ratios[0] == 0.25:
+            assert out.count > 0.01 * d
+    g2, r2 = _inputs(d, 52, heavy=(dist == 2))
+    out2 = run_gpu(g2, r2, dist, ratios)
+    check_parity(oracle, g2, r2, dist, ratios, out2, label=f"modelled dist={dist} {ratios}")
+    if dist != 1:   # Laplace under the exponential chain, Student-t under the GPD chain: the law fits
+        assert not out2.status & sidco.ST_FALLBACK
+    sidco.sidco_set_speculation(0.0)
+    try:
+        out3 = run_gpu(g, r, dist, ratios)
+        check_parity(oracle, g, r, dist, ratios, out3, label=f"theta=0 dist={dist} {ratios}")
+        assert not out3.status & sidco.ST_FALLBACK
+        np.testing.assert_array_equal(np.sort(out3.idx), np.sort(out.idx))
+        assert out3.etas.tobytes() == out.etas.tobytes()
+        sidco.sidco_set_speculation(1.0)
+        out4 = run_gpu(g2, r2, dist, ratios)
+        check_parity(oracle, g2, r2, dist, ratios, out4, label=f"theta=1 dist={dist} {ratios}")
+        np.testing.assert_array_equal(np.sort(out4.idx), np.sort(out2.idx))
+    finally:
+        sidco.sidco_set_speculation(0.5)
+
+
+def test_fallback_in_the_last_stage_respects_capacity_and_ragged_ends(oracle):
+    """The last stage's dense fallback on an unaligned, ragged vector, with and without output overflow."""
+    d = 333_337
+    g = _light_tailed(d, 53)
+    for cap in (None, 50):
+        out = run_gpu(g, np.zeros(d, np.float32), 0, [0.25, 0.2], cap=cap, grad_offset=1, res_offset=3)
+        check_parity(oracle, g, np.zeros(d, np.float32), 0, [0.25, 0.2], out, capacity=cap, label=f"fallback cap={cap}")
+        assert out.status & 64 and out.selected > 0.02 * d
 
 
 @pytest.mark.parametrize("dist", DISTS)
