@@ -127,6 +127,27 @@ int sidco_compress_ex(void *stream, const float *grad, float *residual, int64_t 
                       int32_t *out_count, float *out_eta);
 
 /*
+ * Exact Top-k by magnitude, the operator the paper compares its threshold
+ * estimators with (Sec. 1: Top-k keeps the k entries of largest magnitude; a GPU
+ * finds them with a radix select; footnote of Sec. 2.3: C_eta equals Top-k at
+ * k = khat).  Same buffers and error-compensation semantics as sidco_compress:
+ * acc = grad + residual is formed and stored back into residual (App. B.2), the
+ * k entries of largest |acc| are written as (index, value) pairs, and residual
+ * is zeroed at their positions.
+ *
+ *  k          1 <= k <= d
+ *  out_idx, out_val  device, capacity k
+ *  out_count  device, 1 int32: k
+ *  out_kth    device, 1 float: the k-th largest magnitude
+ * A NaN counts as larger than every number (its bit pattern is).  The k-th
+ * largest magnitude, the selected entries above it and all values are
+ * deterministic; which of the entries EQUAL to the k-th largest magnitude
+ * complete the set may differ between runs.  The pairs are not sorted.
+ */
+int sidco_topk(void *stream, const float *grad, float *residual, int64_t d, int64_t k,
+               int32_t *out_idx, float *out_val, int32_t *out_count, float *out_kth);
+
+/*
  * Steps 1-2 alone: the error-compensation add (App. B.2; skipped when residual
  * is NULL) fused with the sums of the stage-1 fit (Corollary 1 / eq. (6),
  * Corollaries 1.2 and 1.3).  This is the kernel that dominates a call; it is

@@ -17,7 +17,7 @@ DIST_EXP, DIST_GAMMA_GPD, DIST_GPD = 0, 1, 2
 ST_NONFINITE, ST_VAR_ZERO, ST_GAMMA_S, ST_GAMMA_CLAMP, ST_STOPPED, ST_OVERFLOW, ST_FALLBACK = 1, 2, 4, 8, 16, 32, 64
 
 EXPORTS = [
-    "sidco_compress", "sidco_compress_ex", "sidco_fit", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
+    "sidco_compress", "sidco_compress_ex", "sidco_topk", "sidco_fit", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
     "sidco_workspace_bytes", "sidco_set_workspace", "sidco_set_speculation", "sidco_read_diag", "sidco_set_profiling",
     "sidco_get_profile", "sidco_strerror", "sidco_last_hip_error", "sidco_version", "sidco_shutdown",
 ]
@@ -73,6 +73,8 @@ def load() -> C.CDLL:
     lib.sidco_compress_ex.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int, f64p, C.c_int, i32p, f32p, C.c_int64,
                                       i32p, f32p]
     lib.sidco_compress_ex.restype = C.c_int
+    lib.sidco_topk.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int64, i32p, f32p, i32p, f32p]
+    lib.sidco_topk.restype = C.c_int
     lib.sidco_fit.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int]
     lib.sidco_fit.restype = C.c_int
     lib.sidco_fit_result.argtypes = [vp, f64p]
@@ -190,6 +192,21 @@ def sidco_compress_ex(grad, residual, dist: int, ratios, out_idx, out_val, out_c
     _check(load().sidco_compress_ex(_stream_handle(stream), _ptr(grad), _ptr(residual), d, dist, r, len(ratios),
                                     _ptr(out_idx), _ptr(out_val), cap, _ptr(out_count), _ptr(out_eta)),
            "sidco_compress_ex")
+
+
+def sidco_topk(grad, residual, k: int, out_idx, out_val, out_count, out_kth, stream=None) -> None:
+    """Enqueues the exact Top-k comparator; see include/sidco.h.  `residual` may be None."""
+    import torch
+    d = grad.numel()
+    _check_tensor(grad, torch.float32, "grad")
+    if residual is not None:
+        _check_tensor(residual, torch.float32, "residual", d)
+    _check_tensor(out_idx, torch.int32, "out_idx", k)
+    _check_tensor(out_val, torch.float32, "out_val", k)
+    _check_tensor(out_count, torch.int32, "out_count", 1)
+    _check_tensor(out_kth, torch.float32, "out_kth", 1)
+    _check(load().sidco_topk(_stream_handle(stream), _ptr(grad), _ptr(residual), d, k, _ptr(out_idx), _ptr(out_val),
+                             _ptr(out_count), _ptr(out_kth)), "sidco_topk")
 
 
 def sidco_fit(grad, residual, dist: int, stream=None) -> None:

@@ -22,6 +22,8 @@ struct WorkspaceHead {
     alignas(256) double part[2][4 * kMaxBlocks];
     alignas(256) uint32_t cnt[2][kMaxWaves];
     alignas(256) uint32_t blk[2][kMaxBlocks];
+    alignas(256) uint32_t topk_hist[3 * kTopkBins];
+    alignas(256) TopkState topk;
 };
 
 constexpr size_t head_bytes() { return (sizeof(WorkspaceHead) + kAlign - 1) / kAlign * kAlign; }
@@ -121,6 +123,18 @@ int current_ctx(DeviceCtx** c)
     return SIDCO_OK;
 }
 
+// HIP events of the per-kernel profile, created on first use
+int make_events(DeviceCtx& c)
+{
+    if (c.ev_made) return SIDCO_OK;
+    for (int i = 0; i <= kMaxKernels; ++i) {
+        hipError_t e = hipEventCreate(&c.ev[i]);
+        if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
+    }
+    c.ev_made = true;
+    return SIDCO_OK;
+}
+
 int run(void* stream, const float* grad, float* residual, int64_t d, int dist, const double* ratios, int M,
         int32_t* out_idx, float* out_val, int64_t out_cap, int32_t* out_count, float* out_eta)
 {
@@ -150,12 +164,9 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
     c.last_cap = out_cap;
 
     const bool prof = g_profiling;
-    if (prof && !c.ev_made) {
-        for (int i = 0; i <= kMaxKernels; ++i) {
-            e = hipEventCreate(&c.ev[i]);
-            if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
-        }
-        c.ev_made = true;
+    if (prof) {
+        rc = make_events(c);
+        if (rc != SIDCO_OK) return rc;
     }
     int k = 0;
     auto mark = [&](const char* name) {
@@ -332,6 +343,87 @@ int sidco_compress(void* stream, const float* grad, float* residual, int64_t d, 
     if (M < 1) return M;
     return run(stream, grad, residual, d, dist, ratios, M, out_idx, out_val, sidco_out_capacity(d, delta), out_count,
                out_eta);
+}
+
+int sidco_topk(void* stream, const float* grad, float* residual, int64_t d, int64_t k, int32_t* out_idx, float* out_val,
+               int32_t* out_count, float* out_kth)
+{
+    if (!grad || !out_idx || !out_val || !out_count || !out_kth) return SIDCO_ERR_NULL;
+    if (d < 1 || d > (int64_t)INT32_MAX) return SIDCO_ERR_SIZE;
+    if (k < 1 || k > d) return SIDCO_ERR_SIZE;
+    if (!aligned4(grad) || !aligned4(residual) || !aligned4(out_idx) || !aligned4(out_val) || !aligned4(out_count) ||
+        !aligned4(out_kth))
+        return SIDCO_ERR_ALIGN;
+    if (residual && (const void*)residual == (const void*)grad) return SIDCO_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx* cp = nullptr;
+    int rc = current_ctx(&cp);
+    if (rc != SIDCO_OK) return rc;
+    DeviceCtx& c = *cp;
+    rc = ensure_workspace(c, head_bytes() + 2 * seg_bytes(d));
+    if (rc != SIDCO_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    WorkspaceHead* h = (WorkspaceHead*)c.ws;
+
+    Params q;
+    fill_common(q, h, grad, residual, d, SIDCO_DIST_EXP);
+    TopkParams p;
+    memset(&p, 0, sizeof(p));
+    p.grad = grad;
+    p.residual = residual;
+    p.acc = q.acc;
+    p.d = d;
+    p.k = k;
+    p.ntiles = q.ntiles;
+    p.nfull = q.nfull;
+    p.nwaves = q.nwaves;
+    p.nblocks = q.nblocks;
+    p.vec_ok = q.vec_ok;
+    p.hist = h->topk_hist;
+    p.st = &h->topk;
+    p.cnt = h->cnt[0];
+    p.seg = (int2*)((char*)c.ws + head_bytes());
+    p.out_idx = out_idx;
+    p.out_val = out_val;
+    p.out_count = out_count;
+    p.out_kth = out_kth;
+
+    const bool prof = g_profiling;
+    if (prof) {
+        rc = make_events(c);
+        if (rc != SIDCO_OK) return rc;
+    }
+    int kn = 0;
+    auto mark = [&](const char* name) {
+        if (!prof) return;
+        if (name) c.prof_name[kn - 1] = name;
+        (void)hipEventRecord(c.ev[kn], s);
+    };
+    mark(nullptr);
+    launch_topk_zero(p, s);
+    ++kn;
+    mark("k_topk_zero");
+    launch_topk_hist(p, s);
+    ++kn;
+    mark("k_topk_hist");
+    launch_topk_compact(p, s);
+    ++kn;
+    mark("k_topk_compact");
+    // the lists hold the k largest entries and the rest of one histogram bin: short, so few blocks
+    uint32_t grid = (p.nwaves + 31) / 32;
+    if ((double)k > 4.0e6) grid = 256;
+    if (grid > p.nblocks) grid = p.nblocks;
+    if (grid < 1) grid = 1;
+    launch_topk_refine(p, grid, s);
+    ++kn;
+    mark("k_topk_refine");
+    launch_topk_final(p, grid, s);
+    ++kn;
+    mark("k_topk_final");
+    c.prof_n = prof ? kn : 0;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    return SIDCO_OK;
 }
 
 int sidco_fit(void* stream, const float* grad, float* residual, int64_t d, int dist)

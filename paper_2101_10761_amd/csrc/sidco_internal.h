@@ -84,6 +84,42 @@ struct Params {
     int64_t out_cap;
 };
 
+// ---- exact Top-k comparator (sidco_topk.hip) ----
+constexpr int kTopkBins = 2048;  // digit 0 = magnitude bits 30..20; digits 1 and 2 have 1024 bins
+
+struct TopkState {
+    uint32_t prefix[3];            // bin of the k-th largest key in digit 0, 1, 2
+    uint32_t k_rem[3];             // rank of that key inside the bin (k_rem[2] = ties still needed)
+    uint32_t kth_key;              // the k-th largest magnitude as its bit pattern
+    uint32_t reserved;
+    unsigned long long gt_ctr;     // output places reserved for entries above the k-th key
+    unsigned long long eq_ctr;     // entries equal to the k-th key seen so far
+};
+
+struct TopkParams {
+    const float* grad;
+    float* residual;        // NULL: memoryless
+    const float* acc;       // residual, else grad
+    int64_t d;
+    int64_t k;
+    uint32_t ntiles, nfull, nwaves, nblocks;
+    int vec_ok;
+    uint32_t* hist;         // [3][kTopkBins]
+    TopkState* st;
+    uint32_t* cnt;          // [kMaxWaves] list lengths
+    int2* seg;              // per-wave lists
+    int32_t* out_idx;
+    float* out_val;
+    int32_t* out_count;
+    float* out_kth;
+};
+
+void launch_topk_zero(const TopkParams& p, hipStream_t s);
+void launch_topk_hist(const TopkParams& p, hipStream_t s);
+void launch_topk_compact(const TopkParams& p, hipStream_t s);
+void launch_topk_refine(const TopkParams& p, uint32_t grid, hipStream_t s);
+void launch_topk_final(const TopkParams& p, uint32_t grid, hipStream_t s);
+
 void launch_fit(const Params& p, hipStream_t s);
 void launch_compact(const Params& p, bool auto_src, bool stats, bool write, hipStream_t s);
 void launch_final_lists(const Params& p, uint32_t grid_blocks, hipStream_t s);

@@ -79,6 +79,13 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert g(None, ok, None, 1000, 0, r2, 9, ok, ok, 100, ok, ok) == -4
     assert g(None, ok, None, 1000, 0, r2, 2, ok, ok, 0, ok, ok) == -2
     assert g(None, ok, None, 1000, 0, (C.c_double * 2)(0.25, 1.0), 2, ok, ok, 100, ok, ok) == -3
+    t = lib.sidco_topk
+    assert t(None, None, None, 1000, 10, ok, ok, ok, ok) == -1
+    assert t(None, ok, None, 1000, 10, ok, ok, ok, None) == -1
+    assert t(None, ok, None, 0, 10, ok, ok, ok, ok) == -2
+    assert t(None, ok, None, 1000, 0, ok, ok, ok, ok) == -2 and t(None, ok, None, 1000, 1001, ok, ok, ok, ok) == -2
+    assert t(None, C.c_void_p(258), None, 1000, 10, ok, ok, ok, ok) == -8
+    assert t(None, ok, ok, 1000, 10, ok, ok, ok, ok) == -9
     assert lib.sidco_set_workspace(C.c_void_p(100), 1 << 20) == -6      # misaligned
     assert lib.sidco_set_workspace(C.c_void_p(256), 16) == -6           # too small
     assert lib.sidco_read_diag(None, None) == -1
