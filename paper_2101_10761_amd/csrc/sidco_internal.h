@@ -24,8 +24,12 @@ constexpr double kMaterializeBelow = 0.16;
 // lists serve the next stage as long as the mean excess over eta_m is at least about half of what the
 // fitted law predicts (a Gaussian tail under an exponential fit still passes).
 constexpr double kSpeculation = 0.5;
-constexpr int kSrcDense = 0;  // a stage kernel reads the dense vector
-constexpr int kSrcAuto = 1;   // ... the producer's lists if they reach down to its threshold, else the dense vector
+// A call that repeats the previous call's shape on the device (same d, law and ratios: the next
+// training iteration) starts from where the previous call's next threshold really fell on that scale,
+// minus this margin, and never above kHintMax: gradients change slowly from one iteration to the
+// next, so the candidate lists shrink to a little more than the next stage's exceedances.
+constexpr float kHintMargin = 0.1f;
+constexpr float kHintMax = 0.95f;
 static_assert(kMaxBlocks <= kBlock, "one thread per producer block in the prologue reductions");
 
 constexpr int kDistExp = SIDCO_DIST_EXP;
@@ -40,6 +44,13 @@ constexpr uint32_t kStStopped = SIDCO_ST_STOPPED;
 constexpr uint32_t kStOverflow = SIDCO_ST_OVERFLOW;
 constexpr uint32_t kStFallback = SIDCO_ST_FALLBACK;
 
+// A fitted law as the kernels use it (see Fit in the kernel source), with the location it sits on.
+struct FitRecord {
+    int gpd;
+    float loc;
+    double s, c, a, b;
+};
+
 // Device-resident state of one call.  Stage m's kernel reads the entries stage m-1 wrote and
 // writes its own, so no entry is read and written inside one kernel.
 struct DevState {
@@ -47,6 +58,10 @@ struct DevState {
     uint32_t status_after[SIDCO_MAX_STAGES + 1];  // status bits accumulated up to and including stage m
     uint32_t frozen_after[SIDCO_MAX_STAGES + 1];  // 1 once an empty exceedance set stopped the refinement
     float list_eta[SIDCO_MAX_STAGES + 1];         // the lists written by stage m's kernel hold every entry above this
+    FitRecord cand_fit[SIDCO_MAX_STAGES + 1];     // stage m wrote candidate lists: its fitted law and location
+    // Survives from call to call (k_fit does not clear it): where stage m+1's threshold fell between
+    // stage m's target ratio and its own, on the log scale of stage m's fitted law; NaN if unknown.
+    float theta_seen[SIDCO_MAX_STAGES + 1];
     unsigned long long selected_ctr;              // pairs selected by the last stage (cleared by k_fit)
     uint32_t overflow;                            // 1 if selected_ctr exceeded the output capacity
 };
@@ -60,14 +75,17 @@ struct Params {
     uint32_t ntiles;        // ceil(d / kTile)
     uint32_t nfull;         // d / kTile: tiles below this index are complete
     uint32_t nwaves;        // waves that own tiles
-    uint32_t nblocks;       // grid size of every kernel of the call
+    uint32_t nblocks;       // grid size of the kernels that read the dense vector
+    uint32_t nprod;         // blocks of the kernel that wrote part_in / blk_in
     int vec_ok;             // all dense buffers 16-byte aligned: float4 accesses allowed
     int reverse;            // a dense stage kernel walks every wave's tiles from the last to the first
     int dist;
     int M;
     int stage;              // 1-based stage a k_compact launch works for
     double L[SIDCO_MAX_STAGES];  // log(1/delta_m)
-    double Lw;              // > L[stage-1]: the lists of this kernel are candidate lists at this log-ratio; else 0
+    float theta;            // > 0: the lists of this kernel are candidate lists (see stage_prologue); else 0
+    int use_hint;           // the previous call on the device had this call's shape: theta_seen applies
+    int prev_cand;          // the producer of this kernel's source lists wrote candidate lists
     DevState* st;
     const double* part_in;  // [4][kMaxBlocks] partial sums written by the previous kernel
     double* part_out;
@@ -121,7 +139,8 @@ void launch_topk_refine(const TopkParams& p, uint32_t grid, hipStream_t s);
 void launch_topk_final(const TopkParams& p, uint32_t grid, hipStream_t s);
 
 void launch_fit(const Params& p, hipStream_t s);
-void launch_compact(const Params& p, bool auto_src, bool stats, bool write, hipStream_t s);
+void launch_compact(const Params& p, bool stats, bool write, hipStream_t s);
+void launch_lists(const Params& p, uint32_t grid_blocks, hipStream_t s);
 void launch_final_lists(const Params& p, uint32_t grid_blocks, hipStream_t s);
 void launch_gather(const Params& p, hipStream_t s);
 

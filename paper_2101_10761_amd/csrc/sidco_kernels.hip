@@ -60,56 +60,81 @@ __device__ __forceinline__ void block_sum(double (&v)[Q], double (*sh)[4])
 // closed-form thresholds (fp64, evaluated redundantly by every thread of every block)
 // ---------------------------------------------------------------------------------------------
 
-// Moment-matched GPD quantile above the location (eqs. (7)-(9); Corollary 1.3):
-// alpha = (1 - mu^2/var)/2, beta = mu (mu^2/var + 1)/2, increment = (beta/alpha)(exp(-alpha log delta) - 1).
-// L = log(1/delta).  alpha == 0 is the exponential limit.
-__device__ __forceinline__ double gpd_increment(double mu, double var, double L)
+// A fitted law, reduced to what its quantile above the stage's location needs:
+//   linear : t(L) = s * L + c   exponential (eqs. (6), (10)-(11)): s = mean, c = 0
+//                               gamma (Corollary 1.2): s = beta, c = -beta * log Gamma(alpha)
+//                               degenerate fits: s = 0, c = the limit of the closed form
+//   gpd    : t(L) = (b / a) * (exp(a L) - 1)   moment-matched GPD (eqs. (7)-(9); Corollary 1.3):
+//                               a = (1 - mu^2/var) / 2, b = mu (mu^2/var + 1) / 2
+// with L = log(1/ratio).  The parameters are computed once in fp64; the stage's own threshold is the
+// fp64 quantile, the candidate threshold (any value at or above it would do) a cheaper fp32 one.
+struct Fit {
+    bool gpd;
+    double s, c, a, b;
+};
+
+__device__ __forceinline__ Fit fit_linear(double s, double c)
 {
-    const double q = (mu * mu) / var;
-    const double a = 0.5 * (1.0 - q);
-    const double b = 0.5 * mu * (q + 1.0);
-    if (a == 0.0) return b * L;
-    return (b / a) * expm1(a * L);
+    Fit f;
+    f.gpd = false;
+    f.s = s;
+    f.c = c;
+    f.a = f.b = 0.0;
+    return f;
 }
 
-// Stage-1 threshold above 0 for the fitted law at L = log(1/ratio) (Corollary 1 / eq. (6); Corollaries
-// 1.2, 1.3).  `var` is only used for the GPD law, `mulog` only for the gamma law.
-__device__ double stage1_threshold(int dist, double mu, double var, double mulog, double L, uint32_t& status)
+__device__ __forceinline__ Fit fit_gpd(double mu, double var, uint32_t& status)
 {
-    if (dist == kDistExp) return mu * L;  // eq. (6)
-    if (dist == kDistGpd) {
-        if (!(var > 0.0)) {  // all magnitudes equal: limit of the closed form as var -> 0+
-            status |= kStVarZero;
-            return mu;
-        }
-        return gpd_increment(mu, var, L);
+    if (!(var > 0.0)) {  // all magnitudes equal: limit of the closed form as var -> 0+
+        status |= kStVarZero;
+        return fit_linear(0.0, mu);
     }
+    const double q = (mu * mu) / var;
+    Fit f;
+    f.gpd = true;
+    f.a = 0.5 * (1.0 - q);
+    f.b = 0.5 * mu * (q + 1.0);
+    f.s = f.c = 0.0;
+    if (f.a == 0.0) return fit_linear(f.b, 0.0);  // the exponential limit
+    return f;
+}
+
+// Stage-1 fit of the chosen law to |acc| (Corollary 1 / eq. (6); Corollaries 1.2, 1.3).
+// `var` is only used for the GPD law, `mulog` only for the gamma law.
+__device__ Fit stage1_fit(int dist, double mu, double var, double mulog, uint32_t& status)
+{
+    if (dist == kDistExp) return fit_linear(mu, 0.0);  // eq. (6)
+    if (dist == kDistGpd) return fit_gpd(mu, var, status);
     // gamma law: closed-form shape from s = log(mean) - mean(log), threshold -beta (log delta + log Gamma(alpha))
     const double s = log(mu) - mulog;
     if (!(s > 0.0)) {  // the closed form tends to -infinity here and negative thresholds clamp to 0
         status |= kStGammaS;
-        return 0.0;
+        return fit_linear(0.0, 0.0);
     }
     const double a = (3.0 - s + sqrt((s - 3.0) * (s - 3.0) + 24.0 * s)) / (12.0 * s);
     const double b = mu / a;
-    const double t = -b * (lgamma(a) - L);
-    if (t < 0.0) {
-        status |= kStGammaClamp;
-        return 0.0;
-    }
-    return t;
+    return fit_linear(b, -b * lgamma(a));
 }
 
-// Stage m >= 2 increment above eta_{m-1} from the moments of the exceedances
+// Stage m >= 2 fit of the exceedances over eta_{m-1}
 // (Lemma 2 / eqs. (7)-(9) for the GPD chains, Corollary 2 / eqs. (10)-(11) for the exponential chain).
-__device__ double pot_increment(int dist, double ybar, double yvar, double L, uint32_t& status)
+__device__ Fit pot_fit(int dist, double ybar, double yvar, uint32_t& status)
 {
-    if (dist == kDistExp) return ybar * L;
-    if (!(yvar > 0.0)) {
-        status |= kStVarZero;
-        return ybar;
-    }
-    return gpd_increment(ybar, yvar, L);
+    if (dist == kDistExp) return fit_linear(ybar, 0.0);
+    return fit_gpd(ybar, yvar, status);
+}
+
+// the stage's threshold above its location, fp64
+__device__ __forceinline__ double fit_quantile(const Fit& f, double L)
+{
+    return f.gpd ? (f.b / f.a) * expm1(f.a * L) : f.s * L + f.c;
+}
+
+// a candidate threshold above the location, fp32 arithmetic (its accuracy does not matter)
+__device__ __forceinline__ float fit_quantile_fast(const Fit& f, double L)
+{
+    if (!f.gpd) return (float)(f.s * L + f.c);
+    return (float)(f.b / f.a) * expm1f((float)(f.a * L));
 }
 
 // What the prologue of a stage's kernel hands to its body.
@@ -125,18 +150,38 @@ struct StageEta {
 //
 // Speculative candidate lists.  A stage that reads the dense vector and keeps a large fraction
 // (delta_1 = 0.25) would have to write a quarter of it as 8-byte pairs, or make the next stage read the
-// dense vector again.  Instead it evaluates the SAME fitted law a second time at a smaller ratio
-// (p.Lw > p.L[m-1], chosen by the host between this stage's and the next stage's target) and writes only
-// the entries above that candidate threshold eta_w.  The next stage's eta is computed from the exact
-// statistics as always; if it lands at or above eta_w (the fitted tail was not lighter than half of
-// what the model says) the candidate lists contain every entry it can select and replace the dense
-// vector, else that kernel falls back to the dense vector.  Either way the result is the same.
+// dense vector again.  Instead it evaluates the SAME fitted law a second time at a smaller ratio,
+// log(1/ratio) = L_m + theta * L_{m+1}, and writes only the entries above that candidate threshold
+// eta_w.  theta is the host's setting (0.5: halfway between this stage's target and the next one's) or,
+// when the previous call on the device had the same shape, the place where that call's next
+// threshold really fell, less a margin.  The next stage's eta is computed from the exact statistics as
+// always; if it lands at or above eta_w the candidate lists contain every entry it can select and
+// replace the dense vector, else that kernel falls back to the dense vector.  Either way the result is
+// the same: only the time depends on the guess.
 __device__ StageEta stage_prologue(const Params& p, bool auto_src, double (*sh)[4])
 {
     const int m = p.stage;  // 1-based
     const uint32_t t = threadIdx.x;
-    const bool have = t < p.nblocks;
+    const bool have = t < p.nprod;  // one thread per block of the kernel that produced the partial sums
     const double L = p.L[m - 1];
+    // candidate threshold of this kernel's lists: log-ratio Lw > L, or none
+    double Lw = 0.0;
+    if (p.theta > 0.0f) {
+        float theta = p.theta;
+        if (p.use_hint) {
+            const float seen = p.st->theta_seen[m];
+            if (seen == seen) theta = fminf(fmaxf(seen - kHintMargin, theta), kHintMax);
+        }
+        Lw = L + (double)theta * p.L[m];
+    }
+    // the producer's candidate fit, for the record of where this stage's threshold falls on its scale
+    FitRecord prev_fit;
+    prev_fit.gpd = 0;
+    prev_fit.loc = 0.0f;
+    prev_fit.s = prev_fit.c = prev_fit.a = prev_fit.b = 0.0;
+    if (auto_src && p.prev_cand && blockIdx.x == 0 && threadIdx.x == 0) prev_fit = p.st->cand_fit[m - 1];
+    Fit fit = fit_linear(0.0, 0.0);
+    float loc = 0.0f;
     uint32_t status = 0;
     double stats[3] = {0.0, 0.0, 0.0};
     StageEta r;
@@ -169,10 +214,15 @@ __device__ StageEta stage_prologue(const Params& p, bool auto_src, double (*sh)[
             status |= kStNonfinite;
             r.eta = r.eta_w = __builtin_nanf("");
         } else {
-            r.eta = r.eta_w = (float)stage1_threshold(p.dist, mu, var, mulog, L, status);
-            if (p.Lw > L) {
-                uint32_t ignored = 0;
-                const float c = (float)stage1_threshold(p.dist, mu, var, mulog, p.Lw, ignored);
+            fit = stage1_fit(p.dist, mu, var, mulog, status);
+            double tq = fit_quantile(fit, L);
+            if (tq < 0.0) {  // only the gamma form can be negative: delta_1 * Gamma(alpha) > 1
+                status |= kStGammaClamp;
+                tq = 0.0;
+            }
+            r.eta = r.eta_w = (float)tq;
+            if (Lw > L) {
+                const float c = fit_quantile_fast(fit, Lw);
                 if (c > r.eta) r.eta_w = c;
             }
         }
@@ -197,10 +247,11 @@ __device__ StageEta stage_prologue(const Params& p, bool auto_src, double (*sh)[
                 const double yvar = p.dist == kDistExp ? 0.0 : v[1] / (double)n - ybar * ybar;
                 stats[0] = ybar;
                 stats[1] = yvar;
-                r.eta = r.eta_w = (float)((double)eta_prev + pot_increment(p.dist, ybar, yvar, L, status));
-                if (p.Lw > L) {
-                    uint32_t ignored = 0;
-                    const float c = (float)((double)eta_prev + pot_increment(p.dist, ybar, yvar, p.Lw, ignored));
+                fit = pot_fit(p.dist, ybar, yvar, status);
+                loc = eta_prev;
+                r.eta = r.eta_w = (float)((double)eta_prev + fit_quantile(fit, L));
+                if (Lw > L) {
+                    const float c = eta_prev + fit_quantile_fast(fit, Lw);
                     if (c > r.eta) r.eta_w = c;
                 }
             }
@@ -217,6 +268,24 @@ __device__ StageEta stage_prologue(const Params& p, bool auto_src, double (*sh)[
         p.st->status_after[m] = status;
         p.st->frozen_after[m] = frozen ? 1u : 0u;
         p.st->list_eta[m] = r.eta_w;
+        if (p.theta > 0.0f) {
+            FitRecord rec;
+            rec.gpd = fit.gpd ? 1 : 0;
+            rec.loc = loc;
+            rec.s = fit.s;
+            rec.c = fit.c;
+            rec.a = fit.a;
+            rec.b = fit.b;
+            p.st->cand_fit[m] = rec;
+        }
+        if (auto_src && p.prev_cand) {
+            // invert the producer's quantile function at this stage's threshold:
+            // eta = loc + Q(L_{m-1} + theta * L_m)  ->  theta
+            const double tq = (double)r.eta - (double)prev_fit.loc;
+            const double Lq = prev_fit.gpd ? log1p(tq * prev_fit.a / prev_fit.b) / prev_fit.a : (tq - prev_fit.c) / prev_fit.s;
+            const float seen = (float)((Lq - p.L[m - 2]) / L);
+            p.st->theta_seen[m - 1] = (frozen || !(fabsf(seen) < 1.0e6f)) ? __builtin_nanf("") : seen;
+        }
     }
     return r;
 }
@@ -284,6 +353,7 @@ __global__ __launch_bounds__(kBlock) void k_fit(Params p)
         if (p.vec_ok) {
             const f4* __restrict__ g4 = reinterpret_cast<const f4*>(p.grad);
             f4* __restrict__ r4 = reinterpret_cast<f4*>(p.residual);
+            // no second register buffer: with 16 waves per CU in flight it gained nothing (measured)
             for (; t + 4 <= tf; t += 4) fit_tiles<DIST, EC, 4>(g4, r4, t, lane, s1, s2, sl, se);
             for (; t < tf; ++t) fit_tiles<DIST, EC, 1>(g4, r4, t, lane, s1, s2, sl, se);
         }
@@ -399,13 +469,8 @@ __device__ __forceinline__ void compact_dense(const Params& p, f4 (&a0)[U], bool
 #pragma unroll 1  // unrolled, the batches' loads pile up in registers and halve the occupancy
         for (uint32_t k = 0; k < nb; ++k) {
             const uint32_t t = p.reverse ? tf - (k + 1) * U : t0 + k * U;
-            if (k == 0 && pre) {
-                compact_loaded<STATS, WRITE, U>(a0, t, lane, eta_s, eta_w, lw, ns, sy, syy);
-            } else {
-                f4 a[U];
-                load_tiles<U>(a, x4, t, lane);
-                compact_loaded<STATS, WRITE, U>(a, t, lane, eta_s, eta_w, lw, ns, sy, syy);
-            }
+            if (!(k == 0 && pre)) load_tiles<U>(a0, x4, t, lane);  // one copy of the loop body: a0 is the only buffer
+            compact_loaded<STATS, WRITE, U>(a0, t, lane, eta_s, eta_w, lw, ns, sy, syy);
         }
         const uint32_t tr = p.reverse ? t0 : t0 + nb * U;
         for (uint32_t t = tr; t < tr + rem; ++t) {
@@ -455,74 +520,14 @@ __device__ __forceinline__ void compact_slots(const int4 (&q)[U], uint32_t c, ui
     static_assert(U % 2 == 0, "flush check after every second slot group");
 }
 
-// SRC: kSrcDense - the source is the dense vector; kSrcAuto - the producer's survivor lists if they
-// hold every entry above this stage's threshold (see stage_prologue), else the dense vector.
-// STATS: form the sums for the next stage's fit.  WRITE: append the entries above eta_w to this
-// stage's lists (eta_w = eta_m, or a candidate threshold above it for a dense source); a dense stage
-// whose candidates would still be a large fraction only counts and sums.
-template <int SRC, bool STATS, bool WRITE>
-__global__ __launch_bounds__(kBlock, 4) void k_compact(Params p)
+// End of a stage kernel: per block, the number of exceedances of eta_m (the n of the next fit) - or,
+// without statistics (dense last stage), the number of list entries (k_gather's prefix) - and the
+// block's partial sums of y and y^2, each in its fixed slot.
+template <bool STATS>
+__device__ __forceinline__ void stage_epilogue(const Params& p, int lane, int wib, uint32_t count, double sy, double syy,
+                                               double (*sh)[4], uint32_t* sh_cnt)
 {
-    __shared__ double sh[kWavesPerBlock][4];
-    __shared__ uint32_t sh_cnt[kWavesPerBlock];
-    __shared__ int2 ring[WRITE ? kWavesPerBlock : 1][kRingSize];
-    constexpr int U = 4;
-    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    const uint32_t w = blockIdx.x * kWavesPerBlock + wib;
-    const bool active = w < p.nwaves;
-    const uint32_t t0 = active ? tile_begin(w, p.ntiles, p.nwaves) : 0;
-    const uint32_t t1 = active ? tile_begin(w + 1, p.ntiles, p.nwaves) : 0;
-    const uint32_t tf = t1 < p.nfull ? t1 : p.nfull;  // tiles [t0,tf) are complete
-
-    // The first loads of the body do not depend on the threshold: issue them before the prologue so
-    // that their latency overlaps the reduction of the partial sums.
-    const int4* __restrict__ src4 = reinterpret_cast<const int4*>(p.seg_in + (size_t)t0 * kTile);
-    const uint32_t cap2 = (t1 - t0) * (kTile / 2);
-    f4 a0[U];
-    int4 q0[U];
-    uint32_t n_in = 0;
-    const bool pre_dense = SRC == kSrcDense && active && p.vec_ok && t0 + U <= tf;
-    if (SRC == kSrcDense) {
-        if (pre_dense) load_tiles<U>(a0, reinterpret_cast<const f4*>(p.acc), dense_first_batch(p, t0, tf, U), lane);
-    } else if (active) {
-        n_in = p.cnt_in[w];
-        load_slots<U>(q0, src4, 0, cap2, lane);
-    }
-
-    const StageEta se = stage_prologue(p, SRC == kSrcAuto, sh);
-    const float eta = se.eta;
-
-    uint32_t run = 0, ns = 0;
-    double sy = 0.0, syy = 0.0;
-    if (active) {
-        ListWriter lw;
-        lw.list = p.seg_out + (size_t)t0 * kTile;  // room for every element of the wave's tiles
-        lw.ring = ring[WRITE ? wib : 0];
-        lw.run = lw.fill = 0;
-        if (SRC == kSrcDense || !se.lists_ok) {
-            // a fallback from unusable lists writes this stage's exceedances, not candidates
-            const float eta_w = SRC == kSrcDense ? se.eta_w : eta;
-            compact_dense<STATS, WRITE, U>(p, a0, pre_dense, t0, t1, tf, lane, eta, eta_w, lw, ns, sy, syy);
-        } else {
-            n_in = __builtin_amdgcn_readfirstlane(n_in);
-            const uint32_t nslot = (n_in + 1) / 2;
-            // two register buffers: the loads of the next step are in flight while this one is compacted
-            constexpr uint32_t S = 64 * U;
-            int4 q1[U];
-            for (uint32_t c = 0; c < nslot; c += 2 * S) {
-                const bool more1 = c + S < nslot;
-                if (more1) load_slots<U>(q1, src4, c + S, cap2, lane);
-                compact_slots<STATS, U>(q0, c, n_in, lane, eta, lw, ns, sy, syy);
-                if (c + 2 * S < nslot) load_slots<U>(q0, src4, c + 2 * S, cap2, lane);
-                if (more1) compact_slots<STATS, U>(q1, c + S, n_in, lane, eta, lw, ns, sy, syy);
-            }
-        }
-        if (WRITE) run = list_finish(lw, lane);
-        if (lane == 0) p.cnt_out[w] = run;
-    }
-    // per block: the number of exceedances of eta_m (the n of the next fit), or, without statistics
-    // (dense last stage), the number of list entries (k_gather's prefix)
-    if (lane == 0) sh_cnt[wib] = STATS ? ns : run;
+    if (lane == 0) sh_cnt[wib] = count;
     if (STATS) {
         sy = wave_sum(sy);
         syy = wave_sum(syy);
@@ -545,6 +550,128 @@ __global__ __launch_bounds__(kBlock, 4) void k_compact(Params p)
         for (int i = 0; i < kWavesPerBlock; ++i) tot += sh[i][threadIdx.x];
         p.part_out[threadIdx.x * kMaxBlocks + blockIdx.x] = tot;
     }
+}
+
+// k_compact: a stage that reads the dense vector.  STATS: form the sums for the next stage's fit.
+// WRITE: append the entries above eta_w to this stage's lists (eta_w = eta_m, or a candidate threshold
+// above it); a stage whose candidates would still be a large fraction only counts and sums.
+template <bool STATS, bool WRITE>
+__global__ __launch_bounds__(kBlock, 4) void k_compact(Params p)
+{
+    __shared__ double sh[kWavesPerBlock][4];
+    __shared__ uint32_t sh_cnt[kWavesPerBlock];
+    __shared__ int2 ring[WRITE ? kWavesPerBlock : 1][kRingSize];
+    constexpr int U = 4;
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    const uint32_t w = blockIdx.x * kWavesPerBlock + wib;
+    const bool active = w < p.nwaves;
+    const uint32_t t0 = active ? tile_begin(w, p.ntiles, p.nwaves) : 0;
+    const uint32_t t1 = active ? tile_begin(w + 1, p.ntiles, p.nwaves) : 0;
+    const uint32_t tf = t1 < p.nfull ? t1 : p.nfull;  // tiles [t0,tf) are complete
+
+    // The first loads of the body do not depend on the threshold: issue them before the prologue so
+    // that their latency overlaps the reduction of the partial sums.
+    f4 a0[U];
+    const bool pre_dense = active && p.vec_ok && t0 + U <= tf;
+    if (pre_dense) load_tiles<U>(a0, reinterpret_cast<const f4*>(p.acc), dense_first_batch(p, t0, tf, U), lane);
+
+    const StageEta se = stage_prologue(p, false, sh);
+
+    uint32_t run = 0, ns = 0;
+    double sy = 0.0, syy = 0.0;
+    if (active) {
+        ListWriter lw;
+        lw.list = p.seg_out + (size_t)t0 * kTile;  // room for every element of the wave's tiles
+        lw.ring = ring[WRITE ? wib : 0];
+        lw.run = lw.fill = 0;
+        compact_dense<STATS, WRITE, U>(p, a0, pre_dense, t0, t1, tf, lane, se.eta, se.eta_w, lw, ns, sy, syy);
+        if (WRITE) run = list_finish(lw, lane);
+        if (lane == 0) p.cnt_out[w] = run;
+    }
+    stage_epilogue<STATS>(p, lane, wib, STATS ? ns : run, sy, syy, sh, sh_cnt);
+}
+
+// ---------------------------------------------------------------------------------------------
+// k_lists: a stage m < M whose source is the producer's survivor lists, or, if those are candidate
+// lists that do not reach down to this stage's threshold (see stage_prologue), the dense vector.
+// The lists are short (a few per cent of the vector at most) and the kernel is bound by latency and
+// by the launch itself, so the host sizes the grid to the expected list volume: block b takes the
+// source lists [b * per_block, (b + 1) * per_block), wave i of it every 8th of those, and writes one
+// output list per source list, in the same per-wave segments.  The first 128 entries of a wave's
+// first kListGroup lists are loaded before the prologue.
+// ---------------------------------------------------------------------------------------------
+constexpr int kListGroup = 4;
+
+__global__ __launch_bounds__(kBlock, 4) void k_lists(Params p)
+{
+    __shared__ double sh[kWavesPerBlock][4];
+    __shared__ uint32_t sh_cnt[kWavesPerBlock];
+    __shared__ int2 ring[kWavesPerBlock][kRingSize];
+    constexpr int K = kListGroup, U = 4;
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    const uint32_t per_block = (p.nwaves + gridDim.x - 1) / gridDim.x;
+    const uint32_t first = blockIdx.x * per_block + wib;
+    const uint32_t last = min(p.nwaves, (blockIdx.x + 1) * per_block);
+
+    uint32_t n0[K];
+    int4 q0[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t sw = first + k * kWavesPerBlock;
+        const bool valid = sw < last;
+        const uint32_t t0 = valid ? tile_begin(sw, p.ntiles, p.nwaves) : 0;
+        const uint32_t t1 = valid ? tile_begin(sw + 1, p.ntiles, p.nwaves) : 0;
+        n0[k] = valid ? p.cnt_in[sw] : 0u;
+        q0[k] = (uint32_t)lane < (t1 - t0) * (kTile / 2)
+                    ? reinterpret_cast<const int4*>(p.seg_in + (size_t)t0 * kTile)[lane]
+                    : make_int4(0, 0, 0, 0);
+    }
+
+    const StageEta se = stage_prologue(p, true, sh);
+    const float eta = se.eta;
+
+    uint32_t ns = 0;
+    double sy = 0.0, syy = 0.0;
+    for (uint32_t g = first, grp = 0; g < last; g += K * kWavesPerBlock, ++grp) {
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const uint32_t sw = g + k * kWavesPerBlock;
+            if (sw >= last) break;  // wave-uniform
+            const uint32_t t0 = tile_begin(sw, p.ntiles, p.nwaves), t1 = tile_begin(sw + 1, p.ntiles, p.nwaves);
+            ListWriter lw;
+            lw.list = p.seg_out + (size_t)t0 * kTile;
+            lw.ring = ring[wib];
+            lw.run = lw.fill = 0;
+            if (!se.lists_ok) {
+                // this stage's exceedances straight from the dense vector
+                f4 unused[U];
+                const uint32_t tf = t1 < p.nfull ? t1 : p.nfull;
+                compact_dense<true, true, U>(p, unused, false, t0, t1, tf, lane, eta, eta, lw, ns, sy, syy);
+            } else {
+                const int4* __restrict__ src4 = reinterpret_cast<const int4*>(p.seg_in + (size_t)t0 * kTile);
+                const uint32_t cap2 = (t1 - t0) * (kTile / 2);
+                const uint32_t n_in = __builtin_amdgcn_readfirstlane(grp == 0 ? n0[k] : p.cnt_in[sw]);
+                const uint32_t nslot = (n_in + 1) / 2;
+                // slots [0, 64): prefetched for the first group
+                {
+                    int4 q = q0[k];
+                    if (grp != 0) q = (uint32_t)lane < cap2 ? src4[lane] : make_int4(0, 0, 0, 0);
+                    const uint32_t e = 2 * lane;
+                    emit<true, true>(e < n_in, __int_as_float(q.y), q.x, eta, eta, lw, lane, ns, sy, syy);
+                    emit<true, true>(e + 1 < n_in, __int_as_float(q.w), q.z, eta, eta, lw, lane, ns, sy, syy);
+                }
+                // the rest, 256 slots per step
+                for (uint32_t c = 64; c < nslot; c += 64 * U) {
+                    int4 q[U];
+                    load_slots<U>(q, src4, c, cap2, lane);
+                    compact_slots<true, U>(q, c, n_in, lane, eta, lw, ns, sy, syy);
+                }
+            }
+            const uint32_t n_out = list_finish(lw, lane);
+            if (lane == 0) p.cnt_out[sw] = n_out;
+        }
+    }
+    stage_epilogue<true>(p, lane, wib, ns, sy, syy, sh, sh_cnt);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -845,16 +972,17 @@ void launch_fit(const Params& p, hipStream_t s)
     else launch_fit_ec<false>(p, s);
 }
 
-void launch_compact(const Params& p, bool auto_src, bool stats, bool write, hipStream_t s)
+void launch_compact(const Params& p, bool stats, bool write, hipStream_t s)
 {
     const dim3 grid(p.nblocks), block(kBlock);
-    if (!auto_src) {
-        if (stats && write) hipLaunchKernelGGL((k_compact<kSrcDense, true, true>), grid, block, 0, s, p);
-        else if (stats) hipLaunchKernelGGL((k_compact<kSrcDense, true, false>), grid, block, 0, s, p);
-        else hipLaunchKernelGGL((k_compact<kSrcDense, false, true>), grid, block, 0, s, p);
-    } else {
-        hipLaunchKernelGGL((k_compact<kSrcAuto, true, true>), grid, block, 0, s, p);
-    }
+    if (stats && write) hipLaunchKernelGGL((k_compact<true, true>), grid, block, 0, s, p);
+    else if (stats) hipLaunchKernelGGL((k_compact<true, false>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((k_compact<false, true>), grid, block, 0, s, p);
+}
+
+void launch_lists(const Params& p, uint32_t grid_blocks, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_lists, dim3(grid_blocks), dim3(kBlock), 0, s, p);
 }
 
 void launch_final_lists(const Params& p, uint32_t grid_blocks, hipStream_t s)

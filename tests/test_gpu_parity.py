@@ -268,9 +268,9 @@ def test_profile_hooks():
             seen[tuple(ratios)] = [n for n, _ in sidco.sidco_get_profile()]
     finally:
         sidco.sidco_set_profiling(False)
-    assert seen[(0.25, 0.2, 0.2)] == ["k_fit", "k_compact_dense", "k_compact_lists", "k_final_lists"]
+    assert seen[(0.25, 0.2, 0.2)] == ["k_fit", "k_compact_dense", "k_lists", "k_final_lists"]
     assert seen[(0.5, 0.5, 0.5, 0.02)] == ["k_fit", "k_scan_dense", "k_scan_dense", "k_compact_dense", "k_final_lists"]
-    assert seen[(0.1, 0.3, 0.3)] == ["k_fit", "k_compact_dense", "k_compact_lists", "k_final_lists"]
+    assert seen[(0.1, 0.3, 0.3)] == ["k_fit", "k_compact_dense", "k_lists", "k_final_lists"]
     assert seen[(0.01,)] == ["k_fit", "k_compact_dense", "k_gather"]
 
 
@@ -302,6 +302,7 @@ def test_candidate_lists_fall_back_to_the_dense_vector(oracle, dist, ratios, ban
         if band[0] == 0.0 and ratios[0] == 0.25:
             assert out.count > 0.01 * d
     g2, r2 = _inputs(d, 52, heavy=(dist == 2))
+    run_gpu(g2[:1000], None, dist, [0.1])     # another shape in between: the next call starts without a hint
     out2 = run_gpu(g2, r2, dist, ratios)
     check_parity(oracle, g2, r2, dist, ratios, out2, label=f"modelled dist={dist} {ratios}")
     if dist != 1:   # Laplace under the exponential chain, Student-t under the GPD chain: the law fits
@@ -314,11 +315,39 @@ def test_candidate_lists_fall_back_to_the_dense_vector(oracle, dist, ratios, ban
         np.testing.assert_array_equal(np.sort(out3.idx), np.sort(out.idx))
         assert out3.etas.tobytes() == out.etas.tobytes()
         sidco.sidco_set_speculation(1.0)
-        out4 = run_gpu(g2, r2, dist, ratios)
+        out4 = run_gpu(g2, r2, dist, ratios)      # a changed theta is a changed shape: no hint either
         check_parity(oracle, g2, r2, dist, ratios, out4, label=f"theta=1 dist={dist} {ratios}")
         np.testing.assert_array_equal(np.sort(out4.idx), np.sort(out2.idx))
     finally:
         sidco.sidco_set_speculation(0.5)
+
+
+@pytest.mark.parametrize("dist", [0, 2])
+def test_repeated_calls_take_the_previous_thresholds_as_a_hint(oracle, dist):
+    """A call that repeats the previous call's shape (same d, law, ratios) places its candidate threshold where
+    the previous call's next threshold fell.  Results never depend on that: the same input gives the same
+    output whatever ran before, and a change of distribution under the same shape falls back to the dense
+    vector and still matches the oracle."""
+    import paper_2101_10761_amd as sidco
+    d = 900_001
+    gh, rh = _inputs(d, 61, heavy=True)
+    gl, rl = _light_tailed(d, 62), np.zeros(d, np.float32)
+    ratios = [0.25, 0.2, 0.2]
+    run_gpu(gh[:1000], None, dist, [0.1])                     # another shape: the next call starts without a hint
+    outs = []
+    for g, r, label in ((gh, rh, "unhinted"), (gh, rh, "hinted"), (gl, rl, "hint from another distribution"),
+                        (gh, rh, "hint from the light-tailed call"), (gh, rh, "hinted again")):
+        out = run_gpu(g, r, dist, ratios)
+        check_parity(oracle, g, r, dist, ratios, out, label=f"{label} dist={dist}")
+        outs.append(out)
+    for o in (outs[1], outs[3], outs[4]):
+        np.testing.assert_array_equal(np.sort(o.idx), np.sort(outs[0].idx))
+        assert o.etas.tobytes() == outs[0].etas.tobytes()
+        np.testing.assert_array_equal(o.residual.view(np.uint32), outs[0].residual.view(np.uint32))
+    assert not outs[0].status & sidco.ST_FALLBACK and not outs[1].status & sidco.ST_FALLBACK
+    assert not outs[4].status & sidco.ST_FALLBACK
+    if dist == 0:
+        assert outs[2].status & sidco.ST_FALLBACK             # exponential fit of uniform magnitudes
 
 
 def test_fallback_in_the_last_stage_respects_capacity_and_ragged_ends(oracle):
