@@ -127,6 +127,42 @@ int sidco_compress_ex(void *stream, const float *grad, float *residual, int64_t 
                       int32_t *out_count, float *out_eta);
 
 /*
+ * Adapt_Stages (Algorithm 1; Sec. 3): the number of stages for the next Q
+ * iterations from the average number of selected elements over the last Q.
+ * One stage fewer if khat_avg > k (1 + eps_high), one more if
+ * khat_avg < k (1 - eps_low), clamped to [1, max_stages].  Pure host function.
+ * Returns the new number of stages, or a negative error code.
+ */
+int sidco_adapt_stages(int stages, double khat_avg, double k, double eps_high, double eps_low,
+                       int max_stages);
+
+/*
+ * The sparsifier with its stage controller (Algorithm 1 as a whole): one
+ * controller per gradient vector, one sidco_controller_compress per training
+ * iteration.  Each call is sidco_compress with the controller's current number
+ * of stages (ratios as described there, with the controller's delta_1); the
+ * device keeps the running count of reported pairs, and every Q-th call
+ * synchronises `stream` once, reads the count back and applies
+ * sidco_adapt_stages with k = delta * d.  All Q counts of a window enter the
+ * average (the pseudo-code drops the count of the adapting iteration yet divides
+ * by Q; Sec. 3 describes an average over the past Q steps).  The paper's
+ * settings are delta_1 = 0.25, eps_high = eps_low = 0.2, Q = 5 (Sec. 4.1).
+ * Other calls of this library on the same device between two calls of a
+ * controller disturb its count.
+ */
+typedef struct sidco_controller sidco_controller;
+int sidco_controller_create(sidco_controller **out, double delta, int dist, int stages,
+                            int max_stages, int Q, double eps_high, double eps_low, double delta1);
+void sidco_controller_destroy(sidco_controller *c);
+int sidco_controller_stages(const sidco_controller *c);             /* current M               */
+int64_t sidco_controller_iteration(const sidco_controller *c);      /* calls made so far       */
+double sidco_controller_last_average(const sidco_controller *c);    /* khat average at the last
+                                                                       adaptation, -1 before it */
+int sidco_controller_compress(sidco_controller *c, void *stream, const float *grad, float *residual,
+                              int64_t d, int32_t *out_idx, float *out_val, int32_t *out_count,
+                              float *out_eta);
+
+/*
  * Exact Top-k by magnitude, the operator the paper compares its threshold
  * estimators with (Sec. 1: Top-k keeps the k entries of largest magnitude; a GPU
  * finds them with a radix select; footnote of Sec. 2.3: C_eta equals Top-k at

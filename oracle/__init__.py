@@ -13,6 +13,8 @@ from .binding import (  # noqa: F401
     ST_GAMMA_CLAMP,
     ST_STOPPED,
     OracleResult,
+    adapt_stages,
+    adaptive_run,
     build,
     compress,
     ec_add,

@@ -62,6 +62,8 @@ def _load():
         lib.sidco_oracle_compress.argtypes = [f32p, f32p, C.c_int64, C.c_int, C.c_int, f64p, f32p,
                                               i32p, f32p, i64p, f32p, f32p, i64p, f64p, u32p]
         lib.sidco_oracle_compress.restype = C.c_int
+        lib.sidco_oracle_adapt_stages.argtypes = [C.c_int, C.c_double, C.c_double, C.c_double, C.c_double, C.c_int]
+        lib.sidco_oracle_adapt_stages.restype = C.c_int
         lib.sidco_oracle_topk.argtypes = [f32p, C.c_int64, C.c_int64, i32p]
         lib.sidco_oracle_topk.restype = C.c_int64
         _lib = lib
@@ -196,3 +198,28 @@ def topk(acc, k):
     idx = np.empty(max(min(k, acc.size), 1), dtype=np.int32)
     n = _load().sidco_oracle_topk(p, acc.size, k, idx.ctypes.data_as(C.POINTER(C.c_int32)))
     return idx[:n].copy()
+
+
+def adapt_stages(M, khat_avg, k, eps_h=0.2, eps_l=0.2, M_max=MAX_STAGES):
+    return _load().sidco_oracle_adapt_stages(M, khat_avg, k, eps_h, eps_l, M_max)
+
+
+def adaptive_run(grads, residual, *, delta, dist, stages, max_stages=MAX_STAGES, Q=5, eps_h=0.2, eps_l=0.2,
+                 delta1=0.25):
+    """Algorithm 1 over consecutive iterations: compress with the current number of stages, carry the residual,
+    and after every Q-th iteration adapt the number of stages from the average count of the window (R16).
+    `grads` is an iterable of gradients.  Returns a list of (stages used, OracleResult) per iteration."""
+    out = []
+    M = stages
+    acc = 0
+    r = None if residual is None else np.array(residual, dtype=np.float32, copy=True)
+    for i, g in enumerate(grads, start=1):
+        res = compress(g, r, ratios=schedule(delta, M, delta1), dist=dist)
+        out.append((M, res))
+        if r is not None:
+            r = res.residual
+        acc += res.count
+        if i % Q == 0:
+            M = adapt_stages(M, acc / Q, delta * g.size, eps_h, eps_l, max_stages)
+            acc = 0
+    return out

@@ -18,6 +18,7 @@
  *   - threshold operator C_eta .......... Sec. 2.3 ("Gradient compression
  *                                         through thresholding")
  *   - stage loop ........................ Algorithm 1, function Sparsify
+ *   - number of stages .................. Algorithm 1, function Adapt_Stages; Sec. 3
  *
  * Readings taken where the paper is silent or inconsistent (each is a reading,
  * not a quotation; they are listed again in the design notes of the build):
@@ -43,6 +44,11 @@
  *       -infinity there and negative thresholds are clamped to 0); an empty
  *       exceedance set stops refining (eta_M = eta_{m-1}).
  *   R10 residual' = acc with zeros at the selected positions.
+ *   R16 the stage controller averages all Q counts of a window (the pseudo-code
+ *       leaves the adapting iteration's count out of the sum yet divides by Q;
+ *       Sec. 3 says "average ... over the past training steps Q"); this lives in
+ *       the Python driver oracle.adaptive_run, the C function is Adapt_Stages as
+ *       printed.
  *
  * Pins (tests/test_oracle_*.py, run without a GPU): hand-worked examples in
  * tests/golden/, scipy quantile functions of the three distributions, exact
@@ -337,6 +343,19 @@ int sidco_oracle_compress(const float *g, float *r, int64_t d, int dist,
     *status = st;
     free(acc_own);
     return 0;
+}
+
+/* Algorithm 1, function Adapt_Stages (and Sec. 3): one stage fewer when the
+ * average number of selected elements is above k (1 + eps_H), one more when it
+ * is below k (1 - eps_L), and the result clamped to [1, M_max].               */
+int sidco_oracle_adapt_stages(int M, double khat_avg, double k, double eps_h,
+                              double eps_l, int M_max)
+{
+    if (khat_avg > k * (1.0 + eps_h)) M = M - 1;
+    if (khat_avg < k * (1.0 - eps_l)) M = M + 1;
+    if (M < 1) M = 1;
+    if (M > M_max) M = M_max;
+    return M;
 }
 
 /* Exact Top-k by magnitude, for tiny cross-checks (footnote of Sec. 2.3:

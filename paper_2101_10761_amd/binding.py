@@ -17,7 +17,9 @@ DIST_EXP, DIST_GAMMA_GPD, DIST_GPD = 0, 1, 2
 ST_NONFINITE, ST_VAR_ZERO, ST_GAMMA_S, ST_GAMMA_CLAMP, ST_STOPPED, ST_OVERFLOW, ST_FALLBACK = 1, 2, 4, 8, 16, 32, 64
 
 EXPORTS = [
-    "sidco_compress", "sidco_compress_ex", "sidco_topk", "sidco_fit", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
+    "sidco_compress", "sidco_compress_ex", "sidco_topk", "sidco_adapt_stages", "sidco_controller_create",
+    "sidco_controller_destroy", "sidco_controller_stages", "sidco_controller_iteration",
+    "sidco_controller_last_average", "sidco_controller_compress", "sidco_fit", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
     "sidco_workspace_bytes", "sidco_set_workspace", "sidco_set_speculation", "sidco_read_diag", "sidco_set_profiling",
     "sidco_get_profile", "sidco_strerror", "sidco_last_hip_error", "sidco_version", "sidco_shutdown",
 ]
@@ -75,6 +77,21 @@ def load() -> C.CDLL:
     lib.sidco_compress_ex.restype = C.c_int
     lib.sidco_topk.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int64, i32p, f32p, i32p, f32p]
     lib.sidco_topk.restype = C.c_int
+    lib.sidco_adapt_stages.argtypes = [C.c_int, C.c_double, C.c_double, C.c_double, C.c_double, C.c_int]
+    lib.sidco_adapt_stages.restype = C.c_int
+    lib.sidco_controller_create.argtypes = [C.POINTER(C.c_void_p), C.c_double, C.c_int, C.c_int, C.c_int, C.c_int,
+                                            C.c_double, C.c_double, C.c_double]
+    lib.sidco_controller_create.restype = C.c_int
+    lib.sidco_controller_destroy.argtypes = [C.c_void_p]
+    lib.sidco_controller_destroy.restype = None
+    lib.sidco_controller_stages.argtypes = [C.c_void_p]
+    lib.sidco_controller_stages.restype = C.c_int
+    lib.sidco_controller_iteration.argtypes = [C.c_void_p]
+    lib.sidco_controller_iteration.restype = C.c_int64
+    lib.sidco_controller_last_average.argtypes = [C.c_void_p]
+    lib.sidco_controller_last_average.restype = C.c_double
+    lib.sidco_controller_compress.argtypes = [C.c_void_p, vp, f32p, f32p, C.c_int64, i32p, f32p, i32p, f32p]
+    lib.sidco_controller_compress.restype = C.c_int
     lib.sidco_fit.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int]
     lib.sidco_fit.restype = C.c_int
     lib.sidco_fit_result.argtypes = [vp, f64p]
@@ -207,6 +224,59 @@ def sidco_topk(grad, residual, k: int, out_idx, out_val, out_count, out_kth, str
     _check_tensor(out_kth, torch.float32, "out_kth", 1)
     _check(load().sidco_topk(_stream_handle(stream), _ptr(grad), _ptr(residual), d, k, _ptr(out_idx), _ptr(out_val),
                              _ptr(out_count), _ptr(out_kth)), "sidco_topk")
+
+
+def sidco_adapt_stages(stages: int, khat_avg: float, k: float, eps_high: float = 0.2, eps_low: float = 0.2,
+                       max_stages: int = MAX_STAGES) -> int:
+    m = load().sidco_adapt_stages(stages, khat_avg, k, eps_high, eps_low, max_stages)
+    if m < 1:
+        raise SidcoError(m, "sidco_adapt_stages")
+    return m
+
+
+class Controller:
+    """Handle of a sidco_controller (the sparsifier with its stage controller); see include/sidco.h."""
+
+    def __init__(self, delta: float, dist: int, stages: int = 1, max_stages: int = MAX_STAGES, Q: int = 5,
+                 eps_high: float = 0.2, eps_low: float = 0.2, delta1: float = 0.25):
+        self._h = C.c_void_p()
+        _check(load().sidco_controller_create(C.byref(self._h), delta, dist, stages, max_stages, Q, eps_high, eps_low,
+                                              delta1), "sidco_controller_create")
+        self.delta = delta
+
+    def close(self):
+        if self._h:
+            load().sidco_controller_destroy(self._h)
+            self._h = C.c_void_p()
+
+    __del__ = close
+
+    @property
+    def stages(self) -> int:
+        return load().sidco_controller_stages(self._h)
+
+    @property
+    def iteration(self) -> int:
+        return load().sidco_controller_iteration(self._h)
+
+    @property
+    def last_average(self) -> float:
+        return load().sidco_controller_last_average(self._h)
+
+    def compress(self, grad, residual, out_idx, out_val, out_count, out_eta, stream=None) -> None:
+        import torch
+        d = grad.numel()
+        _check_tensor(grad, torch.float32, "grad")
+        if residual is not None:
+            _check_tensor(residual, torch.float32, "residual", d)
+        cap = sidco_out_capacity(d, self.delta)
+        _check_tensor(out_idx, torch.int32, "out_idx", cap)
+        _check_tensor(out_val, torch.float32, "out_val", cap)
+        _check_tensor(out_count, torch.int32, "out_count", 1)
+        _check_tensor(out_eta, torch.float32, "out_eta", 1)
+        _check(load().sidco_controller_compress(self._h, _stream_handle(stream), _ptr(grad), _ptr(residual), d,
+                                                _ptr(out_idx), _ptr(out_val), _ptr(out_count), _ptr(out_eta)),
+               "sidco_controller_compress")
 
 
 def sidco_fit(grad, residual, dist: int, stream=None) -> None:

@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <mutex>
+#include <new>
 
 #include "sidco_internal.h"
 
@@ -157,7 +158,7 @@ int make_events(DeviceCtx& c)
 }
 
 int run(void* stream, const float* grad, float* residual, int64_t d, int dist, const double* ratios, int M,
-        int32_t* out_idx, float* out_val, int64_t out_cap, int32_t* out_count, float* out_eta)
+        int32_t* out_idx, float* out_val, int64_t out_cap, int32_t* out_count, float* out_eta, bool acc_reset = true)
 {
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceCtx* cp = nullptr;
@@ -182,6 +183,7 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
     p.out_count = out_count;
     p.out_eta = out_eta;
     p.out_cap = out_cap;
+    p.acc_reset = acc_reset ? 1 : 0;
     c.last_cap = out_cap;
     const double theta = g_speculation;
     bool same_shape = c.sig_d == d && c.sig_dist == dist && c.sig_M == M && c.sig_theta == theta;
@@ -380,6 +382,100 @@ int sidco_compress(void* stream, const float* grad, float* residual, int64_t d, 
                out_eta);
 }
 
+int sidco_adapt_stages(int stages, double khat_avg, double k, double eps_high, double eps_low, int max_stages)
+{
+    if (stages < 1 || max_stages < 1 || max_stages > SIDCO_MAX_STAGES) return SIDCO_ERR_STAGES;
+    if (!(k > 0.0) || !(khat_avg >= 0.0)) return SIDCO_ERR_ARG;
+    if (!(eps_high >= 0.0) || !(eps_low >= 0.0 && eps_low < 1.0)) return SIDCO_ERR_ARG;
+    int M = stages;
+    if (khat_avg > k * (1.0 + eps_high)) M -= 1;
+    if (khat_avg < k * (1.0 - eps_low)) M += 1;
+    if (M < 1) M = 1;
+    if (M > max_stages) M = max_stages;
+    return M;
+}
+
+struct sidco_controller {
+    double delta, delta1, eps_high, eps_low;
+    int dist, stages, max_stages, Q;
+    int64_t iteration;      // calls made so far
+    double last_avg;        // khat average the last adaptation saw (-1 before the first)
+};
+
+int sidco_controller_create(sidco_controller** out, double delta, int dist, int stages, int max_stages, int Q,
+                            double eps_high, double eps_low, double delta1)
+{
+    if (!out) return SIDCO_ERR_NULL;
+    *out = nullptr;
+    if (!(delta > 0.0 && delta < 1.0) || !(delta1 > 0.0 && delta1 < 1.0)) return SIDCO_ERR_DELTA;
+    if (dist != SIDCO_DIST_EXP && dist != SIDCO_DIST_GAMMA_GPD && dist != SIDCO_DIST_GPD) return SIDCO_ERR_DIST;
+    if (max_stages < 1 || max_stages > SIDCO_MAX_STAGES || stages < 1 || stages > max_stages) return SIDCO_ERR_STAGES;
+    if (Q < 1) return SIDCO_ERR_ARG;
+    if (!(eps_high >= 0.0) || !(eps_low >= 0.0 && eps_low < 1.0)) return SIDCO_ERR_ARG;
+    sidco_controller* c = new (std::nothrow) sidco_controller;
+    if (!c) return SIDCO_ERR_ARG;
+    c->delta = delta;
+    c->delta1 = delta1;
+    c->eps_high = eps_high;
+    c->eps_low = eps_low;
+    c->dist = dist;
+    c->stages = stages;
+    c->max_stages = max_stages;
+    c->Q = Q;
+    c->iteration = 0;
+    c->last_avg = -1.0;
+    *out = c;
+    return SIDCO_OK;
+}
+
+void sidco_controller_destroy(sidco_controller* c) { delete c; }
+
+int sidco_controller_stages(const sidco_controller* c) { return c ? c->stages : SIDCO_ERR_NULL; }
+
+int64_t sidco_controller_iteration(const sidco_controller* c) { return c ? c->iteration : (int64_t)SIDCO_ERR_NULL; }
+
+double sidco_controller_last_average(const sidco_controller* c) { return c ? c->last_avg : -1.0; }
+
+int sidco_controller_compress(sidco_controller* c, void* stream, const float* grad, float* residual, int64_t d,
+                              int32_t* out_idx, float* out_val, int32_t* out_count, float* out_eta)
+{
+    if (!c) return SIDCO_ERR_NULL;
+    int rc = check_common(grad, residual, d, c->dist, out_idx, out_val, out_count, out_eta);
+    if (rc != SIDCO_OK) return rc;
+    double ratios[SIDCO_MAX_STAGES];
+    const int M = sidco_stage_ratios(c->delta, c->stages, c->delta1, ratios);
+    if (M < 1) return M;
+    // the count of reported pairs starts over on the first call after an adaptation
+    const bool first_of_window = c->iteration % c->Q == 0;
+    rc = run(stream, grad, residual, d, c->dist, ratios, M, out_idx, out_val, sidco_out_capacity(d, c->delta),
+             out_count, out_eta, first_of_window);
+    if (rc != SIDCO_OK) return rc;
+    c->iteration += 1;
+    if (c->iteration % c->Q != 0) return SIDCO_OK;
+    // every Q-th call: read the count back (the only host synchronisation of the controller) and adapt
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    DevState st;
+    int64_t cap;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        DeviceCtx& ctx = g_ctx[dev];
+        cap = ctx.last_cap;
+        e = hipMemcpyAsync(&st, &((WorkspaceHead*)ctx.ws)->st, sizeof(DevState), hipMemcpyDeviceToHost,
+                           (hipStream_t)stream);
+        if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(controller)");
+        e = hipStreamSynchronize((hipStream_t)stream);
+        if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    }
+    const unsigned long long last = st.selected_ctr < (unsigned long long)cap ? st.selected_ctr : (unsigned long long)cap;
+    const double avg = (double)(st.khat_sum + last) / (double)c->Q;
+    c->last_avg = avg;
+    const int next = sidco_adapt_stages(c->stages, avg, c->delta * (double)d, c->eps_high, c->eps_low, c->max_stages);
+    if (next >= 1) c->stages = next;
+    return SIDCO_OK;
+}
+
 int sidco_topk(void* stream, const float* grad, float* residual, int64_t d, int64_t k, int32_t* out_idx, float* out_val,
                int32_t* out_count, float* out_kth)
 {
@@ -478,6 +574,7 @@ int sidco_fit(void* stream, const float* grad, float* residual, int64_t d, int d
     Params p;
     fill_common(p, h, grad, residual, d, dist);
     p.M = 1;
+    p.acc_reset = 1;
     p.part_out = h->part[0];
     launch_fit(p, (hipStream_t)stream);
     cp->fit_nblocks = p.nblocks;

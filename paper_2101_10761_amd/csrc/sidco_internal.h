@@ -62,6 +62,10 @@ struct DevState {
     // Survives from call to call (k_fit does not clear it): where stage m+1's threshold fell between
     // stage m's target ratio and its own, on the log scale of stage m's fitted law; NaN if unknown.
     float theta_seen[SIDCO_MAX_STAGES + 1];
+    // Adapt_Stages bookkeeping (Algorithm 1): pairs reported by the calls since the controller last
+    // looked, not counting the call in flight; k_fit folds the previous call's count in (or starts over)
+    unsigned long long khat_sum;
+    long long prev_cap;                           // output capacity of the previous call (clips its count)
     unsigned long long selected_ctr;              // pairs selected by the last stage (cleared by k_fit)
     uint32_t overflow;                            // 1 if selected_ctr exceeded the output capacity
 };
@@ -79,6 +83,7 @@ struct Params {
     uint32_t nprod;         // blocks of the kernel that wrote part_in / blk_in
     int vec_ok;             // all dense buffers 16-byte aligned: float4 accesses allowed
     int reverse;            // a dense stage kernel walks every wave's tiles from the last to the first
+    int acc_reset;          // k_fit: start the controller's count of reported pairs over instead of adding to it
     int dist;
     int M;
     int stage;              // 1-based stage a k_compact launch works for

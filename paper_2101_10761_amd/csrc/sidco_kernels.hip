@@ -393,6 +393,11 @@ __global__ __launch_bounds__(kBlock) void k_fit(Params p)
         p.st->status_after[0] = 0;
         p.st->frozen_after[0] = 0;
         p.st->diag.stages = p.M;
+        // Adapt_Stages bookkeeping: the pairs the previous call reported join the running count
+        const unsigned long long prev_sel = p.st->selected_ctr;
+        const unsigned long long prev_cap = (unsigned long long)p.st->prev_cap;
+        p.st->khat_sum = p.acc_reset ? 0ull : p.st->khat_sum + (prev_sel < prev_cap ? prev_sel : prev_cap);
+        p.st->prev_cap = (long long)p.out_cap;
         p.st->selected_ctr = 0;
         p.st->overflow = 0;
         if (p.out_count) *p.out_count = 0;

@@ -120,3 +120,27 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libsidco.so"))
     with pytest.raises(FileNotFoundError):
         binding.load()
+
+
+def test_controller_argument_errors(lib):
+    h = C.c_void_p()
+    f = lib.sidco_controller_create
+    assert f(None, 0.01, 0, 1, 8, 5, 0.2, 0.2, 0.25) == -1
+    assert f(C.byref(h), 0.0, 0, 1, 8, 5, 0.2, 0.2, 0.25) == -3
+    assert f(C.byref(h), 0.01, 7, 1, 8, 5, 0.2, 0.2, 0.25) == -5
+    assert f(C.byref(h), 0.01, 0, 9, 8, 5, 0.2, 0.2, 0.25) == -4
+    assert f(C.byref(h), 0.01, 0, 1, 8, 0, 0.2, 0.2, 0.25) == -9
+    assert f(C.byref(h), 0.01, 0, 1, 8, 5, -0.2, 0.2, 0.25) == -9
+    assert not h.value
+
+
+def test_adapt_stages_matches_the_oracle(lib, oracle):
+    for M in (1, 2, 5, 8):
+        for avg in (0.0, 10.0, 799.0, 800.0, 1000.0, 1200.0, 1201.0, 1e6):
+            for eh, el, mmax in ((0.2, 0.2, 8), (0.1, 0.3, 8), (0.2, 0.2, 5)):
+                if M > mmax:
+                    continue
+                assert sidco.sidco_adapt_stages(M, avg, 1000.0, eh, el, mmax) == oracle.adapt_stages(M, avg, 1000.0, eh, el, mmax)
+    assert lib.sidco_adapt_stages(0, 1.0, 1.0, 0.2, 0.2, 8) == -4
+    assert lib.sidco_adapt_stages(1, 1.0, 0.0, 0.2, 0.2, 8) == -9
+    assert lib.sidco_adapt_stages(1, 1.0, 1.0, 0.2, 1.0, 8) == -9

@@ -36,6 +36,12 @@ MUTANTS = [
     ("residual_not_zeroed", "if (residual) residual[j] = 0.0f;", ""),
     ("ec_add_dropped", "volatile float s = g[j] + r[j];", "volatile float s = g[j];"),
     ("schedule_no_root", "pow(delta / delta1, 1.0 / (double)(stages - 1))", "delta / delta1"),
+    ("adapt_up_down_swapped", "if (khat_avg > k * (1.0 + eps_h)) M = M - 1;", "if (khat_avg > k * (1.0 + eps_h)) M = M + 1;"),
+    ("adapt_low_band_uses_high_eps", "if (khat_avg < k * (1.0 - eps_l)) M = M + 1;",
+     "if (khat_avg < k * (1.0 - eps_h)) M = M + 1;"),
+    ("adapt_non_strict", "if (khat_avg > k * (1.0 + eps_h)) M = M - 1;", "if (khat_avg >= k * (1.0 + eps_h)) M = M - 1;"),
+    ("adapt_no_upper_clamp", "if (M > M_max) M = M_max;", ""),
+    ("adapt_no_lower_clamp", "if (M < 1) M = 1;\n    if (M > M_max)", "if (M > M_max)"),
     ("signed_values_lost", "if (val) val[k] = acc[j];", "if (val) val[k] = fabsf(acc[j]);"),
 ]
 

@@ -409,3 +409,44 @@ def test_error_feedback_conserves_gradient_mass(oracle):
         sent[res.idx] += res.val
         r = res.residual
     np.testing.assert_allclose(sent + r, total, rtol=0, atol=1e-8)
+
+
+# ----------------------------------------------------------------------------------------------
+# Adapt_Stages and the controller loop (Algorithm 1; Sec. 3)
+# ----------------------------------------------------------------------------------------------
+def _golden_adapt_rows():
+    rows = []
+    for line in open(GOLDEN):
+        if line.startswith("A") and "|" in line:
+            f = [x.strip() for x in line.split("|")]
+            rows.append((f[0], int(f[1]), float(f[2]), float(f[3]), float(f[4]), float(f[5]), int(f[6]), int(f[7])))
+    return rows
+
+
+@pytest.mark.parametrize("row", _golden_adapt_rows(), ids=lambda r: r[0])
+def test_golden_adapt_stages(oracle, row):
+    _, M, avg, k, eh, el, mmax, want = row
+    assert oracle.adapt_stages(M, avg, k, eh, el, mmax) == want
+
+
+def test_adaptive_run_settles_inside_the_tolerance_band(oracle):
+    """Sec. 3: the number of stages moves only while the window's average count is outside k (1 +- eps).
+    Gaussian gradients are lighter-tailed than the exponential law, so a single exponential stage selects far
+    too few (Sec. 2.3) and each added stage selects more: the controller adds one stage per window until the
+    average is inside the band, then stays there."""
+    rng = np.random.default_rng(78)
+    d, delta, Q, W = 200_000, 0.001, 5, 7
+    grads = [(rng.standard_normal(d) * 1e-3).astype(np.float32) for _ in range(W * Q)]
+    run = oracle.adaptive_run(grads, np.zeros(d, np.float32), delta=delta, dist=0, stages=1, max_stages=6, Q=Q)
+    Ms = [m for m, _ in run]
+    assert all(len(set(Ms[w * Q:(w + 1) * Q])) == 1 for w in range(W))                   # fixed inside a window
+    k = delta * d
+    avgs = [float(np.mean([r.count for _, r in run[w * Q:(w + 1) * Q]])) for w in range(W)]
+    for w in range(W - 1):  # the step taken after window w is Adapt_Stages on that window's average (all Q counts)
+        assert Ms[(w + 1) * Q] == oracle.adapt_stages(Ms[w * Q], avgs[w], k, 0.2, 0.2, 6)
+    assert avgs[0] < 0.8 * k and Ms[Q] == 2                 # one stage: far below the band, so a stage is added
+    inside = [0.8 * k <= a <= 1.2 * k for a in avgs]
+    first = inside.index(True)
+    assert 1 <= first < W - 1 and all(inside[first:])       # reaches the band and stays inside
+    assert len(set(Ms[first * Q:])) == 1
+    assert Ms[:first * Q + 1:Q] == list(range(1, first + 2))  # one stage more per window on the way
