@@ -163,6 +163,26 @@ int sidco_controller_compress(sidco_controller *c, void *stream, const float *gr
                               float *out_eta);
 
 /*
+ * Decompression / aggregation, the step that follows the sparsifier in the
+ * distributed algorithm (Algorithm 2: the workers' sparsified gradients are
+ * averaged): dense[idx[i]] += scale * val[i] for i < min(*count, capacity).
+ *
+ *  dense     device, d floats, in/out (the caller zeroes it before the first list)
+ *  idx, val  device, one worker's output pairs as sidco_compress wrote them
+ *            (indices distinct within one list)
+ *  count     device, 1 int32: the list's length (so no host read-back is needed)
+ *  capacity  elements idx / val have room for
+ *  scale     e.g. 1/N for the average over N workers
+ * One list per call; lists of several workers are added by consecutive calls on
+ * the stream, so the sum is formed in a fixed order.  An index outside [0, d)
+ * is skipped and remembered; sidco_scatter_check (synchronises `stream`)
+ * returns 1 if that happened since the last check, else 0.
+ */
+int sidco_scatter_add(void *stream, float *dense, int64_t d, const int32_t *idx, const float *val,
+                      const int32_t *count, int64_t capacity, float scale);
+int sidco_scatter_check(void *stream);
+
+/*
  * Exact Top-k by magnitude, the operator the paper compares its threshold
  * estimators with (Sec. 1: Top-k keeps the k entries of largest magnitude; a GPU
  * finds them with a radix select; footnote of Sec. 2.3: C_eta equals Top-k at

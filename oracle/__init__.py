@@ -25,6 +25,7 @@ from .binding import (  # noqa: F401
     gpd_fit,
     moments_all,
     moments_pot,
+    scatter_add,
     schedule,
     select,
     topk,

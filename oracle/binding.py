@@ -64,6 +64,8 @@ def _load():
         lib.sidco_oracle_compress.restype = C.c_int
         lib.sidco_oracle_adapt_stages.argtypes = [C.c_int, C.c_double, C.c_double, C.c_double, C.c_double, C.c_int]
         lib.sidco_oracle_adapt_stages.restype = C.c_int
+        lib.sidco_oracle_scatter_add.argtypes = [f32p, C.c_int64, i32p, f32p, C.c_int64, C.c_float]
+        lib.sidco_oracle_scatter_add.restype = C.c_int64
         lib.sidco_oracle_topk.argtypes = [f32p, C.c_int64, C.c_int64, i32p]
         lib.sidco_oracle_topk.restype = C.c_int64
         _lib = lib
@@ -223,3 +225,14 @@ def adaptive_run(grads, residual, *, delta, dist, stages, max_stages=MAX_STAGES,
             M = adapt_stages(M, acc / Q, delta * g.size, eps_h, eps_l, max_stages)
             acc = 0
     return out
+
+
+def scatter_add(dense, idx, val, scale=1.0):
+    """dense[idx] += scale * val in place (float32 array); returns the number of out-of-range indices skipped."""
+    assert dense.dtype == np.float32 and dense.flags.c_contiguous
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    val = np.ascontiguousarray(val, dtype=np.float32)
+    assert idx.size == val.size
+    return int(_load().sidco_oracle_scatter_add(
+        dense.ctypes.data_as(C.POINTER(C.c_float)), dense.size, idx.ctypes.data_as(C.POINTER(C.c_int32)),
+        val.ctypes.data_as(C.POINTER(C.c_float)), idx.size, np.float32(scale)))

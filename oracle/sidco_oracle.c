@@ -19,6 +19,7 @@
  *                                         through thresholding")
  *   - stage loop ........................ Algorithm 1, function Sparsify
  *   - number of stages .................. Algorithm 1, function Adapt_Stages; Sec. 3
+ *   - aggregation of sparse gradients ... Algorithm 2 (App. A)
  *
  * Readings taken where the paper is silent or inconsistent (each is a reading,
  * not a quotation; they are listed again in the design notes of the build):
@@ -343,6 +344,27 @@ int sidco_oracle_compress(const float *g, float *r, int64_t d, int dist,
     *status = st;
     free(acc_own);
     return 0;
+}
+
+/* Algorithm 2, aggregation of the workers' sparsified gradients: one worker's
+ * (index, value) pairs are added into the dense sum, scaled (1/N for the
+ * average).  fp32, two roundings per element: product, then sum.  Returns the
+ * number of pairs whose index is outside [0, d) (they are skipped).          */
+int64_t sidco_oracle_scatter_add(float *dense, int64_t d, const int32_t *idx,
+                                 const float *val, int64_t n, float scale)
+{
+    int64_t bad = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t j = idx[i];
+        if (j < 0 || j >= d) {
+            ++bad;
+            continue;
+        }
+        volatile float prod = scale * val[i]; /* volatile: no fused multiply-add */
+        volatile float sum = dense[j] + prod;
+        dense[j] = sum;
+    }
+    return bad;
 }
 
 /* Algorithm 1, function Adapt_Stages (and Sec. 3): one stage fewer when the

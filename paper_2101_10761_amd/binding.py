@@ -19,7 +19,8 @@ ST_NONFINITE, ST_VAR_ZERO, ST_GAMMA_S, ST_GAMMA_CLAMP, ST_STOPPED, ST_OVERFLOW, 
 EXPORTS = [
     "sidco_compress", "sidco_compress_ex", "sidco_topk", "sidco_adapt_stages", "sidco_controller_create",
     "sidco_controller_destroy", "sidco_controller_stages", "sidco_controller_iteration",
-    "sidco_controller_last_average", "sidco_controller_compress", "sidco_fit", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
+    "sidco_controller_last_average", "sidco_controller_compress", "sidco_scatter_add", "sidco_scatter_check",
+    "sidco_fit", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
     "sidco_workspace_bytes", "sidco_set_workspace", "sidco_set_speculation", "sidco_read_diag", "sidco_set_profiling",
     "sidco_get_profile", "sidco_strerror", "sidco_last_hip_error", "sidco_version", "sidco_shutdown",
 ]
@@ -92,6 +93,10 @@ def load() -> C.CDLL:
     lib.sidco_controller_last_average.restype = C.c_double
     lib.sidco_controller_compress.argtypes = [C.c_void_p, vp, f32p, f32p, C.c_int64, i32p, f32p, i32p, f32p]
     lib.sidco_controller_compress.restype = C.c_int
+    lib.sidco_scatter_add.argtypes = [vp, f32p, C.c_int64, i32p, f32p, i32p, C.c_int64, C.c_float]
+    lib.sidco_scatter_add.restype = C.c_int
+    lib.sidco_scatter_check.argtypes = [vp]
+    lib.sidco_scatter_check.restype = C.c_int
     lib.sidco_fit.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int]
     lib.sidco_fit.restype = C.c_int
     lib.sidco_fit_result.argtypes = [vp, f64p]
@@ -277,6 +282,25 @@ class Controller:
         _check(load().sidco_controller_compress(self._h, _stream_handle(stream), _ptr(grad), _ptr(residual), d,
                                                 _ptr(out_idx), _ptr(out_val), _ptr(out_count), _ptr(out_eta)),
                "sidco_controller_compress")
+
+
+def sidco_scatter_add(dense, idx, val, count, scale: float = 1.0, stream=None) -> None:
+    """dense[idx[i]] += scale * val[i] for i < count (a device scalar); see include/sidco.h."""
+    import torch
+    _check_tensor(dense, torch.float32, "dense")
+    _check_tensor(idx, torch.int32, "idx", 1)
+    _check_tensor(val, torch.float32, "val", 1)
+    _check_tensor(count, torch.int32, "count", 1)
+    cap = min(idx.numel(), val.numel())
+    _check(load().sidco_scatter_add(_stream_handle(stream), _ptr(dense), dense.numel(), _ptr(idx), _ptr(val), _ptr(count),
+                                    cap, scale), "sidco_scatter_add")
+
+
+def sidco_scatter_check(stream=None) -> bool:
+    rc = load().sidco_scatter_check(_stream_handle(stream))
+    if rc < 0:
+        raise SidcoError(rc, "sidco_scatter_check")
+    return bool(rc)
 
 
 def sidco_fit(grad, residual, dist: int, stream=None) -> None:

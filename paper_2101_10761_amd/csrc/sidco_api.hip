@@ -44,6 +44,7 @@ struct DeviceCtx {
     bool ev_made = false;
     int prof_n = 0;            // kernels of the last profiled call
     const char* prof_name[kMaxKernels] = {};
+    bool bad_cleared = false;  // the scatter kernels' bad-index flag has been initialised in this workspace
     int64_t last_cap = 0;      // output capacity of the last compress call
     // shape of the last compress call: a call that repeats it may use the device's record of where the
     // thresholds fell (DevState::theta_seen)
@@ -102,6 +103,7 @@ int ensure_workspace(DeviceCtx& c, size_t need)
     c.ws_bytes = need;
     c.ws_owned = true;
     c.sig_d = 0;  // a fresh workspace holds no record of an earlier call
+    c.bad_cleared = false;
     return SIDCO_OK;
 }
 
@@ -351,6 +353,8 @@ int sidco_set_workspace(void* device_ptr, size_t bytes)
     c.ws_bytes = device_ptr ? bytes : 0;
     c.ws_owned = false;
     c.sig_d = 0;  // a fresh workspace holds no record of an earlier call
+    c.bad_cleared = false;
+    c.bad_cleared = false;
     return SIDCO_OK;
 }
 
@@ -474,6 +478,47 @@ int sidco_controller_compress(sidco_controller* c, void* stream, const float* gr
     const int next = sidco_adapt_stages(c->stages, avg, c->delta * (double)d, c->eps_high, c->eps_low, c->max_stages);
     if (next >= 1) c->stages = next;
     return SIDCO_OK;
+}
+
+int sidco_scatter_add(void* stream, float* dense, int64_t d, const int32_t* idx, const float* val, const int32_t* count,
+                      int64_t capacity, float scale)
+{
+    if (!dense || !idx || !val || !count) return SIDCO_ERR_NULL;
+    if (d < 1 || d > (int64_t)INT32_MAX || capacity < 1 || capacity > (int64_t)INT32_MAX) return SIDCO_ERR_SIZE;
+    if (!aligned4(dense) || !aligned4(idx) || !aligned4(val) || !aligned4(count)) return SIDCO_ERR_ALIGN;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx* cp = nullptr;
+    int rc = current_ctx(&cp);
+    if (rc != SIDCO_OK) return rc;
+    rc = ensure_workspace(*cp, cp->ws ? cp->ws_bytes : head_bytes());  // the head alone is enough here
+    if (rc != SIDCO_OK) return rc;
+    WorkspaceHead* h = (WorkspaceHead*)cp->ws;
+    if (!cp->bad_cleared) {
+        launch_clear_u32(&h->st.bad_index, (hipStream_t)stream);
+        cp->bad_cleared = true;
+    }
+    launch_scatter_add(dense, d, idx, val, count, capacity, scale, &h->st.bad_index, (hipStream_t)stream);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    return SIDCO_OK;
+}
+
+int sidco_scatter_check(void* stream)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx* cp = nullptr;
+    int rc = current_ctx(&cp);
+    if (rc != SIDCO_OK) return rc;
+    if (!cp->ws || !cp->bad_cleared) return 0;
+    uint32_t bad = 0;
+    WorkspaceHead* h = (WorkspaceHead*)cp->ws;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipMemcpyAsync(&bad, &h->st.bad_index, sizeof(bad), hipMemcpyDeviceToHost, s);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(bad_index)");
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    if (bad) launch_clear_u32(&h->st.bad_index, s);
+    return bad ? 1 : 0;
 }
 
 int sidco_topk(void* stream, const float* grad, float* residual, int64_t d, int64_t k, int32_t* out_idx, float* out_val,

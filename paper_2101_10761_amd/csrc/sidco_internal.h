@@ -68,6 +68,7 @@ struct DevState {
     long long prev_cap;                           // output capacity of the previous call (clips its count)
     unsigned long long selected_ctr;              // pairs selected by the last stage (cleared by k_fit)
     uint32_t overflow;                            // 1 if selected_ctr exceeded the output capacity
+    uint32_t bad_index;                           // sidco_scatter_add met an index outside [0, d) since the last check
 };
 
 // Kernel arguments (passed by value).
@@ -143,6 +144,9 @@ void launch_topk_compact(const TopkParams& p, hipStream_t s);
 void launch_topk_refine(const TopkParams& p, uint32_t grid, hipStream_t s);
 void launch_topk_final(const TopkParams& p, uint32_t grid, hipStream_t s);
 
+void launch_clear_u32(uint32_t* p, hipStream_t s);
+void launch_scatter_add(float* dense, int64_t d, const int32_t* idx, const float* val, const int32_t* count,
+                        int64_t capacity, float scale, uint32_t* bad, hipStream_t s);
 void launch_fit(const Params& p, hipStream_t s);
 void launch_compact(const Params& p, bool stats, bool write, hipStream_t s);
 void launch_lists(const Params& p, uint32_t grid_blocks, hipStream_t s);

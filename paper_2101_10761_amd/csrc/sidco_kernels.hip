@@ -958,6 +958,46 @@ __global__ __launch_bounds__(kBlock) void k_gather(Params p)
 }
 
 // ---------------------------------------------------------------------------------------------
+// k_scatter_add: the step after the sparsifier in Algorithm 2 - a worker's (index, value) pairs are
+// added into the dense aggregate, dense[idx[i]] += scale * val[i].  The indices of one list are
+// distinct, so plain read-modify-write needs no atomics and the result is deterministic; lists of
+// several workers are added by consecutive launches.  Two roundings per element (product, then sum),
+// as a plain fp32 loop does.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_scatter_add(float* __restrict__ dense, int64_t d, const int32_t* __restrict__ idx,
+                                                        const float* __restrict__ val, const int32_t* __restrict__ count,
+                                                        int64_t capacity, float scale, uint32_t* __restrict__ bad)
+{
+    int64_t n = (int64_t)*count;
+    if (n > capacity) n = capacity;
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += stride) {
+        const int64_t j = (int64_t)idx[i];
+        if (j < 0 || j >= d) {  // never written; reported
+            atomicOr(bad, 1u);
+            continue;
+        }
+        dense[j] = __fadd_rn(dense[j], __fmul_rn(scale, val[i]));
+    }
+}
+
+__global__ void k_clear_u32(uint32_t* p) { *p = 0; }
+
+// a fill kernel rather than a memset: callers may record the stream into a HIP graph
+void launch_clear_u32(uint32_t* p, hipStream_t s) { hipLaunchKernelGGL(k_clear_u32, dim3(1), dim3(1), 0, s, p); }
+
+void launch_scatter_add(float* dense, int64_t d, const int32_t* idx, const float* val, const int32_t* count,
+                        int64_t capacity, float scale, uint32_t* bad, hipStream_t s)
+{
+    // the list length is only known on the device: a grid for the capacity, capped; idle blocks exit at once
+    int64_t blocks = (capacity + 4 * kBlock - 1) / (4 * kBlock);
+    if (blocks < 1) blocks = 1;
+    if (blocks > 2 * kMaxBlocks) blocks = 2 * kMaxBlocks;
+    hipLaunchKernelGGL(k_scatter_add, dim3((uint32_t)blocks), dim3(kBlock), 0, s, dense, d, idx, val, count, capacity,
+                       scale, bad);
+}
+
+// ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
 template <bool EC>

@@ -42,6 +42,9 @@ MUTANTS = [
     ("adapt_non_strict", "if (khat_avg > k * (1.0 + eps_h)) M = M - 1;", "if (khat_avg >= k * (1.0 + eps_h)) M = M - 1;"),
     ("adapt_no_upper_clamp", "if (M > M_max) M = M_max;", ""),
     ("adapt_no_lower_clamp", "if (M < 1) M = 1;\n    if (M > M_max)", "if (M > M_max)"),
+    ("scatter_scale_dropped", "volatile float prod = scale * val[i];", "volatile float prod = val[i];"),
+    ("scatter_overwrites", "volatile float sum = dense[j] + prod;", "volatile float sum = prod;"),
+    ("scatter_upper_bound_off_by_one", "if (j < 0 || j >= d) {", "if (j < 0 || j > d) {"),
     ("signed_values_lost", "if (val) val[k] = acc[j];", "if (val) val[k] = fabsf(acc[j]);"),
 ]
 

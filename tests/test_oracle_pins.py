@@ -450,3 +450,31 @@ def test_adaptive_run_settles_inside_the_tolerance_band(oracle):
     assert 1 <= first < W - 1 and all(inside[first:])       # reaches the band and stays inside
     assert len(set(Ms[first * Q:])) == 1
     assert Ms[:first * Q + 1:Q] == list(range(1, first + 2))  # one stage more per window on the way
+
+
+# ----------------------------------------------------------------------------------------------
+# aggregation of sparse gradients (Algorithm 2)
+# ----------------------------------------------------------------------------------------------
+def test_scatter_add_reconstructs_and_averages(oracle):
+    """Scattering a worker's pairs onto zeros and adding its residual gives back acc exactly (the sparsifier
+    only moves entries); the scaled sum over workers equals numpy's fp32 sum taken in the same order; indices
+    outside the vector are skipped and counted."""
+    rng = np.random.default_rng(5)
+    d, N = 50_000, 4
+    dense = np.zeros(d, np.float32)
+    want = np.zeros(d, np.float32)
+    for n in range(N):
+        g = rng.laplace(0, 1e-3, size=d).astype(np.float32)
+        r = rng.laplace(0, 3e-4, size=d).astype(np.float32)
+        res = oracle.compress(g, r, ratios=[0.25, 0.04], dist=0)
+        one = np.zeros(d, np.float32)
+        assert oracle.scatter_add(one, res.idx, res.val, 1.0) == 0
+        np.testing.assert_array_equal((one + res.residual).view(np.uint32), oracle.ec_add(g, r).view(np.uint32))
+        assert np.count_nonzero(one) == np.count_nonzero(res.val)
+        assert oracle.scatter_add(dense, res.idx, res.val, 1.0 / N) == 0
+        want[res.idx] = want[res.idx] + np.float32(1.0 / N) * res.val      # numpy fp32: product rounded, then sum
+    np.testing.assert_array_equal(dense.view(np.uint32), want.view(np.uint32))
+    before = dense.copy()
+    assert oracle.scatter_add(dense, np.array([-1, d, 7], np.int32), np.array([1, 1, 0.5], np.float32), 2.0) == 2
+    before[7] += np.float32(1.0)
+    np.testing.assert_array_equal(dense, before)
