@@ -127,6 +127,35 @@ int sidco_compress_ex(void *stream, const float *grad, float *residual, int64_t 
                       int32_t *out_count, float *out_eta);
 
 /*
+ * Several vectors in one launch sequence: the tensors of one flat gradient
+ * buffer, each sparsified on its own exactly as sidco_compress would (the cost of
+ * the compressor depends only on the vector's size, App. A, so layer-wise
+ * compression is n independent problems; here they share every kernel launch).
+ *
+ *  grad, residual  device, flat buffers; tensor t is the elements
+ *                  [offsets[t], offsets[t+1]) of both (residual may be NULL)
+ *  offsets         host, n+1 ascending int64; every tensor has 1..2^31-1 elements
+ *  n               1..512 tensors per call
+ *  delta, dist, stages   as in sidco_compress, the same for every tensor
+ *  out_idx, out_val      device; tensor t's pairs start at out_offsets[t] and have room
+ *                  for out_offsets[t+1] - out_offsets[t] >= 1 pairs; indices are
+ *                  relative to the tensor's first element
+ *  out_offsets     host, n+1 int64 (sidco_batched_out_offsets fills the default:
+ *                  sidco_out_capacity per tensor)
+ *  out_counts, out_etas  device, n int32 / n floats
+ * The first call with a given layout uploads a table and synchronises `stream`;
+ * calls that repeat it are asynchronous like every other call.
+ */
+int sidco_compress_batched(void *stream, const float *grad, float *residual, const int64_t *offsets,
+                           int n, double delta, int dist, int stages,
+                           int32_t *out_idx, float *out_val, const int64_t *out_offsets,
+                           int32_t *out_counts, float *out_etas);
+int sidco_batched_out_offsets(const int64_t *offsets, int n, double delta, int64_t *out_offsets);
+size_t sidco_workspace_bytes_batched(const int64_t *offsets, int n);
+/* Diagnostics of tensor t of the last batched call on the current device. Synchronises `stream`. */
+int sidco_read_diag_batched(void *stream, int t, sidco_diag *host_out);
+
+/*
  * Adapt_Stages (Algorithm 1; Sec. 3): the number of stages for the next Q
  * iterations from the average number of selected elements over the last Q.
  * One stage fewer if khat_avg > k (1 + eps_high), one more if

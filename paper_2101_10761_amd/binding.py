@@ -17,7 +17,8 @@ DIST_EXP, DIST_GAMMA_GPD, DIST_GPD = 0, 1, 2
 ST_NONFINITE, ST_VAR_ZERO, ST_GAMMA_S, ST_GAMMA_CLAMP, ST_STOPPED, ST_OVERFLOW, ST_FALLBACK = 1, 2, 4, 8, 16, 32, 64
 
 EXPORTS = [
-    "sidco_compress", "sidco_compress_ex", "sidco_topk", "sidco_adapt_stages", "sidco_controller_create",
+    "sidco_compress", "sidco_compress_ex", "sidco_compress_batched", "sidco_batched_out_offsets",
+    "sidco_workspace_bytes_batched", "sidco_read_diag_batched", "sidco_topk", "sidco_adapt_stages", "sidco_controller_create",
     "sidco_controller_destroy", "sidco_controller_stages", "sidco_controller_iteration",
     "sidco_controller_last_average", "sidco_controller_compress", "sidco_scatter_add", "sidco_scatter_check",
     "sidco_fit", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
@@ -78,6 +79,16 @@ def load() -> C.CDLL:
     lib.sidco_compress_ex.restype = C.c_int
     lib.sidco_topk.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int64, i32p, f32p, i32p, f32p]
     lib.sidco_topk.restype = C.c_int
+    i64p = C.POINTER(C.c_int64)
+    lib.sidco_compress_batched.argtypes = [vp, f32p, f32p, i64p, C.c_int, C.c_double, C.c_int, C.c_int, i32p, f32p,
+                                           i64p, i32p, f32p]
+    lib.sidco_compress_batched.restype = C.c_int
+    lib.sidco_batched_out_offsets.argtypes = [i64p, C.c_int, C.c_double, i64p]
+    lib.sidco_batched_out_offsets.restype = C.c_int
+    lib.sidco_workspace_bytes_batched.argtypes = [i64p, C.c_int]
+    lib.sidco_workspace_bytes_batched.restype = C.c_size_t
+    lib.sidco_read_diag_batched.argtypes = [vp, C.c_int, C.POINTER(Diag)]
+    lib.sidco_read_diag_batched.restype = C.c_int
     lib.sidco_adapt_stages.argtypes = [C.c_int, C.c_double, C.c_double, C.c_double, C.c_double, C.c_int]
     lib.sidco_adapt_stages.restype = C.c_int
     lib.sidco_controller_create.argtypes = [C.POINTER(C.c_void_p), C.c_double, C.c_int, C.c_int, C.c_int, C.c_int,
@@ -214,6 +225,45 @@ def sidco_compress_ex(grad, residual, dist: int, ratios, out_idx, out_val, out_c
     _check(load().sidco_compress_ex(_stream_handle(stream), _ptr(grad), _ptr(residual), d, dist, r, len(ratios),
                                     _ptr(out_idx), _ptr(out_val), cap, _ptr(out_count), _ptr(out_eta)),
            "sidco_compress_ex")
+
+
+def _i64_array(values):
+    return (C.c_int64 * len(values))(*[int(v) for v in values])
+
+
+def sidco_batched_out_offsets(offsets, delta: float) -> list[int]:
+    """Default placement of the tensors' outputs: sidco_out_capacity pairs each, back to back."""
+    n = len(offsets) - 1
+    out = (C.c_int64 * (n + 1))()
+    _check(load().sidco_batched_out_offsets(_i64_array(offsets), n, delta, out), "sidco_batched_out_offsets")
+    return [out[i] for i in range(n + 1)]
+
+
+def sidco_workspace_bytes_batched(offsets) -> int:
+    return int(load().sidco_workspace_bytes_batched(_i64_array(offsets), len(offsets) - 1))
+
+
+def sidco_compress_batched(grad, residual, offsets, delta: float, dist: int, stages: int, out_idx, out_val, out_offsets,
+                           out_counts, out_etas, stream=None) -> None:
+    """Enqueues one sparsifier call per tensor of the flat buffer, all in one launch sequence; see include/sidco.h."""
+    import torch
+    n = len(offsets) - 1
+    _check_tensor(grad, torch.float32, "grad", offsets[-1])
+    if residual is not None:
+        _check_tensor(residual, torch.float32, "residual", offsets[-1])
+    _check_tensor(out_idx, torch.int32, "out_idx", out_offsets[-1])
+    _check_tensor(out_val, torch.float32, "out_val", out_offsets[-1])
+    _check_tensor(out_counts, torch.int32, "out_counts", n)
+    _check_tensor(out_etas, torch.float32, "out_etas", n)
+    _check(load().sidco_compress_batched(_stream_handle(stream), _ptr(grad), _ptr(residual), _i64_array(offsets), n, delta,
+                                         dist, stages, _ptr(out_idx), _ptr(out_val), _i64_array(out_offsets),
+                                         _ptr(out_counts), _ptr(out_etas)), "sidco_compress_batched")
+
+
+def sidco_read_diag_batched(t: int, stream=None) -> Diag:
+    diag = Diag()
+    _check(load().sidco_read_diag_batched(_stream_handle(stream), t, C.byref(diag)), "sidco_read_diag_batched")
+    return diag
 
 
 def sidco_topk(grad, residual, k: int, out_idx, out_val, out_count, out_kth, stream=None) -> None:

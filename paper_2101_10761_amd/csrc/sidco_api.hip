@@ -7,6 +7,7 @@
 
 #include <mutex>
 #include <new>
+#include <vector>
 
 #include "sidco_internal.h"
 
@@ -26,6 +27,7 @@ struct WorkspaceHead {
     alignas(256) uint32_t blk[2][kMaxBlocks];
     alignas(256) uint32_t topk_hist[3 * kTopkBins];
     alignas(256) TopkState topk;
+    alignas(256) BatchTable batch;  // at a fixed place, so that single calls in between leave it alone
 };
 
 constexpr size_t head_bytes() { return (sizeof(WorkspaceHead) + kAlign - 1) / kAlign * kAlign; }
@@ -52,6 +54,12 @@ struct DeviceCtx {
     int sig_dist = -1, sig_M = 0;
     double sig_ratios[SIDCO_MAX_STAGES] = {};
     double sig_theta = -1.0;
+    // batched calls: host image of the table the device holds (descriptors and block maps), the
+    // shared arguments it was used with, and the output capacities for the diagnostics
+    std::vector<unsigned char> batch_image;
+    double batch_delta = -1.0, batch_theta = -1.0;
+    int batch_dist = -1, batch_M = 0, batch_n = 0;
+    std::vector<int64_t> batch_cap;
     uint32_t fit_nblocks = 0;  // grid, length and law of the last sidco_fit call
     int64_t fit_d = 0;
     int fit_dist = 0;
@@ -104,6 +112,8 @@ int ensure_workspace(DeviceCtx& c, size_t need)
     c.ws_owned = true;
     c.sig_d = 0;  // a fresh workspace holds no record of an earlier call
     c.bad_cleared = false;
+    c.batch_image.clear();
+    c.batch_image.clear();
     return SIDCO_OK;
 }
 
@@ -145,6 +155,30 @@ uint32_t final_grid(const Params& p, double expect)
     if (grid > p.nblocks) grid = p.nblocks;
     if (grid < 1) grid = 1;
     return grid;
+}
+
+// Lowest theta a threshold hint may lead to in a dense stage whose source still holds the fraction `cum` of
+// the vector: the candidate lists must stay within kMaterializeBelow of the vector.
+float hint_floor(double cum, double L_stage, double L_next)
+{
+    const double t = (log(cum / kMaterializeBelow) - L_stage) / L_next;
+    return (float)(t > 0.0 ? t : 0.0);
+}
+
+// the host's view of a call's device state
+void fill_diag(const DevState& st, int64_t cap, sidco_diag* host_out)
+{
+    *host_out = st.diag;
+    host_out->selected = (int64_t)st.selected_ctr;
+    host_out->count = (int32_t)((int64_t)st.selected_ctr < cap ? (int64_t)st.selected_ctr : cap);
+    if (st.overflow) host_out->status |= SIDCO_ST_OVERFLOW;
+    host_out->reserved = 0;
+    const int M = host_out->stages;
+    for (int m = (M < 0 ? 0 : M); m < SIDCO_MAX_STAGES; ++m) {  // entries of earlier, longer calls
+        host_out->eta[m] = 0.0f;
+        host_out->n[m] = 0;
+        host_out->stats[m][0] = host_out->stats[m][1] = host_out->stats[m][2] = 0.0;
+    }
 }
 
 // HIP events of the per-kernel profile, created on first use
@@ -213,7 +247,7 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
     // stage-1 sums (and acc) -> part[0]
     p.part_out = h->part[0];
     launch_fit(p, s);
-    uint32_t nprod = p.nblocks;  // blocks of the kernel launched last
+
     ++k;
     mark("k_fit");
 
@@ -228,7 +262,6 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
     auto bind = [&](int m) {
         const int in = sel, out = sel ^ 1;
         p.stage = m;
-        p.nprod = nprod;
         p.theta = 0.0f;
         p.prev_cand = cand ? 1 : 0;
         p.part_in = h->part[in];
@@ -248,11 +281,13 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
             const double Lw = p.L[m - 1] + theta * p.L[m];
             const double frac = cum * exp(-Lw);
             const bool write = frac <= kMaterializeBelow;
-            if (write && theta > 0.0) p.theta = (float)theta;
+            if (write && theta > 0.0) {
+                p.theta = (float)theta;
+                p.theta_min = hint_floor(cum, p.L[m - 1], p.L[m]);
+            }
             p.reverse = reverse;
             reverse = !reverse;
             launch_compact(p, /*stats=*/true, write, s);
-            nprod = p.nblocks;
             ++k;
             mark(write ? "k_compact_dense" : "k_scan_dense");
             if (write) {
@@ -264,7 +299,6 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
             // one source list per wave: the kernel is a chain of dependent round trips per list, and
             // fewer, longer chains were slower than more blocks (measured: 128 blocks 18 us, 512 blocks 14 us)
             launch_lists(p, p.nblocks, s);
-            nprod = p.nblocks;
             ++k;
             mark("k_lists");
             list_frac = cum * ratios[m - 1];
@@ -278,7 +312,6 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
         launch_compact(p, /*stats=*/false, /*write=*/true, s);
         ++k;
         mark("k_compact_dense");
-        p.nprod = p.nblocks;
         p.cnt_in = h->cnt[sel];
         p.blk_in = h->blk[sel];
         p.seg_in = segbuf[sel];
@@ -354,6 +387,7 @@ int sidco_set_workspace(void* device_ptr, size_t bytes)
     c.ws_owned = false;
     c.sig_d = 0;  // a fresh workspace holds no record of an earlier call
     c.bad_cleared = false;
+    c.batch_image.clear();
     c.bad_cleared = false;
     return SIDCO_OK;
 }
@@ -521,6 +555,242 @@ int sidco_scatter_check(void* stream)
     return bad ? 1 : 0;
 }
 
+// ---- batched calls ----
+namespace {
+
+struct BatchPlan {
+    std::vector<TensorDesc> desc;
+    std::vector<uint16_t> map, fmap;
+    uint32_t blocks = 0, final_blocks = 0;
+    uint64_t slots = 0;  // survivor-list slots of all vectors
+};
+
+// Splits the 512 blocks of a launch over the vectors in proportion to their lengths (at least one each).
+int plan_batch(const float* grad, float* residual, const int64_t* offsets, int n, int32_t* out_idx, float* out_val,
+               const int64_t* out_offsets, int32_t* out_counts, float* out_etas, BatchPlan& pl)
+{
+    if (n < 1 || n > kMaxBatch) return SIDCO_ERR_SIZE;
+    uint64_t tiles_total = 0;
+    for (int t = 0; t < n; ++t) {
+        const int64_t d = offsets[t + 1] - offsets[t];
+        if (offsets[t] < 0 || d < 1 || d > (int64_t)INT32_MAX) return SIDCO_ERR_SIZE;
+        if (out_offsets[t] < 0 || out_offsets[t + 1] - out_offsets[t] < 1) return SIDCO_ERR_SIZE;
+        tiles_total += (uint64_t)((d + kTile - 1) / kTile);
+    }
+    pl.desc.assign(n, TensorDesc());
+    pl.map.assign(kMaxBlocks, 0);
+    pl.fmap.assign(kMaxBlocks, 0);
+    uint32_t fb = 0, ff = 0;
+    uint64_t slot = 0;
+    for (int t = 0; t < n; ++t) {
+        TensorDesc& ds = pl.desc[t];
+        const int64_t d = offsets[t + 1] - offsets[t];
+        const uint64_t ntiles = (uint64_t)((d + kTile - 1) / kTile);
+        uint64_t share = 1 + ((uint64_t)(kMaxBlocks - n) * ntiles) / tiles_total;
+        uint64_t nwaves = share * kWavesPerBlock < ntiles ? share * kWavesPerBlock : ntiles;
+        ds.grad = grad + offsets[t];
+        ds.residual = residual ? residual + offsets[t] : nullptr;
+        ds.d = d;
+        ds.first_block = fb;
+        ds.nblocks = (uint32_t)((nwaves + kWavesPerBlock - 1) / kWavesPerBlock);
+        ds.first_final = ff;
+        ds.nfinal = (uint32_t)((nwaves + 31) / 32);
+        ds.seg_off = slot;
+        ds.out_idx = out_idx + out_offsets[t];
+        ds.out_val = out_val + out_offsets[t];
+        ds.out_count = out_counts + t;
+        ds.out_eta = out_etas + t;
+        ds.out_cap = out_offsets[t + 1] - out_offsets[t];
+        ds.vec_ok = aligned16(ds.grad) && aligned16(ds.residual);
+        ds.reserved = 0;
+        for (uint32_t i = 0; i < ds.nblocks; ++i) pl.map[fb + i] = (uint16_t)t;
+        for (uint32_t i = 0; i < ds.nfinal; ++i) pl.fmap[ff + i] = (uint16_t)t;
+        fb += ds.nblocks;
+        ff += ds.nfinal;
+        slot += ntiles * kTile;
+    }
+    pl.blocks = fb;
+    pl.final_blocks = ff;
+    pl.slots = slot;
+    return SIDCO_OK;
+}
+
+}  // namespace
+
+int sidco_batched_out_offsets(const int64_t* offsets, int n, double delta, int64_t* out_offsets)
+{
+    if (!offsets || !out_offsets) return SIDCO_ERR_NULL;
+    if (n < 1 || n > kMaxBatch) return SIDCO_ERR_SIZE;
+    if (!(delta > 0.0 && delta < 1.0)) return SIDCO_ERR_DELTA;
+    out_offsets[0] = 0;
+    for (int t = 0; t < n; ++t) {
+        const int64_t cap = sidco_out_capacity(offsets[t + 1] - offsets[t], delta);
+        if (cap < 1) return SIDCO_ERR_SIZE;
+        out_offsets[t + 1] = out_offsets[t] + cap;
+    }
+    return SIDCO_OK;
+}
+
+size_t sidco_workspace_bytes_batched(const int64_t* offsets, int n)
+{
+    if (!offsets || n < 1 || n > kMaxBatch) return 0;
+    uint64_t slots = 0;
+    for (int t = 0; t < n; ++t) {
+        const int64_t d = offsets[t + 1] - offsets[t];
+        if (d < 1) return 0;
+        slots += (uint64_t)((d + kTile - 1) / kTile) * kTile;
+    }
+    return head_bytes() + 2 * slots * sizeof(int2);
+}
+
+int sidco_compress_batched(void* stream, const float* grad, float* residual, const int64_t* offsets, int n, double delta,
+                           int dist, int stages, int32_t* out_idx, float* out_val, const int64_t* out_offsets,
+                           int32_t* out_counts, float* out_etas)
+{
+    if (!grad || !offsets || !out_idx || !out_val || !out_offsets || !out_counts || !out_etas) return SIDCO_ERR_NULL;
+    if (dist != SIDCO_DIST_EXP && dist != SIDCO_DIST_GAMMA_GPD && dist != SIDCO_DIST_GPD) return SIDCO_ERR_DIST;
+    if (!aligned4(grad) || !aligned4(residual) || !aligned4(out_idx) || !aligned4(out_val) || !aligned4(out_counts) ||
+        !aligned4(out_etas))
+        return SIDCO_ERR_ALIGN;
+    if (residual && (const void*)residual == (const void*)grad) return SIDCO_ERR_ARG;
+    if (!(delta > 0.0 && delta < 1.0)) return SIDCO_ERR_DELTA;
+    if (stages < 1 || stages > SIDCO_MAX_STAGES) return SIDCO_ERR_STAGES;
+    double ratios[SIDCO_MAX_STAGES];
+    const int M = sidco_stage_ratios(delta, stages, 0.25, ratios);
+    if (M < 1) return M;
+    BatchPlan pl;
+    int rc = plan_batch(grad, residual, offsets, n, out_idx, out_val, out_offsets, out_counts, out_etas, pl);
+    if (rc != SIDCO_OK) return rc;
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx* cp = nullptr;
+    rc = current_ctx(&cp);
+    if (rc != SIDCO_OK) return rc;
+    DeviceCtx& c = *cp;
+    rc = ensure_workspace(c, head_bytes() + 2 * pl.slots * sizeof(int2));
+    if (rc != SIDCO_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    WorkspaceHead* h = (WorkspaceHead*)c.ws;
+    const double theta = g_speculation;
+
+    // The table on the device: uploaded when it differs from the one already there (the first call with a
+    // layout; synchronous).  A call that repeats the previous one, shared arguments included, may use the
+    // vectors' threshold hints.
+    const size_t desc_bytes = (size_t)n * sizeof(TensorDesc), map_bytes = kMaxBlocks * sizeof(uint16_t);
+    std::vector<unsigned char> image(desc_bytes + 2 * map_bytes);
+    memcpy(image.data(), pl.desc.data(), desc_bytes);
+    memcpy(image.data() + desc_bytes, pl.map.data(), map_bytes);
+    memcpy(image.data() + desc_bytes + map_bytes, pl.fmap.data(), map_bytes);
+    const bool same_table = image == c.batch_image;
+    const bool same_shape = same_table && c.batch_delta == delta && c.batch_theta == theta && c.batch_dist == dist &&
+                            c.batch_M == M;
+    if (!same_table) {
+        hipError_t e = hipStreamSynchronize(s);  // an earlier call on the stream may still read the old table
+        if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+        e = hipMemcpy(h->batch.desc, pl.desc.data(), desc_bytes, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(h->batch.map, pl.map.data(), map_bytes, hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(h->batch.fmap, pl.fmap.data(), map_bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            c.batch_image.clear();
+            return hip_fail(e, "hipMemcpy(batch table)");
+        }
+        c.batch_image.swap(image);
+    }
+    c.batch_delta = delta;
+    c.batch_theta = theta;
+    c.batch_dist = dist;
+    c.batch_M = M;
+    c.batch_n = n;
+    c.batch_cap.resize(n);
+    for (int t = 0; t < n; ++t) c.batch_cap[t] = pl.desc[t].out_cap;
+    c.sig_d = 0;  // the single-call record of the head is not touched, but keep the rule simple: no hint across kinds
+
+    BatchArgs a;
+    memset(&a, 0, sizeof(a));
+    a.tb = &h->batch;
+    const size_t seg = pl.slots * sizeof(int2);
+    for (int i = 0; i < 2; ++i) {
+        a.part[i] = h->part[i];
+        a.cnt[i] = h->cnt[i];
+        a.blk[i] = h->blk[i];
+        a.seg[i] = (int2*)((char*)c.ws + head_bytes() + i * seg);
+    }
+    a.dist = dist;
+    a.M = M;
+    for (int m = 0; m < M; ++m) a.L[m] = log(1.0 / ratios[m]);
+    a.use_hint = same_shape ? 1 : 0;
+
+    // same sequence as a single call (see run), every kernel once for all vectors
+    a.in = 1;
+    a.out = 0;
+    launch_fit_batched(a, residual != nullptr, pl.blocks, s);
+    bool lists = false, cand = false, reverse = true;
+    double cum = 1.0;
+    int sel = 0;
+    auto bind = [&](int m) {
+        a.in = sel;
+        a.out = sel ^ 1;
+        sel ^= 1;
+        a.stage = m;
+        a.theta = 0.0f;
+        a.prev_cand = cand ? 1 : 0;
+    };
+    for (int m = 1; m < M; ++m) {
+        bind(m);
+        if (!lists) {
+            const double Lw = a.L[m - 1] + theta * a.L[m];
+            const bool write = cum * exp(-Lw) <= kMaterializeBelow;
+            if (write && theta > 0.0) {
+                a.theta = (float)theta;
+                a.theta_min = hint_floor(cum, a.L[m - 1], a.L[m]);
+            }
+            a.reverse = reverse ? 1 : 0;
+            reverse = !reverse;
+            launch_compact_batched(a, /*stats=*/true, write, pl.blocks, s);
+            if (write) {
+                lists = true;
+                cand = theta > 0.0;
+            }
+        } else {
+            launch_lists_batched(a, pl.blocks, s);
+            cand = false;
+        }
+        cum *= ratios[m - 1];
+    }
+    bind(M);
+    if (!lists) {
+        a.reverse = reverse ? 1 : 0;
+        launch_compact_batched(a, /*stats=*/false, /*write=*/true, pl.blocks, s);
+        a.in = sel;  // the gather reads what the compaction just wrote
+        launch_gather_batched(a, pl.blocks, s);
+    } else {
+        launch_final_lists_batched(a, pl.final_blocks, s);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    return SIDCO_OK;
+}
+
+int sidco_read_diag_batched(void* stream, int t, sidco_diag* host_out)
+{
+    if (!host_out) return SIDCO_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx* cp = nullptr;
+    int rc = current_ctx(&cp);
+    if (rc != SIDCO_OK) return rc;
+    DeviceCtx& c = *cp;
+    if (!c.ws || c.batch_image.empty()) return SIDCO_ERR_WORKSPACE;
+    if (t < 0 || t >= c.batch_n) return SIDCO_ERR_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    DevState st;
+    hipError_t e = hipMemcpyAsync(&st, &((WorkspaceHead*)c.ws)->batch.st[t], sizeof(DevState), hipMemcpyDeviceToHost, s);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(diag)");
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    fill_diag(st, c.batch_cap[t], host_out);
+    return SIDCO_OK;
+}
+
 int sidco_topk(void* stream, const float* grad, float* residual, int64_t d, int64_t k, int32_t* out_idx, float* out_val,
                int32_t* out_count, float* out_kth)
 {
@@ -670,17 +940,7 @@ int sidco_read_diag(void* stream, sidco_diag* host_out)
     if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(diag)");
     e = hipStreamSynchronize(s);
     if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
-    *host_out = st.diag;
-    host_out->selected = (int64_t)st.selected_ctr;
-    host_out->count = (int32_t)((int64_t)st.selected_ctr < c.last_cap ? (int64_t)st.selected_ctr : c.last_cap);
-    if (st.overflow) host_out->status |= SIDCO_ST_OVERFLOW;
-    host_out->reserved = 0;
-    const int M = host_out->stages;
-    for (int m = (M < 0 ? 0 : M); m < SIDCO_MAX_STAGES; ++m) {  // entries of earlier, longer calls
-        host_out->eta[m] = 0.0f;
-        host_out->n[m] = 0;
-        host_out->stats[m][0] = host_out->stats[m][1] = host_out->stats[m][2] = 0.0;
-    }
+    fill_diag(st, c.last_cap, host_out);
     return SIDCO_OK;
 }
 

@@ -80,8 +80,7 @@ struct Params {
     uint32_t ntiles;        // ceil(d / kTile)
     uint32_t nfull;         // d / kTile: tiles below this index are complete
     uint32_t nwaves;        // waves that own tiles
-    uint32_t nblocks;       // grid size of the kernels that read the dense vector
-    uint32_t nprod;         // blocks of the kernel that wrote part_in / blk_in
+    uint32_t nblocks;       // grid size of the kernels that read the dense vector or write partial sums
     int vec_ok;             // all dense buffers 16-byte aligned: float4 accesses allowed
     int reverse;            // a dense stage kernel walks every wave's tiles from the last to the first
     int acc_reset;          // k_fit: start the controller's count of reported pairs over instead of adding to it
@@ -90,6 +89,7 @@ struct Params {
     int stage;              // 1-based stage a k_compact launch works for
     double L[SIDCO_MAX_STAGES];  // log(1/delta_m)
     float theta;            // > 0: the lists of this kernel are candidate lists (see stage_prologue); else 0
+    float theta_min;        // lowest theta a hint may lead to: below it the lists would exceed kMaterializeBelow
     int use_hint;           // the previous call on the device had this call's shape: theta_seen applies
     int prev_cand;          // the producer of this kernel's source lists wrote candidate lists
     DevState* st;
@@ -143,6 +143,60 @@ void launch_topk_hist(const TopkParams& p, hipStream_t s);
 void launch_topk_compact(const TopkParams& p, hipStream_t s);
 void launch_topk_refine(const TopkParams& p, uint32_t grid, hipStream_t s);
 void launch_topk_final(const TopkParams& p, uint32_t grid, hipStream_t s);
+
+// A block's place in its vector's grid (the whole launch for a single call, a slice of it in a batch).
+struct Blk {
+    uint32_t id;  // block index within the vector's grid
+    uint32_t n;   // size of that grid
+};
+
+// ---- batched calls: several vectors (the tensors of one flat buffer) in one launch sequence ----
+constexpr int kMaxBatch = kMaxBlocks;  // every vector owns at least one block of the 512-block launches
+
+struct TensorDesc {
+    const float* grad;      // the vector's first element
+    float* residual;        // NULL: memoryless
+    int64_t d;
+    uint32_t first_block;   // the vector's blocks in the dense grids: [first_block, first_block + nblocks)
+    uint32_t nblocks;
+    uint32_t first_final;   // ... and in the last stage's grid
+    uint32_t nfinal;
+    uint64_t seg_off;       // first slot of the vector in the survivor-list buffers
+    int32_t* out_idx;
+    float* out_val;
+    int32_t* out_count;
+    float* out_eta;
+    int64_t out_cap;
+    int vec_ok;
+    int reserved;
+};
+
+struct BatchTable {
+    DevState st[kMaxBatch];
+    TensorDesc desc[kMaxBatch];
+    uint16_t map[kMaxBlocks];   // block of a dense grid -> vector
+    uint16_t fmap[kMaxBlocks];  // block of the last stage's grid -> vector
+};
+
+// Kernel arguments of a batched launch (by value): what all vectors share.
+struct BatchArgs {
+    BatchTable* tb;
+    double* part[2];
+    uint32_t* cnt[2];
+    uint32_t* blk[2];
+    int2* seg[2];
+    int in, out;            // which half of the double buffers the kernel reads / writes
+    int dist, M, stage, reverse;
+    double L[SIDCO_MAX_STAGES];
+    float theta, theta_min;
+    int use_hint, prev_cand;
+};
+
+void launch_fit_batched(const BatchArgs& a, bool ec, uint32_t blocks, hipStream_t s);
+void launch_compact_batched(const BatchArgs& a, bool stats, bool write, uint32_t blocks, hipStream_t s);
+void launch_lists_batched(const BatchArgs& a, uint32_t blocks, hipStream_t s);
+void launch_final_lists_batched(const BatchArgs& a, uint32_t final_blocks, hipStream_t s);
+void launch_gather_batched(const BatchArgs& a, uint32_t blocks, hipStream_t s);
 
 void launch_clear_u32(uint32_t* p, hipStream_t s);
 void launch_scatter_add(float* dense, int64_t d, const int32_t* idx, const float* val, const int32_t* count,

@@ -137,6 +137,17 @@ __device__ __forceinline__ float fit_quantile_fast(const Fit& f, double L)
     return (float)(f.b / f.a) * expm1f((float)(f.a * L));
 }
 
+// log(1/delta_i) of stage i+1.  A chain of selects rather than an index: the arguments of a batched launch
+// are assembled in registers, and an indexed array there would be spilled to scratch memory.
+__device__ __forceinline__ double stage_L(const Params& p, int i)
+{
+    double v = 0.0;
+#pragma unroll
+    for (int j = 0; j < SIDCO_MAX_STAGES; ++j)
+        if (j == i) v = p.L[j];
+    return v;
+}
+
 // What the prologue of a stage's kernel hands to its body.
 struct StageEta {
     float eta;      // eta_m: the stage's threshold (statistics of the next fit; selection in the last stage)
@@ -154,32 +165,33 @@ struct StageEta {
 // log(1/ratio) = L_m + theta * L_{m+1}, and writes only the entries above that candidate threshold
 // eta_w.  theta is the host's setting (0.5: halfway between this stage's target and the next one's) or,
 // when the previous call on the device had the same shape, the place where that call's next
-// threshold really fell, less a margin.  The next stage's eta is computed from the exact statistics as
+// threshold really fell, less a margin (and not so low that the lists would outgrow what the host
+// planned for: theta_min).  The next stage's eta is computed from the exact statistics as
 // always; if it lands at or above eta_w the candidate lists contain every entry it can select and
 // replace the dense vector, else that kernel falls back to the dense vector.  Either way the result is
 // the same: only the time depends on the guess.
-__device__ StageEta stage_prologue(const Params& p, bool auto_src, double (*sh)[4])
+__device__ StageEta stage_prologue(const Params& p, Blk b, bool auto_src, double (*sh)[4])
 {
     const int m = p.stage;  // 1-based
     const uint32_t t = threadIdx.x;
-    const bool have = t < p.nprod;  // one thread per block of the kernel that produced the partial sums
-    const double L = p.L[m - 1];
+    const bool have = t < p.nblocks;  // one thread per block of the kernel that produced the partial sums
+    const double L = stage_L(p, m - 1);
     // candidate threshold of this kernel's lists: log-ratio Lw > L, or none
     double Lw = 0.0;
     if (p.theta > 0.0f) {
         float theta = p.theta;
         if (p.use_hint) {
             const float seen = p.st->theta_seen[m];
-            if (seen == seen) theta = fminf(fmaxf(seen - kHintMargin, theta), kHintMax);
+            if (seen == seen) theta = fminf(fmaxf(seen - kHintMargin, p.theta_min), kHintMax);
         }
-        Lw = L + (double)theta * p.L[m];
+        Lw = L + (double)theta * stage_L(p, m);
     }
     // the producer's candidate fit, for the record of where this stage's threshold falls on its scale
     FitRecord prev_fit;
     prev_fit.gpd = 0;
     prev_fit.loc = 0.0f;
     prev_fit.s = prev_fit.c = prev_fit.a = prev_fit.b = 0.0;
-    if (auto_src && p.prev_cand && blockIdx.x == 0 && threadIdx.x == 0) prev_fit = p.st->cand_fit[m - 1];
+    if (auto_src && p.prev_cand && b.id == 0 && threadIdx.x == 0) prev_fit = p.st->cand_fit[m - 1];
     Fit fit = fit_linear(0.0, 0.0);
     float loc = 0.0f;
     uint32_t status = 0;
@@ -259,7 +271,7 @@ __device__ StageEta stage_prologue(const Params& p, bool auto_src, double (*sh)[
     }
     r.lists_ok = auto_src && (r.eta >= list_eta);  // false for a NaN threshold, which selects nothing anyway
     if (auto_src && !r.lists_ok) status |= kStFallback;
-    if (blockIdx.x == 0 && t == 0) {
+    if (b.id == 0 && t == 0) {
         p.st->diag.eta[m - 1] = r.eta;
         p.st->diag.n[m - 1] = (int64_t)n;
         p.st->diag.stats[m - 1][0] = stats[0];
@@ -283,7 +295,7 @@ __device__ StageEta stage_prologue(const Params& p, bool auto_src, double (*sh)[
             // eta = loc + Q(L_{m-1} + theta * L_m)  ->  theta
             const double tq = (double)r.eta - (double)prev_fit.loc;
             const double Lq = prev_fit.gpd ? log1p(tq * prev_fit.a / prev_fit.b) / prev_fit.a : (tq - prev_fit.c) / prev_fit.s;
-            const float seen = (float)((Lq - p.L[m - 2]) / L);
+            const float seen = (float)((Lq - stage_L(p, m - 2)) / L);
             p.st->theta_seen[m - 1] = (frozen || !(fabsf(seen) < 1.0e6f)) ? __builtin_nanf("") : seen;
         }
     }
@@ -339,11 +351,11 @@ __device__ __forceinline__ void fit_tiles(const f4* __restrict__ g4, f4* __restr
 }
 
 template <int DIST, bool EC>
-__global__ __launch_bounds__(kBlock) void k_fit(Params p)
+__device__ __forceinline__ void fit_body(const Params& p, Blk b)
 {
     __shared__ double sh[kWavesPerBlock][4];
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    const uint32_t w = blockIdx.x * kWavesPerBlock + wib;
+    const uint32_t w = b.id * kWavesPerBlock + wib;
     double s1 = 0.0, s2 = 0.0, sl = 0.0;
     int se = 0;
     if (w < p.nwaves) {
@@ -387,9 +399,9 @@ __global__ __launch_bounds__(kBlock) void k_fit(Params p)
         double tot = 0.0;
 #pragma unroll
         for (int i = 0; i < kWavesPerBlock; ++i) tot += sh[i][threadIdx.x];
-        p.part_out[threadIdx.x * kMaxBlocks + blockIdx.x] = tot;
+        p.part_out[threadIdx.x * kMaxBlocks + b.id] = tot;
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    if (b.id == 0 && threadIdx.x == 0) {
         p.st->status_after[0] = 0;
         p.st->frozen_after[0] = 0;
         p.st->diag.stages = p.M;
@@ -529,8 +541,8 @@ __device__ __forceinline__ void compact_slots(const int4 (&q)[U], uint32_t c, ui
 // without statistics (dense last stage), the number of list entries (k_gather's prefix) - and the
 // block's partial sums of y and y^2, each in its fixed slot.
 template <bool STATS>
-__device__ __forceinline__ void stage_epilogue(const Params& p, int lane, int wib, uint32_t count, double sy, double syy,
-                                               double (*sh)[4], uint32_t* sh_cnt)
+__device__ __forceinline__ void stage_epilogue(const Params& p, Blk b, int lane, int wib, uint32_t count, double sy,
+                                               double syy, double (*sh)[4], uint32_t* sh_cnt)
 {
     if (lane == 0) sh_cnt[wib] = count;
     if (STATS) {
@@ -547,13 +559,13 @@ __device__ __forceinline__ void stage_epilogue(const Params& p, int lane, int wi
         uint32_t tot = 0;
 #pragma unroll
         for (int i = 0; i < kWavesPerBlock; ++i) tot += sh_cnt[i];
-        p.blk_out[blockIdx.x] = tot;
+        p.blk_out[b.id] = tot;
     }
     if (STATS && threadIdx.x < 2) {
         double tot = 0.0;
 #pragma unroll
         for (int i = 0; i < kWavesPerBlock; ++i) tot += sh[i][threadIdx.x];
-        p.part_out[threadIdx.x * kMaxBlocks + blockIdx.x] = tot;
+        p.part_out[threadIdx.x * kMaxBlocks + b.id] = tot;
     }
 }
 
@@ -561,14 +573,14 @@ __device__ __forceinline__ void stage_epilogue(const Params& p, int lane, int wi
 // WRITE: append the entries above eta_w to this stage's lists (eta_w = eta_m, or a candidate threshold
 // above it); a stage whose candidates would still be a large fraction only counts and sums.
 template <bool STATS, bool WRITE>
-__global__ __launch_bounds__(kBlock, 4) void k_compact(Params p)
+__device__ __forceinline__ void compact_body(const Params& p, Blk b)
 {
     __shared__ double sh[kWavesPerBlock][4];
     __shared__ uint32_t sh_cnt[kWavesPerBlock];
     __shared__ int2 ring[WRITE ? kWavesPerBlock : 1][kRingSize];
     constexpr int U = 4;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    const uint32_t w = blockIdx.x * kWavesPerBlock + wib;
+    const uint32_t w = b.id * kWavesPerBlock + wib;
     const bool active = w < p.nwaves;
     const uint32_t t0 = active ? tile_begin(w, p.ntiles, p.nwaves) : 0;
     const uint32_t t1 = active ? tile_begin(w + 1, p.ntiles, p.nwaves) : 0;
@@ -580,7 +592,7 @@ __global__ __launch_bounds__(kBlock, 4) void k_compact(Params p)
     const bool pre_dense = active && p.vec_ok && t0 + U <= tf;
     if (pre_dense) load_tiles<U>(a0, reinterpret_cast<const f4*>(p.acc), dense_first_batch(p, t0, tf, U), lane);
 
-    const StageEta se = stage_prologue(p, false, sh);
+    const StageEta se = stage_prologue(p, b, false, sh);
 
     uint32_t run = 0, ns = 0;
     double sy = 0.0, syy = 0.0;
@@ -593,7 +605,7 @@ __global__ __launch_bounds__(kBlock, 4) void k_compact(Params p)
         if (WRITE) run = list_finish(lw, lane);
         if (lane == 0) p.cnt_out[w] = run;
     }
-    stage_epilogue<STATS>(p, lane, wib, STATS ? ns : run, sy, syy, sh, sh_cnt);
+    stage_epilogue<STATS>(p, b, lane, wib, STATS ? ns : run, sy, syy, sh, sh_cnt);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -607,16 +619,16 @@ __global__ __launch_bounds__(kBlock, 4) void k_compact(Params p)
 // ---------------------------------------------------------------------------------------------
 constexpr int kListGroup = 4;
 
-__global__ __launch_bounds__(kBlock, 4) void k_lists(Params p)
+__device__ __forceinline__ void lists_body(const Params& p, Blk b)
 {
     __shared__ double sh[kWavesPerBlock][4];
     __shared__ uint32_t sh_cnt[kWavesPerBlock];
     __shared__ int2 ring[kWavesPerBlock][kRingSize];
     constexpr int K = kListGroup, U = 4;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    const uint32_t per_block = (p.nwaves + gridDim.x - 1) / gridDim.x;
-    const uint32_t first = blockIdx.x * per_block + wib;
-    const uint32_t last = min(p.nwaves, (blockIdx.x + 1) * per_block);
+    const uint32_t per_block = (p.nwaves + b.n - 1) / b.n;
+    const uint32_t first = b.id * per_block + wib;
+    const uint32_t last = min(p.nwaves, (b.id + 1) * per_block);
 
     uint32_t n0[K];
     int4 q0[K];
@@ -632,7 +644,7 @@ __global__ __launch_bounds__(kBlock, 4) void k_lists(Params p)
                     : make_int4(0, 0, 0, 0);
     }
 
-    const StageEta se = stage_prologue(p, true, sh);
+    const StageEta se = stage_prologue(p, b, true, sh);
     const float eta = se.eta;
 
     uint32_t ns = 0;
@@ -676,7 +688,7 @@ __global__ __launch_bounds__(kBlock, 4) void k_lists(Params p)
             if (lane == 0) p.cnt_out[sw] = n_out;
         }
     }
-    stage_epilogue<true>(p, lane, wib, ns, sy, syy, sh, sh_cnt);
+    stage_epilogue<true>(p, b, lane, wib, ns, sy, syy, sh, sh_cnt);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -774,7 +786,7 @@ __device__ __forceinline__ void final_emit_dense(const Params& p, uint32_t sw, i
     }
 }
 
-__global__ __launch_bounds__(kBlock) void k_final_lists(Params p)
+__device__ __forceinline__ void final_body(const Params& p, Blk b)
 {
     __shared__ double sh[kWavesPerBlock][4];
     __shared__ uint32_t sh_cnt[kWavesPerBlock];
@@ -782,9 +794,9 @@ __global__ __launch_bounds__(kBlock) void k_final_lists(Params p)
     constexpr int K = kFinalGroup;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     // source lists of this wave: first, first + 8, first + 16, ... below last
-    const uint32_t per_block = (p.nwaves + gridDim.x - 1) / gridDim.x;
-    const uint32_t first = blockIdx.x * per_block + wib;
-    const uint32_t last = min(p.nwaves, (blockIdx.x + 1) * per_block);
+    const uint32_t per_block = (p.nwaves + b.n - 1) / b.n;
+    const uint32_t first = b.id * per_block + wib;
+    const uint32_t last = min(p.nwaves, (b.id + 1) * per_block);
 
     // first group of lists: counts and first 64 slots of each, all loads issued together and before
     // the prologue (none depends on the threshold)
@@ -797,7 +809,7 @@ __global__ __launch_bounds__(kBlock) void k_final_lists(Params p)
         q0[k] = (uint32_t)lane < l0[k].cap2 ? l0[k].src4[lane] : make_int4(0, 0, 0, 0);
     }
 
-    const StageEta se = stage_prologue(p, true, sh);
+    const StageEta se = stage_prologue(p, b, true, sh);
     const float eta = se.eta;
 
     // pass A: count
@@ -851,7 +863,7 @@ __global__ __launch_bounds__(kBlock) void k_final_lists(Params p)
         const unsigned long long end = base + tot;
         atomicMax(p.out_count, (int32_t)(end < cap ? end : cap));
         if (end > cap) p.st->overflow = 1u;  // every writer stores the same value
-        if (blockIdx.x == 0) {
+        if (b.id == 0) {
             *p.out_eta = eta;
             p.st->diag.status = p.st->status_after[p.M];  // written by this thread in the prologue
         }
@@ -900,13 +912,13 @@ __global__ __launch_bounds__(kBlock) void k_final_lists(Params p)
 // k_gather: survivor lists of the last stage -> contiguous (index, value) output; residual update.
 // Used when the last stage read the dense vector (M = 1): no atomics, output order is fixed.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void k_gather(Params p)
+__device__ __forceinline__ void gather_body(const Params& p, Blk b)
 {
     __shared__ unsigned long long sh_u[kWavesPerBlock][2];
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
     const uint32_t t = threadIdx.x;
-    const uint32_t w = blockIdx.x * kWavesPerBlock + wib;
-    const uint32_t w0 = blockIdx.x * kWavesPerBlock;
+    const uint32_t w = b.id * kWavesPerBlock + wib;
+    const uint32_t w0 = b.id * kWavesPerBlock;
     const bool active = w < p.nwaves;
     // independent loads first: block counts, the block's wave counts, this wave's count and first entries
     const unsigned long long c = t < p.nblocks ? (unsigned long long)p.blk_in[t] : 0ull;
@@ -918,7 +930,7 @@ __global__ __launch_bounds__(kBlock) void k_gather(Params p)
     if ((uint32_t)lane < cap_w) first = src[lane];
 
     // exclusive prefix of the per-block counts at this block, and their total
-    unsigned long long below = wave_sum_u64(t < blockIdx.x ? c : 0ull);
+    unsigned long long below = wave_sum_u64(t < b.id ? c : 0ull);
     unsigned long long total = wave_sum_u64(c);
     if (lane == 0) {
         sh_u[wib][0] = below;
@@ -933,7 +945,7 @@ __global__ __launch_bounds__(kBlock) void k_gather(Params p)
         total += sh_u[i][1];
     }
     const unsigned long long cap = (unsigned long long)p.out_cap;
-    if (blockIdx.x == 0 && t == 0) {
+    if (b.id == 0 && t == 0) {
         *p.out_count = (int32_t)(total > cap ? cap : total);
         *p.out_eta = p.st->diag.eta[p.M - 1];
         p.st->selected_ctr = total;
@@ -998,6 +1010,99 @@ void launch_scatter_add(float* dense, int64_t d, const int32_t* idx, const float
 }
 
 // ---------------------------------------------------------------------------------------------
+// kernels: one call on one vector (the grid is the vector's), or a batch of vectors in one launch
+// (every block belongs to one vector and finds that vector's arguments in a table on the device)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ Blk whole_grid() { return Blk{blockIdx.x, gridDim.x}; }
+
+// Arguments of this block's vector in a batched launch.  final_grid: the launch uses the last stage's
+// (smaller) grid.
+__device__ __forceinline__ Params batch_params(const BatchArgs& a, bool final_grid, Blk& b)
+{
+    const uint32_t t = __builtin_amdgcn_readfirstlane((uint32_t)(final_grid ? a.tb->fmap[blockIdx.x] : a.tb->map[blockIdx.x]));
+    const TensorDesc& ds = a.tb->desc[t];
+    Params p;
+    p.grad = ds.grad;
+    p.residual = ds.residual;
+    p.acc = ds.residual ? ds.residual : ds.grad;
+    p.d = ds.d;
+    p.ntiles = (uint32_t)((ds.d + kTile - 1) / kTile);
+    p.nfull = (uint32_t)(ds.d / kTile);
+    p.nwaves = ds.nblocks * kWavesPerBlock < p.ntiles ? ds.nblocks * kWavesPerBlock : p.ntiles;
+    p.nblocks = ds.nblocks;
+    p.vec_ok = ds.vec_ok;
+    p.reverse = a.reverse;
+    p.acc_reset = 1;
+    p.dist = a.dist;
+    p.M = a.M;
+    p.stage = a.stage;
+#pragma unroll
+    for (int m = 0; m < SIDCO_MAX_STAGES; ++m) p.L[m] = a.L[m];
+    p.theta = a.theta;
+    p.theta_min = a.theta_min;
+    p.use_hint = a.use_hint;
+    p.prev_cand = a.prev_cand;
+    p.st = &a.tb->st[t];
+    p.part_in = a.part[a.in] + ds.first_block;
+    p.part_out = a.part[a.out] + ds.first_block;
+    p.cnt_in = a.cnt[a.in] + ds.first_block * kWavesPerBlock;
+    p.cnt_out = a.cnt[a.out] + ds.first_block * kWavesPerBlock;
+    p.blk_in = a.blk[a.in] + ds.first_block;
+    p.blk_out = a.blk[a.out] + ds.first_block;
+    p.seg_in = a.seg[a.in] + ds.seg_off;
+    p.seg_out = a.seg[a.out] + ds.seg_off;
+    p.out_idx = ds.out_idx;
+    p.out_val = ds.out_val;
+    p.out_count = ds.out_count;
+    p.out_eta = ds.out_eta;
+    p.out_cap = ds.out_cap;
+    b.id = blockIdx.x - (final_grid ? ds.first_final : ds.first_block);
+    b.n = final_grid ? ds.nfinal : ds.nblocks;
+    return p;
+}
+
+template <int DIST, bool EC>
+__global__ __launch_bounds__(kBlock) void k_fit(Params p) { fit_body<DIST, EC>(p, whole_grid()); }
+template <bool STATS, bool WRITE>
+__global__ __launch_bounds__(kBlock, 4) void k_compact(Params p) { compact_body<STATS, WRITE>(p, whole_grid()); }
+__global__ __launch_bounds__(kBlock, 4) void k_lists(Params p) { lists_body(p, whole_grid()); }
+__global__ __launch_bounds__(kBlock) void k_final_lists(Params p) { final_body(p, whole_grid()); }
+__global__ __launch_bounds__(kBlock) void k_gather(Params p) { gather_body(p, whole_grid()); }
+
+template <int DIST, bool EC>
+__global__ __launch_bounds__(kBlock) void k_fit_batched(BatchArgs a)
+{
+    Blk b;
+    const Params p = batch_params(a, false, b);
+    fit_body<DIST, EC>(p, b);
+}
+template <bool STATS, bool WRITE>
+__global__ __launch_bounds__(kBlock, 4) void k_compact_batched(BatchArgs a)
+{
+    Blk b;
+    const Params p = batch_params(a, false, b);
+    compact_body<STATS, WRITE>(p, b);
+}
+__global__ __launch_bounds__(kBlock, 4) void k_lists_batched(BatchArgs a)
+{
+    Blk b;
+    const Params p = batch_params(a, false, b);
+    lists_body(p, b);
+}
+__global__ __launch_bounds__(kBlock) void k_final_lists_batched(BatchArgs a)
+{
+    Blk b;
+    const Params p = batch_params(a, true, b);
+    final_body(p, b);
+}
+__global__ __launch_bounds__(kBlock) void k_gather_batched(BatchArgs a)
+{
+    Blk b;
+    const Params p = batch_params(a, false, b);
+    gather_body(p, b);
+}
+
+// ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
 template <bool EC>
@@ -1038,6 +1143,47 @@ void launch_final_lists(const Params& p, uint32_t grid_blocks, hipStream_t s)
 void launch_gather(const Params& p, hipStream_t s)
 {
     hipLaunchKernelGGL(k_gather, dim3(p.nblocks), dim3(kBlock), 0, s, p);
+}
+
+// batched: `blocks` is the sum of the vectors' grids (the last stage's own, smaller sum for launch_final)
+template <bool EC>
+static void launch_fit_batched_ec(const BatchArgs& a, uint32_t blocks, hipStream_t s)
+{
+    const dim3 grid(blocks), block(kBlock);
+    switch (a.dist) {
+        case kDistExp: hipLaunchKernelGGL((k_fit_batched<kDistExp, EC>), grid, block, 0, s, a); break;
+        case kDistGamma: hipLaunchKernelGGL((k_fit_batched<kDistGamma, EC>), grid, block, 0, s, a); break;
+        default: hipLaunchKernelGGL((k_fit_batched<kDistGpd, EC>), grid, block, 0, s, a); break;
+    }
+}
+
+void launch_fit_batched(const BatchArgs& a, bool ec, uint32_t blocks, hipStream_t s)
+{
+    if (ec) launch_fit_batched_ec<true>(a, blocks, s);
+    else launch_fit_batched_ec<false>(a, blocks, s);
+}
+
+void launch_compact_batched(const BatchArgs& a, bool stats, bool write, uint32_t blocks, hipStream_t s)
+{
+    const dim3 grid(blocks), block(kBlock);
+    if (stats && write) hipLaunchKernelGGL((k_compact_batched<true, true>), grid, block, 0, s, a);
+    else if (stats) hipLaunchKernelGGL((k_compact_batched<true, false>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((k_compact_batched<false, true>), grid, block, 0, s, a);
+}
+
+void launch_lists_batched(const BatchArgs& a, uint32_t blocks, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_lists_batched, dim3(blocks), dim3(kBlock), 0, s, a);
+}
+
+void launch_final_lists_batched(const BatchArgs& a, uint32_t final_blocks, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_final_lists_batched, dim3(final_blocks), dim3(kBlock), 0, s, a);
+}
+
+void launch_gather_batched(const BatchArgs& a, uint32_t blocks, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_gather_batched, dim3(blocks), dim3(kBlock), 0, s, a);
 }
 
 }  // namespace sidco

@@ -144,3 +144,26 @@ def test_adapt_stages_matches_the_oracle(lib, oracle):
     assert lib.sidco_adapt_stages(0, 1.0, 1.0, 0.2, 0.2, 8) == -4
     assert lib.sidco_adapt_stages(1, 1.0, 0.0, 0.2, 0.2, 8) == -9
     assert lib.sidco_adapt_stages(1, 1.0, 1.0, 0.2, 1.0, 8) == -9
+
+
+def test_batched_argument_errors_and_helpers(lib):
+    ok = C.c_void_p(256)
+    off = (C.c_int64 * 3)(0, 1000, 3000)
+    oo = (C.c_int64 * 3)(0, 100, 300)
+    f = lib.sidco_compress_batched
+    assert f(None, None, None, off, 2, 0.01, 0, 2, ok, ok, oo, ok, ok) == -1
+    assert f(None, ok, None, None, 2, 0.01, 0, 2, ok, ok, oo, ok, ok) == -1
+    assert f(None, ok, None, off, 0, 0.01, 0, 2, ok, ok, oo, ok, ok) == -2
+    assert f(None, ok, None, off, 513, 0.01, 0, 2, ok, ok, oo, ok, ok) == -2
+    assert f(None, ok, None, (C.c_int64 * 3)(0, 1000, 1000), 2, 0.01, 0, 2, ok, ok, oo, ok, ok) == -2   # empty tensor
+    assert f(None, ok, None, off, 2, 0.01, 0, 2, ok, ok, (C.c_int64 * 3)(0, 100, 100), ok, ok) == -2    # no room
+    assert f(None, ok, None, off, 2, 1.0, 0, 2, ok, ok, oo, ok, ok) == -3
+    assert f(None, ok, None, off, 2, 0.01, 5, 2, ok, ok, oo, ok, ok) == -5
+    assert f(None, ok, None, off, 2, 0.01, 0, 0, ok, ok, oo, ok, ok) == -4
+    assert f(None, ok, ok, off, 2, 0.01, 0, 2, ok, ok, oo, ok, ok) == -9
+    offs = [0, 1000, 3000, 3001]
+    got = sidco.sidco_batched_out_offsets(offs, 0.01)
+    caps = [sidco.sidco_out_capacity(b - a, 0.01) for a, b in zip(offs, offs[1:])]
+    assert got == [0, caps[0], caps[0] + caps[1], sum(caps)]
+    assert sidco.sidco_workspace_bytes_batched(offs) >= 2 * 8 * (1024 + 2048 + 256)
+    assert lib.sidco_read_diag_batched(None, 0, None) == -1

@@ -355,9 +355,14 @@ def test_fallback_in_the_last_stage_respects_capacity_and_ragged_ends(oracle):
     d = 333_337
     g = _light_tailed(d, 53)
     for cap in (None, 50):
+        run_gpu(g[:1000], None, 0, [0.1])     # another shape in between: the next call starts without a hint
         out = run_gpu(g, np.zeros(d, np.float32), 0, [0.25, 0.2], cap=cap, grad_offset=1, res_offset=3)
         check_parity(oracle, g, np.zeros(d, np.float32), 0, [0.25, 0.2], out, capacity=cap, label=f"fallback cap={cap}")
         assert out.status & 64 and out.selected > 0.02 * d
+    # the same call again: the hint now says how low the next threshold falls, and the lists reach down to it
+    again = run_gpu(g, np.zeros(d, np.float32), 0, [0.25, 0.2], cap=50, grad_offset=1, res_offset=3)
+    check_parity(oracle, g, np.zeros(d, np.float32), 0, [0.25, 0.2], again, capacity=50, label="fallback learnt")
+    assert not again.status & 64
 
 
 @pytest.mark.parametrize("dist", DISTS)
