@@ -566,8 +566,7 @@ struct BatchPlan {
 };
 
 // Splits the 512 blocks of a launch over the vectors in proportion to their lengths (at least one each).
-int plan_batch(const float* grad, float* residual, const int64_t* offsets, int n, int32_t* out_idx, float* out_val,
-               const int64_t* out_offsets, int32_t* out_counts, float* out_etas, BatchPlan& pl)
+int plan_batch(const int64_t* offsets, int n, const int64_t* out_offsets, BatchPlan& pl)
 {
     if (n < 1 || n > kMaxBatch) return SIDCO_ERR_SIZE;
     uint64_t tiles_total = 0;
@@ -588,20 +587,16 @@ int plan_batch(const float* grad, float* residual, const int64_t* offsets, int n
         const uint64_t ntiles = (uint64_t)((d + kTile - 1) / kTile);
         uint64_t share = 1 + ((uint64_t)(kMaxBlocks - n) * ntiles) / tiles_total;
         uint64_t nwaves = share * kWavesPerBlock < ntiles ? share * kWavesPerBlock : ntiles;
-        ds.grad = grad + offsets[t];
-        ds.residual = residual ? residual + offsets[t] : nullptr;
+        ds.offset = offsets[t];
         ds.d = d;
         ds.first_block = fb;
         ds.nblocks = (uint32_t)((nwaves + kWavesPerBlock - 1) / kWavesPerBlock);
         ds.first_final = ff;
         ds.nfinal = (uint32_t)((nwaves + 31) / 32);
         ds.seg_off = slot;
-        ds.out_idx = out_idx + out_offsets[t];
-        ds.out_val = out_val + out_offsets[t];
-        ds.out_count = out_counts + t;
-        ds.out_eta = out_etas + t;
+        ds.out_offset = out_offsets[t];
         ds.out_cap = out_offsets[t + 1] - out_offsets[t];
-        ds.vec_ok = aligned16(ds.grad) && aligned16(ds.residual);
+        ds.index = (uint32_t)t;
         ds.reserved = 0;
         for (uint32_t i = 0; i < ds.nblocks; ++i) pl.map[fb + i] = (uint16_t)t;
         for (uint32_t i = 0; i < ds.nfinal; ++i) pl.fmap[ff + i] = (uint16_t)t;
@@ -659,7 +654,7 @@ int sidco_compress_batched(void* stream, const float* grad, float* residual, con
     const int M = sidco_stage_ratios(delta, stages, 0.25, ratios);
     if (M < 1) return M;
     BatchPlan pl;
-    int rc = plan_batch(grad, residual, offsets, n, out_idx, out_val, out_offsets, out_counts, out_etas, pl);
+    int rc = plan_batch(offsets, n, out_offsets, pl);
     if (rc != SIDCO_OK) return rc;
 
     std::lock_guard<std::mutex> lock(g_mu);
@@ -708,6 +703,12 @@ int sidco_compress_batched(void* stream, const float* grad, float* residual, con
     BatchArgs a;
     memset(&a, 0, sizeof(a));
     a.tb = &h->batch;
+    a.grad = grad;
+    a.residual = residual;
+    a.out_idx = out_idx;
+    a.out_val = out_val;
+    a.out_counts = out_counts;
+    a.out_etas = out_etas;
     const size_t seg = pl.slots * sizeof(int2);
     for (int i = 0; i < 2; ++i) {
         a.part[i] = h->part[i];

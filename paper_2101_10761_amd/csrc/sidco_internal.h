@@ -153,22 +153,20 @@ struct Blk {
 // ---- batched calls: several vectors (the tensors of one flat buffer) in one launch sequence ----
 constexpr int kMaxBatch = kMaxBlocks;  // every vector owns at least one block of the 512-block launches
 
+// One vector of a batch, relative to the call's base pointers (so that the table on the device depends on
+// the layout alone and survives a change of buffers).
 struct TensorDesc {
-    const float* grad;      // the vector's first element
-    float* residual;        // NULL: memoryless
+    int64_t offset;         // first element in grad / residual
     int64_t d;
+    int64_t out_offset;     // first pair in out_idx / out_val
+    int64_t out_cap;
+    uint64_t seg_off;       // first slot of the vector in the survivor-list buffers
     uint32_t first_block;   // the vector's blocks in the dense grids: [first_block, first_block + nblocks)
     uint32_t nblocks;
     uint32_t first_final;   // ... and in the last stage's grid
     uint32_t nfinal;
-    uint64_t seg_off;       // first slot of the vector in the survivor-list buffers
-    int32_t* out_idx;
-    float* out_val;
-    int32_t* out_count;
-    float* out_eta;
-    int64_t out_cap;
-    int vec_ok;
-    int reserved;
+    uint32_t index;         // position in out_counts / out_etas
+    uint32_t reserved;
 };
 
 struct BatchTable {
@@ -181,6 +179,12 @@ struct BatchTable {
 // Kernel arguments of a batched launch (by value): what all vectors share.
 struct BatchArgs {
     BatchTable* tb;
+    const float* grad;      // base pointers of the call
+    float* residual;
+    int32_t* out_idx;
+    float* out_val;
+    int32_t* out_counts;
+    float* out_etas;
     double* part[2];
     uint32_t* cnt[2];
     uint32_t* blk[2];

@@ -1022,15 +1022,15 @@ __device__ __forceinline__ Params batch_params(const BatchArgs& a, bool final_gr
     const uint32_t t = __builtin_amdgcn_readfirstlane((uint32_t)(final_grid ? a.tb->fmap[blockIdx.x] : a.tb->map[blockIdx.x]));
     const TensorDesc& ds = a.tb->desc[t];
     Params p;
-    p.grad = ds.grad;
-    p.residual = ds.residual;
-    p.acc = ds.residual ? ds.residual : ds.grad;
+    p.grad = a.grad + ds.offset;
+    p.residual = a.residual ? a.residual + ds.offset : nullptr;
+    p.acc = p.residual ? p.residual : p.grad;
     p.d = ds.d;
     p.ntiles = (uint32_t)((ds.d + kTile - 1) / kTile);
     p.nfull = (uint32_t)(ds.d / kTile);
     p.nwaves = ds.nblocks * kWavesPerBlock < p.ntiles ? ds.nblocks * kWavesPerBlock : p.ntiles;
     p.nblocks = ds.nblocks;
-    p.vec_ok = ds.vec_ok;
+    p.vec_ok = (((uintptr_t)p.grad | (uintptr_t)p.residual) & 15u) == 0;
     p.reverse = a.reverse;
     p.acc_reset = 1;
     p.dist = a.dist;
@@ -1051,10 +1051,10 @@ __device__ __forceinline__ Params batch_params(const BatchArgs& a, bool final_gr
     p.blk_out = a.blk[a.out] + ds.first_block;
     p.seg_in = a.seg[a.in] + ds.seg_off;
     p.seg_out = a.seg[a.out] + ds.seg_off;
-    p.out_idx = ds.out_idx;
-    p.out_val = ds.out_val;
-    p.out_count = ds.out_count;
-    p.out_eta = ds.out_eta;
+    p.out_idx = a.out_idx + ds.out_offset;
+    p.out_val = a.out_val + ds.out_offset;
+    p.out_count = a.out_counts + ds.index;
+    p.out_eta = a.out_etas + ds.index;
     p.out_cap = ds.out_cap;
     b.id = blockIdx.x - (final_grid ? ds.first_final : ds.first_block);
     b.n = final_grid ? ds.nfinal : ds.nblocks;
