@@ -246,7 +246,7 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
 
     // stage-1 sums (and acc) -> part[0]
     p.part_out = h->part[0];
-    launch_fit(p, s);
+    launch_fit(p, (double*)segbuf[1], s);  // the second list buffer is free until the first stage kernel writes it
 
     ++k;
     mark("k_fit");
@@ -892,7 +892,7 @@ int sidco_fit(void* stream, const float* grad, float* residual, int64_t d, int d
     p.M = 1;
     p.acc_reset = 1;
     p.part_out = h->part[0];
-    launch_fit(p, (hipStream_t)stream);
+    launch_fit(p, (double*)((char*)cp->ws + head_bytes() + seg_bytes(d)), (hipStream_t)stream);
     cp->fit_nblocks = p.nblocks;
     cp->fit_d = d;
     cp->fit_dist = dist;

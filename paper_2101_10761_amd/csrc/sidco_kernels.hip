@@ -350,6 +350,22 @@ __device__ __forceinline__ void fit_tiles(const f4* __restrict__ g4, f4* __restr
     }
 }
 
+// start of a call: per-call device state, by one thread
+__device__ __forceinline__ void fit_reset_state(const Params& p)
+{
+    p.st->status_after[0] = 0;
+    p.st->frozen_after[0] = 0;
+    p.st->diag.stages = p.M;
+    // Adapt_Stages bookkeeping: the pairs the previous call reported join the running count
+    const unsigned long long prev_sel = p.st->selected_ctr;
+    const unsigned long long prev_cap = (unsigned long long)p.st->prev_cap;
+    p.st->khat_sum = p.acc_reset ? 0ull : p.st->khat_sum + (prev_sel < prev_cap ? prev_sel : prev_cap);
+    p.st->prev_cap = (long long)p.out_cap;
+    p.st->selected_ctr = 0;
+    p.st->overflow = 0;
+    if (p.out_count) *p.out_count = 0;
+}
+
 template <int DIST, bool EC>
 __device__ __forceinline__ void fit_body(const Params& p, Blk b)
 {
@@ -401,19 +417,90 @@ __device__ __forceinline__ void fit_body(const Params& p, Blk b)
         for (int i = 0; i < kWavesPerBlock; ++i) tot += sh[i][threadIdx.x];
         p.part_out[threadIdx.x * kMaxBlocks + b.id] = tot;
     }
-    if (b.id == 0 && threadIdx.x == 0) {
-        p.st->status_after[0] = 0;
-        p.st->frozen_after[0] = 0;
-        p.st->diag.stages = p.M;
-        // Adapt_Stages bookkeeping: the pairs the previous call reported join the running count
-        const unsigned long long prev_sel = p.st->selected_ctr;
-        const unsigned long long prev_cap = (unsigned long long)p.st->prev_cap;
-        p.st->khat_sum = p.acc_reset ? 0ull : p.st->khat_sum + (prev_sel < prev_cap ? prev_sel : prev_cap);
-        p.st->prev_cap = (long long)p.out_cap;
-        p.st->selected_ctr = 0;
-        p.st->overflow = 0;
-        if (p.out_count) *p.out_count = 0;
+    if (b.id == 0 && threadIdx.x == 0) fit_reset_state(p);
+}
+
+// ---------------------------------------------------------------------------------------------
+// k_fit_flat + k_fit_reduce: the same pass for large vectors.  One float4 per thread and a grid that
+// covers the vector in address order: the blocks in flight at any time touch one narrow window of each
+// buffer, which DRAM serves better than the 3 x 4096 separate streams of the per-wave ranges once
+// those ranges are long (measured inside a call at d = 138 M: 303 us against 354 us; no gain at 66 M, a loss at 25 M).
+// The price is one partial sum per 256-thread block - far too many for every block of the next
+// kernel to add up - so a second, small kernel folds them into the usual 512 slots, in a fixed order.
+// ---------------------------------------------------------------------------------------------
+template <int DIST, bool EC>
+__global__ __launch_bounds__(kFlatBlock) void k_fit_flat(Params p, double* __restrict__ flat_part, uint32_t nflat)
+{
+    __shared__ double sh[kFlatBlock / 64][4];
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    const size_t nvec = (size_t)(p.d / 4);
+    const size_t i = (size_t)blockIdx.x * kFlatBlock + threadIdx.x;
+    double s1 = 0.0, s2 = 0.0, sl = 0.0;
+    int se = 0;
+    if (i < nvec) {
+        const f4* __restrict__ g4 = reinterpret_cast<const f4*>(p.grad);
+        f4* __restrict__ r4 = reinterpret_cast<f4*>(p.residual);
+        f4 c = EC ? __builtin_nontemporal_load(g4 + i) : g4[i];
+        if (EC) {
+            c = c + r4[i];
+            r4[i] = c;
+        }
+        fit_accum<DIST>(c.x, s1, s2, sl, se);
+        fit_accum<DIST>(c.y, s1, s2, sl, se);
+        fit_accum<DIST>(c.z, s1, s2, sl, se);
+        fit_accum<DIST>(c.w, s1, s2, sl, se);
     }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {  // the last d % 4 elements
+        for (int64_t j = (int64_t)nvec * 4; j < p.d; ++j) {
+            float c = p.grad[j];
+            if (EC) {
+                c = c + p.residual[j];
+                p.residual[j] = c;
+            }
+            fit_accum<DIST>(c, s1, s2, sl, se);
+        }
+    }
+    double v[3] = {s1, s2, sl + (double)se};
+    v[0] = wave_sum(v[0]);
+    v[1] = wave_sum(v[1]);
+    v[2] = wave_sum(v[2]);
+    if (lane == 0) {
+        sh[wib][0] = v[0];
+        sh[wib][1] = v[1];
+        sh[wib][2] = v[2];
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        double tot = 0.0;
+#pragma unroll
+        for (int w = 0; w < kFlatBlock / 64; ++w) tot += sh[w][threadIdx.x];
+        flat_part[(size_t)threadIdx.x * nflat + blockIdx.x] = tot;
+    }
+}
+
+// Slot s of the 512 receives the partial sums of the flat blocks [s * per, (s + 1) * per): one wave
+// per slot, every lane adds its share in order, then the lanes are combined in a fixed order.
+__global__ __launch_bounds__(kBlock) void k_fit_reduce(Params p, const double* __restrict__ flat_part, uint32_t nflat,
+                                                       uint32_t per)
+{
+    const int lane = threadIdx.x & 63;
+    const uint32_t slot = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    const uint32_t b0 = slot * per, b1 = b0 + per < nflat ? b0 + per : nflat;
+    double v[3] = {0.0, 0.0, 0.0};
+    for (uint32_t b = b0 + lane; b < b1; b += 64) {
+        v[0] += flat_part[b];
+        if (p.dist == kDistGpd) v[1] += flat_part[(size_t)nflat + b];
+        if (p.dist == kDistGamma) v[2] += flat_part[2 * (size_t)nflat + b];
+    }
+    v[0] = wave_sum(v[0]);
+    v[1] = wave_sum(v[1]);
+    v[2] = wave_sum(v[2]);
+    if (lane == 0 && slot < (uint32_t)kMaxBlocks) {
+        p.part_out[0 * kMaxBlocks + slot] = v[0];
+        p.part_out[1 * kMaxBlocks + slot] = v[1];
+        p.part_out[2 * kMaxBlocks + slot] = v[2];
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) fit_reset_state(p);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1116,8 +1203,28 @@ static void launch_fit_ec(const Params& p, hipStream_t s)
     }
 }
 
-void launch_fit(const Params& p, hipStream_t s)
+template <bool EC>
+static void launch_fit_flat_ec(const Params& p, double* flat_part, uint32_t nflat, hipStream_t s)
 {
+    const dim3 grid(nflat), block(kFlatBlock);
+    switch (p.dist) {
+        case kDistExp: hipLaunchKernelGGL((k_fit_flat<kDistExp, EC>), grid, block, 0, s, p, flat_part, nflat); break;
+        case kDistGamma: hipLaunchKernelGGL((k_fit_flat<kDistGamma, EC>), grid, block, 0, s, p, flat_part, nflat); break;
+        default: hipLaunchKernelGGL((k_fit_flat<kDistGpd, EC>), grid, block, 0, s, p, flat_part, nflat); break;
+    }
+}
+
+// `scratch`: device memory for 3 * fit_flat_blocks(d) doubles when the flat shape is used (else unused)
+void launch_fit(const Params& p, double* scratch, hipStream_t s)
+{
+    if (fit_uses_flat(p.d, p.vec_ok != 0)) {
+        const uint32_t nflat = fit_flat_blocks(p.d);
+        if (p.residual) launch_fit_flat_ec<true>(p, scratch, nflat, s);
+        else launch_fit_flat_ec<false>(p, scratch, nflat, s);
+        const uint32_t per = (nflat + kMaxBlocks - 1) / kMaxBlocks;
+        hipLaunchKernelGGL(k_fit_reduce, dim3(kMaxBlocks / kWavesPerBlock), dim3(kBlock), 0, s, p, scratch, nflat, per);
+        return;
+    }
     if (p.residual) launch_fit_ec<true>(p, s);
     else launch_fit_ec<false>(p, s);
 }

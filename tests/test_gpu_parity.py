@@ -366,7 +366,8 @@ def test_fallback_in_the_last_stage_respects_capacity_and_ragged_ends(oracle):
 
 
 @pytest.mark.parametrize("dist", DISTS)
-@pytest.mark.parametrize("d,off", [(1, 0), (257, 0), (1_000_003, 0), (3_000_001, 1), (25_557_032, 0)])
+@pytest.mark.parametrize("d,off", [(1, 0), (257, 0), (1_000_003, 0), (3_000_001, 1), (25_557_032, 0),
+                                   (100_000_003, 0)])   # the last one takes the large-vector launch shape
 def test_fit_alone(oracle, dist, d, off):
     """Steps 1-2 on their own: acc bit-exact (one fp32 add), sums within 1e-5 of the oracle's moments."""
     import torch
