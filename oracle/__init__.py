@@ -12,11 +12,15 @@ from .binding import (  # noqa: F401
     ST_GAMMA_S,
     ST_GAMMA_CLAMP,
     ST_STOPPED,
+    DgcResult,
     OracleResult,
     adapt_stages,
     adaptive_run,
     build,
     compress,
+    dgc,
+    dgc_sample_indices,
+    dgc_sizes,
     ec_add,
     eta_exp,
     eta_gamma,
@@ -28,5 +32,6 @@ from .binding import (  # noqa: F401
     scatter_add,
     schedule,
     select,
+    splitmix64,
     topk,
 )

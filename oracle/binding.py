@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import ctypes as C
+import math
 import os
 import subprocess
 from dataclasses import dataclass
@@ -68,6 +69,13 @@ def _load():
         lib.sidco_oracle_scatter_add.restype = C.c_int64
         lib.sidco_oracle_topk.argtypes = [f32p, C.c_int64, C.c_int64, i32p]
         lib.sidco_oracle_topk.restype = C.c_int64
+        lib.sidco_oracle_splitmix64.argtypes = [C.c_uint64, C.c_uint64]
+        lib.sidco_oracle_splitmix64.restype = C.c_uint64
+        lib.sidco_oracle_dgc_sample_index.argtypes = [C.c_uint64, C.c_uint64, C.c_int64]
+        lib.sidco_oracle_dgc_sample_index.restype = C.c_int64
+        lib.sidco_oracle_dgc.argtypes = [f32p, f32p, C.c_int64, C.c_double, C.c_int64, C.c_uint64, i32p, f32p, i64p,
+                                         f32p, i64p]
+        lib.sidco_oracle_dgc.restype = C.c_int
         _lib = lib
     return _lib
 
@@ -236,3 +244,52 @@ def scatter_add(dense, idx, val, scale=1.0):
     return int(_load().sidco_oracle_scatter_add(
         dense.ctypes.data_as(C.POINTER(C.c_float)), dense.size, idx.ctypes.data_as(C.POINTER(C.c_int32)),
         val.ctypes.data_as(C.POINTER(C.c_float)), idx.size, np.float32(scale)))
+
+
+def splitmix64(seed, j):
+    return int(_load().sidco_oracle_splitmix64(seed, j))
+
+
+def dgc_sample_indices(seed, n_s, d):
+    lib = _load()
+    return np.array([lib.sidco_oracle_dgc_sample_index(seed, j, d) for j in range(n_s)], dtype=np.int64)
+
+
+def dgc_sizes(d, delta, sample_ratio):
+    """(n_s, k_s, k) of the DGC comparator (readings R18, R19, R21)."""
+    n_s = min(max(int(math.ceil(sample_ratio * float(d))), 1), d)
+    k_s = min(max(int(math.ceil(delta * float(n_s))), 1), n_s)
+    k = min(max(int(math.ceil(delta * float(d))), 1), d)
+    return n_s, k_s, k
+
+
+@dataclass
+class DgcResult:
+    idx: np.ndarray          # ascending
+    val: np.ndarray
+    count: int
+    eta: np.float32          # threshold from the subset
+    first_pass: int          # entries above it, before the trim to k
+    residual: np.ndarray | None
+
+
+def dgc(g, residual=None, *, delta, sample_ratio=0.01, seed=0) -> DgcResult:
+    """DGC's sampling threshold with the hierarchical trim (Sec. 1, related work and its footnote)."""
+    g, gp = _f32(g)
+    d = g.size
+    n_s, _, k = dgc_sizes(d, delta, sample_ratio)
+    r = rp = None
+    if residual is not None:
+        r = np.array(residual, dtype=np.float32, copy=True)
+        rp = r.ctypes.data_as(C.POINTER(C.c_float))
+    idx = np.empty(k, dtype=np.int32)
+    val = np.empty(k, dtype=np.float32)
+    count, first = C.c_int64(0), C.c_int64(0)
+    eta = C.c_float(0)
+    rc = _load().sidco_oracle_dgc(gp, rp, d, delta, n_s, seed, idx.ctypes.data_as(C.POINTER(C.c_int32)),
+                                  val.ctypes.data_as(C.POINTER(C.c_float)), C.byref(count), C.byref(eta),
+                                  C.byref(first))
+    if rc != 0:
+        raise MemoryError("sidco_oracle_dgc failed")
+    n = count.value
+    return DgcResult(idx[:n].copy(), val[:n].copy(), n, np.float32(eta.value), first.value, r)

@@ -412,3 +412,119 @@ int64_t sidco_oracle_topk(const float *acc, int64_t d, int64_t k, int32_t *idx)
     free(m);
     return k;
 }
+
+/* ------------------------------------------------------------------------ */
+/* DGC's sampling threshold, the comparator the paper describes in Sec. 1
+ * (related work, with its footnote): draw a random subset of the gradient
+ * (about 1 %), take Top-k of that subset at the same ratio to obtain a
+ * threshold, select with the threshold, and - if that selects more than the
+ * target k - run Top-k once more on the selected entries.
+ *
+ * Readings (the paper gives no more than the sentence above):
+ *   R18 the subset is n_s draws WITH replacement; draw j is element
+ *       floor(u_j * d / 2^32), u_j = the upper 32 bits of output j of the
+ *       splitmix64 sequence started at `seed` (a counter-based generator, so
+ *       the draws can be made in any order);
+ *   R19 k_s = ceil(delta * n_s) (at least 1); the threshold is the k_s-th
+ *       largest magnitude of the subset, bit patterns ordered as unsigned
+ *       integers (a NaN sorts above infinity);
+ *   R20 the first pass selects |acc| > threshold, strictly, in fp32, as C_eta;
+ *   R21 k = ceil(delta * d); with more than k selected the k of largest
+ *       magnitude stay (ties: lower index first here; any choice is valid);
+ *       with k or fewer selected they all stay - no second threshold search.
+ */
+static uint64_t splitmix64_at(uint64_t seed, uint64_t j)
+{
+    /* output j (j = 0 is the first) of the sequence whose state starts at seed */
+    uint64_t z = seed + (j + 1u) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+uint64_t sidco_oracle_splitmix64(uint64_t seed, uint64_t j) { return splitmix64_at(seed, j); }
+
+int64_t sidco_oracle_dgc_sample_index(uint64_t seed, uint64_t j, int64_t d)
+{
+    uint64_t u = splitmix64_at(seed, j) >> 32;
+    return (int64_t)((u * (uint64_t)d) >> 32);
+}
+
+static int u32_desc(const void *p, const void *q)
+{
+    uint32_t x = *(const uint32_t *)p, y = *(const uint32_t *)q;
+    return (x < y) - (x > y);
+}
+static uint32_t mag_bits(float x)
+{
+    uint32_t b;
+    memcpy(&b, &x, 4);
+    return b & 0x7fffffffu;
+}
+
+static int dgc_above(float x, float eta) { return fabsf(x) > eta; } /* R20 */
+
+/* g, r as in sidco_oracle_compress (r in/out, may be NULL).  idx/val have room
+ * for k = ceil(delta*d) pairs; idx is written in ascending order.  Returns 0,
+ * or -1 when out of memory.                                                  */
+int sidco_oracle_dgc(const float *g, float *r, int64_t d, double delta, int64_t n_s,
+                     uint64_t seed, int32_t *idx, float *val, int64_t *count,
+                     float *eta_out, int64_t *first_pass)
+{
+    float *acc_own = NULL, *acc = r;
+    if (!r) {
+        acc_own = (float *)malloc((size_t)d * sizeof(float));
+        if (!acc_own) return -1;
+        acc = acc_own;
+    }
+    sidco_oracle_ec_add(g, r, d, acc);
+
+    /* threshold from the subset */
+    uint32_t *keys = (uint32_t *)malloc((size_t)n_s * sizeof(uint32_t));
+    if (!keys) { free(acc_own); return -1; }
+    for (int64_t j = 0; j < n_s; ++j)
+        keys[j] = mag_bits(acc[sidco_oracle_dgc_sample_index(seed, (uint64_t)j, d)]);
+    qsort(keys, (size_t)n_s, sizeof(uint32_t), u32_desc);
+    int64_t k_s = (int64_t)ceil(delta * (double)n_s);
+    if (k_s < 1) k_s = 1;
+    if (k_s > n_s) k_s = n_s;
+    uint32_t kappa = keys[k_s - 1];
+    free(keys);
+    float eta;
+    memcpy(&eta, &kappa, 4);
+    *eta_out = eta;
+
+    /* first pass: everything above the threshold */
+    int64_t k = (int64_t)ceil(delta * (double)d);
+    if (k < 1) k = 1;
+    if (k > d) k = d;
+    int64_t n_sel = 0;
+    for (int64_t j = 0; j < d; ++j)
+        if (dgc_above(acc[j], eta)) ++n_sel;
+    *first_pass = n_sel;
+
+    mag_t *m = (mag_t *)malloc((size_t)(n_sel > 0 ? n_sel : 1) * sizeof(mag_t));
+    if (!m) { free(acc_own); return -1; }
+    int64_t n = 0;
+    for (int64_t j = 0; j < d; ++j)
+        if (dgc_above(acc[j], eta)) {
+            m[n].a = fabsf(acc[j]);
+            m[n].j = (int32_t)j;
+            ++n;
+        }
+    /* second pass only if the first one selected too many */
+    int64_t keep = n_sel;
+    if (n_sel > k) {
+        qsort(m, (size_t)n_sel, sizeof(mag_t), mag_cmp);
+        keep = k;
+    }
+    for (int64_t i = 0; i < keep; ++i) idx[i] = m[i].j;
+    free(m);
+    qsort(idx, (size_t)keep, sizeof(int32_t), i32_cmp);
+    for (int64_t i = 0; i < keep; ++i) {
+        val[i] = acc[idx[i]];
+        if (r) r[idx[i]] = 0.0f;
+    }
+    *count = keep;
+    free(acc_own);
+    return 0;
+}

@@ -1,5 +1,5 @@
 """Shows that the oracle's pins are sharp: each plausible mistake, planted in a copy of the oracle's
-source on the CPU, makes tests/test_oracle_pins.py fail."""
+source on the CPU, makes tests/test_oracle_pins.py or tests/test_oracle_dgc.py fail."""
 import os
 import subprocess
 import sys
@@ -46,6 +46,16 @@ MUTANTS = [
     ("scatter_overwrites", "volatile float sum = dense[j] + prod;", "volatile float sum = prod;"),
     ("scatter_upper_bound_off_by_one", "if (j < 0 || j >= d) {", "if (j < 0 || j > d) {"),
     ("signed_values_lost", "if (val) val[k] = acc[j];", "if (val) val[k] = fabsf(acc[j]);"),
+    # the DGC comparator
+    ("dgc_generator_shift", "z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;", "z = (z ^ (z >> 29)) * 0x94D049BB133111EBull;"),
+    ("dgc_generator_first_output_skipped", "seed + (j + 1u) * 0x9E3779B97F4A7C15ull", "seed + (j + 2u) * 0x9E3779B97F4A7C15ull"),
+    ("dgc_index_from_low_bits", "uint64_t u = splitmix64_at(seed, j) >> 32;", "uint64_t u = splitmix64_at(seed, j) & 0xffffffffu;"),
+    ("dgc_rank_off_by_one", "uint32_t kappa = keys[k_s - 1];", "uint32_t kappa = keys[k_s];"),
+    ("dgc_sorted_ascending", "return (x < y) - (x > y);", "return (x > y) - (x < y);"),
+    ("dgc_first_pass_non_strict", "{ return fabsf(x) > eta; }", "{ return fabsf(x) >= eta; }"),
+    ("dgc_always_trims_to_k_s", "keep = k;", "keep = k_s;"),
+    ("dgc_sample_of_gradient_not_acc", "keys[j] = mag_bits(acc[", "keys[j] = mag_bits(g["),
+    ("dgc_residual_kept", "if (r) r[idx[i]] = 0.0f;", ""),
 ]
 
 
@@ -61,7 +71,8 @@ def _run_mutant(args):
                    check=True, capture_output=True)
     env = dict(os.environ, SIDCO_ORACLE_LIB=lib)
     p = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
-                        os.path.join(ROOT, "tests", "test_oracle_pins.py")],
+                        os.path.join(ROOT, "tests", "test_oracle_pins.py"),
+                        os.path.join(ROOT, "tests", "test_oracle_dgc.py")],
                        cwd=ROOT, env=env, capture_output=True, text=True)
     return name, p.returncode
 
