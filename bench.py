@@ -61,6 +61,7 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-topk", action="store_true", help="skip the exact Top-k comparator leg")
+    ap.add_argument("--no-dgc", action="store_true", help="skip the DGC comparator leg")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (the sparsifier is local to a worker: no collectives, "
@@ -213,6 +214,49 @@ def main():
         log(f"top-k comparator (k={k}): {topk_ms * 1e3:.1f} us/step -> {topk['value']} G elem/s; "
             f"SIDCo is {topk['sidco_speedup_over_topk']}x faster")
 
+    # Comparator: DGC's sampling threshold (1 % subset, fresh seed every step) on the same gradients, own carried
+    # residual; reports its time and how close the threshold's own selection comes to k (before the trim)
+    dgc = None
+    if not args.no_dgc:
+        rho = 0.01
+        n_s, k_s, k = sidco.sidco_dgc_sizes(d, w.delta, rho)
+        g_idx = torch.empty(k, dtype=torch.int32, device=dev)
+        g_val = torch.empty(k, dtype=torch.float32, device=dev)
+        g_cnt = torch.zeros(1, dtype=torch.int32, device=dev)
+        g_eta = torch.zeros(1, dtype=torch.float32, device=dev)
+        g_res = torch.from_numpy(w.residual).to(dev) if ec else None
+        n_dgc = max(1, min(args.steps, 100))
+        for i in range(10):
+            sidco.sidco_dgc(grads[i % nbuf], g_res, w.delta, rho, i, g_idx, g_val, g_cnt, g_eta, stream=stream)
+        torch.cuda.synchronize()
+        tt = time.perf_counter()
+        for i in range(n_dgc):
+            sidco.sidco_dgc(grads[(10 + i) % nbuf], g_res, w.delta, rho, 10 + i, g_idx, g_val, g_cnt, g_eta,
+                            stream=stream)
+        torch.cuda.synchronize()
+        dgc_ms = (time.perf_counter() - tt) * 1e3 / n_dgc
+        firsts = []
+        sidco.sidco_set_profiling(True)
+        dgc_kern: dict[str, list[float]] = {}
+        for i in range(min(args.profile_steps, 20)):
+            sidco.sidco_dgc(grads[i % nbuf], g_res, w.delta, rho, 1000 + i, g_idx, g_val, g_cnt, g_eta, stream=stream)
+            for name, ms in sidco.sidco_get_profile():
+                dgc_kern.setdefault(name, []).append(ms)
+            firsts.append(sidco.sidco_dgc_result(stream)[2] / k)
+        sidco.sidco_set_profiling(False)
+        dgc = {
+            "kind": "DGC sampling threshold: radix select on a 1 % subset, one pass, trim to k by a second select "
+                    "(own HIP kernels)",
+            "sample_ratio": rho, "n_sample": n_s, "k_sample": k_s, "k": k, "steps": n_dgc,
+            "ms_per_step": round(dgc_ms, 5), "value": round(d / (dgc_ms * 1e-3) / 1e9, 2), "unit": "G elem/s",
+            "sidco_speedup_over_dgc": round(dgc_ms / ms_per_step, 3),
+            "first_pass_over_k": {"mean": round(float(np.mean(firsts)), 4), "min": round(float(np.min(firsts)), 4),
+                                  "max": round(float(np.max(firsts)), 4)} if firsts else None,
+            "kernels_us": {n: round(float(np.mean(v)) * 1e3, 2) for n, v in dgc_kern.items()},
+        }
+        log(f"DGC comparator (n_s={n_s}, k={k}): {dgc_ms * 1e3:.1f} us/step -> {dgc['value']} G elem/s; "
+            f"first-pass count / k = {dgc['first_pass_over_k']}")
+
     # Layer-wise mode of a multi-tensor vector: every tensor sparsified on its own, (i) all tensors in one
     # batched launch sequence, (ii) one call per tensor
     per_tensor = None
@@ -293,7 +337,7 @@ def main():
                         f"stages={w.stages}, delta1={w.delta1}, error_feedback={'on' if ec else 'off'}",
             "gradient_buffers_in_rotation": nbuf, "khat_over_k": round(float(np.mean(khat)) / (w.delta * d), 4),
         },
-        "roofline": roofline, "path": path, "cpu_baseline": cpu_baseline, "topk_comparator": topk, "per_tensor": per_tensor,
+        "roofline": roofline, "path": path, "cpu_baseline": cpu_baseline, "topk_comparator": topk, "dgc_comparator": dgc, "per_tensor": per_tensor,
         "paper_context": "the paper prints no absolute compression rate in text (its figures are the only source); it "
                          "states that on a V100 (PyTorch 1.1, CUDA 10.2) every threshold estimator is far faster than "
                          "Top-k and that SIDCo compresses at least 2x faster than DGC (Sec. 4.2, App. E)",

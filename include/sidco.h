@@ -233,6 +233,37 @@ int sidco_topk(void *stream, const float *grad, float *residual, int64_t d, int6
                int32_t *out_idx, float *out_val, int32_t *out_count, float *out_kth);
 
 /*
+ * DGC's sampling threshold, one of the threshold methods the paper compares
+ * with (Sec. 1, related work and its footnote): a random subset of the
+ * gradient is drawn, Top-k of the subset at the target ratio gives a
+ * threshold, the threshold selects from the whole vector, and a second Top-k
+ * trims the selection when it exceeds the target.  Same buffers and
+ * error-compensation semantics as sidco_compress.
+ *
+ *  delta         target ratio, 0 < delta < 1; k = ceil(delta * d)
+ *  sample_ratio  size of the subset relative to d, 0 < sample_ratio <= 1
+ *                (DGC's example is 0.01): n_s = ceil(sample_ratio * d) draws
+ *                with replacement; draw j is element floor(u_j * d / 2^32),
+ *                u_j = upper 32 bits of output j of the splitmix64 sequence
+ *                started at `seed`
+ *  out_idx, out_val  device, capacity k
+ *  out_count     device, 1 int32: entries written, min(k, first-pass count)
+ *  out_eta       device, 1 float: the subset's threshold, i.e. its k_s-th
+ *                largest magnitude, k_s = ceil(delta * n_s)
+ * The first pass keeps |acc| > threshold (strict, fp32).  If that is more than
+ * k entries, the k of largest magnitude stay (which of the entries tied with the
+ * smallest one stay may differ between runs); otherwise all of them stay.
+ * sidco_dgc_sizes fills sizes[0..2] = n_s, k_s, k (host only).
+ * sidco_dgc_result fills host_out[0..3] = n_s, k_s, first-pass count and
+ * entries written of the last sidco_dgc on the current device; it synchronises `stream`.
+ */
+int sidco_dgc(void *stream, const float *grad, float *residual, int64_t d, double delta,
+              double sample_ratio, uint64_t seed,
+              int32_t *out_idx, float *out_val, int32_t *out_count, float *out_eta);
+int sidco_dgc_sizes(int64_t d, double delta, double sample_ratio, int64_t *sizes);
+int sidco_dgc_result(void *stream, int64_t *host_out);
+
+/*
  * Steps 1-2 alone: the error-compensation add (App. B.2; skipped when residual
  * is NULL) fused with the sums of the stage-1 fit (Corollary 1 / eq. (6),
  * Corollaries 1.2 and 1.3).  This is the kernel that dominates a call; it is

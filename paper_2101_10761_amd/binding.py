@@ -18,7 +18,7 @@ ST_NONFINITE, ST_VAR_ZERO, ST_GAMMA_S, ST_GAMMA_CLAMP, ST_STOPPED, ST_OVERFLOW, 
 
 EXPORTS = [
     "sidco_compress", "sidco_compress_ex", "sidco_compress_batched", "sidco_batched_out_offsets",
-    "sidco_workspace_bytes_batched", "sidco_read_diag_batched", "sidco_topk", "sidco_adapt_stages", "sidco_controller_create",
+    "sidco_workspace_bytes_batched", "sidco_read_diag_batched", "sidco_topk", "sidco_dgc", "sidco_dgc_sizes", "sidco_dgc_result", "sidco_adapt_stages", "sidco_controller_create",
     "sidco_controller_destroy", "sidco_controller_stages", "sidco_controller_iteration",
     "sidco_controller_last_average", "sidco_controller_compress", "sidco_scatter_add", "sidco_scatter_check",
     "sidco_fit", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
@@ -80,6 +80,12 @@ def load() -> C.CDLL:
     lib.sidco_topk.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int64, i32p, f32p, i32p, f32p]
     lib.sidco_topk.restype = C.c_int
     i64p = C.POINTER(C.c_int64)
+    lib.sidco_dgc.argtypes = [vp, f32p, f32p, C.c_int64, C.c_double, C.c_double, C.c_uint64, i32p, f32p, i32p, f32p]
+    lib.sidco_dgc.restype = C.c_int
+    lib.sidco_dgc_sizes.argtypes = [C.c_int64, C.c_double, C.c_double, i64p]
+    lib.sidco_dgc_sizes.restype = C.c_int
+    lib.sidco_dgc_result.argtypes = [vp, i64p]
+    lib.sidco_dgc_result.restype = C.c_int
     lib.sidco_compress_batched.argtypes = [vp, f32p, f32p, i64p, C.c_int, C.c_double, C.c_int, C.c_int, i32p, f32p,
                                            i64p, i32p, f32p]
     lib.sidco_compress_batched.restype = C.c_int
@@ -279,6 +285,37 @@ def sidco_topk(grad, residual, k: int, out_idx, out_val, out_count, out_kth, str
     _check_tensor(out_kth, torch.float32, "out_kth", 1)
     _check(load().sidco_topk(_stream_handle(stream), _ptr(grad), _ptr(residual), d, k, _ptr(out_idx), _ptr(out_val),
                              _ptr(out_count), _ptr(out_kth)), "sidco_topk")
+
+
+def sidco_dgc_sizes(d: int, delta: float, sample_ratio: float = 0.01):
+    """(n_s, k_s, k) of the DGC comparator for a vector of d elements."""
+    sizes = (C.c_int64 * 3)()
+    _check(load().sidco_dgc_sizes(d, delta, sample_ratio, sizes), "sidco_dgc_sizes")
+    return int(sizes[0]), int(sizes[1]), int(sizes[2])
+
+
+def sidco_dgc(grad, residual, delta: float, sample_ratio: float, seed: int, out_idx, out_val, out_count, out_eta,
+              stream=None) -> None:
+    """Enqueues the DGC comparator; see include/sidco.h.  `residual` may be None."""
+    import torch
+    d = grad.numel()
+    _check_tensor(grad, torch.float32, "grad")
+    if residual is not None:
+        _check_tensor(residual, torch.float32, "residual", d)
+    k = sidco_dgc_sizes(d, delta, sample_ratio)[2]
+    _check_tensor(out_idx, torch.int32, "out_idx", k)
+    _check_tensor(out_val, torch.float32, "out_val", k)
+    _check_tensor(out_count, torch.int32, "out_count", 1)
+    _check_tensor(out_eta, torch.float32, "out_eta", 1)
+    _check(load().sidco_dgc(_stream_handle(stream), _ptr(grad), _ptr(residual), d, delta, sample_ratio, seed,
+                            _ptr(out_idx), _ptr(out_val), _ptr(out_count), _ptr(out_eta)), "sidco_dgc")
+
+
+def sidco_dgc_result(stream=None):
+    """(n_s, k_s, first-pass count, entries written) of the last sidco_dgc; synchronises the stream."""
+    out = (C.c_int64 * 4)()
+    _check(load().sidco_dgc_result(_stream_handle(stream), out), "sidco_dgc_result")
+    return tuple(int(v) for v in out)
 
 
 def sidco_adapt_stages(stages: int, khat_avg: float, k: float, eps_high: float = 0.2, eps_low: float = 0.2,

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsidco.so")
-SOURCES = ["sidco_kernels.hip", "sidco_topk.hip", "sidco_api.hip"]
+SOURCES = ["sidco_kernels.hip", "sidco_topk.hip", "sidco_dgc.hip", "sidco_api.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

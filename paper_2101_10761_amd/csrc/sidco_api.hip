@@ -27,6 +27,8 @@ struct WorkspaceHead {
     alignas(256) uint32_t blk[2][kMaxBlocks];
     alignas(256) uint32_t topk_hist[3 * kTopkBins];
     alignas(256) TopkState topk;
+    alignas(256) uint32_t dgc_hist[2][3 * kTopkBins];
+    alignas(256) DgcState dgc;
     alignas(256) BatchTable batch;  // at a fixed place, so that single calls in between leave it alone
 };
 
@@ -46,6 +48,7 @@ struct DeviceCtx {
     bool ev_made = false;
     int prof_n = 0;            // kernels of the last profiled call
     const char* prof_name[kMaxKernels] = {};
+    int64_t dgc_n_s = 0, dgc_k_s = 0;  // sizes of the last sidco_dgc call
     bool bad_cleared = false;  // the scatter kernels' bad-index flag has been initialised in this workspace
     int64_t last_cap = 0;      // output capacity of the last compress call
     // shape of the last compress call: a call that repeats it may use the device's record of where the
@@ -112,7 +115,7 @@ int ensure_workspace(DeviceCtx& c, size_t need)
     c.ws_owned = true;
     c.sig_d = 0;  // a fresh workspace holds no record of an earlier call
     c.bad_cleared = false;
-    c.batch_image.clear();
+    c.dgc_n_s = 0;
     c.batch_image.clear();
     return SIDCO_OK;
 }
@@ -387,6 +390,7 @@ int sidco_set_workspace(void* device_ptr, size_t bytes)
     c.ws_owned = false;
     c.sig_d = 0;  // a fresh workspace holds no record of an earlier call
     c.bad_cleared = false;
+    c.dgc_n_s = 0;
     c.batch_image.clear();
     c.bad_cleared = false;
     return SIDCO_OK;
@@ -870,6 +874,163 @@ int sidco_topk(void* stream, const float* grad, float* residual, int64_t d, int6
     c.prof_n = prof ? kn : 0;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    return SIDCO_OK;
+}
+
+// n_s, k_s and k of the DGC comparator; false if an argument is out of range
+static bool dgc_sizes(int64_t d, double delta, double sample_ratio, int64_t* n_s, int64_t* k_s, int64_t* k)
+{
+    if (d < 1 || d > (int64_t)INT32_MAX) return false;
+    if (!(delta > 0.0 && delta < 1.0) || !(sample_ratio > 0.0 && sample_ratio <= 1.0)) return false;
+    int64_t ns = (int64_t)ceil(sample_ratio * (double)d);
+    ns = ns < 1 ? 1 : (ns > d ? d : ns);
+    int64_t ks = (int64_t)ceil(delta * (double)ns);
+    ks = ks < 1 ? 1 : (ks > ns ? ns : ks);
+    int64_t kk = (int64_t)ceil(delta * (double)d);
+    kk = kk < 1 ? 1 : (kk > d ? d : kk);
+    *n_s = ns;
+    *k_s = ks;
+    *k = kk;
+    return true;
+}
+
+int sidco_dgc_sizes(int64_t d, double delta, double sample_ratio, int64_t* sizes)
+{
+    if (!sizes) return SIDCO_ERR_NULL;
+    if (d < 1 || d > (int64_t)INT32_MAX) return SIDCO_ERR_SIZE;
+    if (!dgc_sizes(d, delta, sample_ratio, &sizes[0], &sizes[1], &sizes[2])) return SIDCO_ERR_DELTA;
+    return SIDCO_OK;
+}
+
+int sidco_dgc(void* stream, const float* grad, float* residual, int64_t d, double delta, double sample_ratio,
+              uint64_t seed, int32_t* out_idx, float* out_val, int32_t* out_count, float* out_eta)
+{
+    int rc = check_common(grad, residual, d, SIDCO_DIST_EXP, out_idx, out_val, out_count, out_eta);
+    if (rc != SIDCO_OK) return rc;
+    int64_t n_s, k_s, k;
+    if (!dgc_sizes(d, delta, sample_ratio, &n_s, &k_s, &k)) return SIDCO_ERR_DELTA;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx* cp = nullptr;
+    rc = current_ctx(&cp);
+    if (rc != SIDCO_OK) return rc;
+    DeviceCtx& c = *cp;
+    rc = ensure_workspace(c, head_bytes() + 2 * seg_bytes(d));
+    if (rc != SIDCO_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    WorkspaceHead* h = (WorkspaceHead*)c.ws;
+
+    Params q;
+    fill_common(q, h, grad, residual, d, SIDCO_DIST_EXP);
+    DgcParams p;
+    memset(&p, 0, sizeof(p));
+    p.grad = grad;
+    p.residual = residual;
+    p.d = d;
+    p.k = k;
+    p.ntiles = q.ntiles;
+    p.nfull = q.nfull;
+    p.nwaves = q.nwaves;
+    p.nblocks = q.nblocks;
+    p.vec_ok = q.vec_ok;
+    p.seed = seed;
+    p.n_s = (uint32_t)n_s;
+    p.k_s = (uint32_t)k_s;
+    p.keys = (uint32_t*)((char*)c.ws + head_bytes() + seg_bytes(d));  // the second list buffer is free here
+    p.hist_s = h->dgc_hist[0];
+    p.hist_l = h->dgc_hist[1];
+    p.st = &h->dgc;
+    p.cnt = h->cnt[0];
+    p.seg = (int2*)((char*)c.ws + head_bytes());
+    p.out_eta = out_eta;
+
+    // the second select runs on the kernels of the exact Top-k, with k decided on the device
+    TopkParams t;
+    memset(&t, 0, sizeof(t));
+    t.grad = grad;
+    t.residual = residual;
+    t.acc = q.acc;
+    t.d = d;
+    t.k = k;
+    t.k_from_state = 1;
+    t.ntiles = q.ntiles;
+    t.nfull = q.nfull;
+    t.nwaves = q.nwaves;
+    t.nblocks = q.nblocks;
+    t.vec_ok = q.vec_ok;
+    t.hist = h->dgc_hist[1];
+    t.st = &h->dgc.lists;
+    t.cnt = p.cnt;
+    t.seg = p.seg;
+    t.out_idx = out_idx;
+    t.out_val = out_val;
+    t.out_count = out_count;
+    t.out_kth = &h->dgc.kth;
+
+    const bool prof = g_profiling;
+    if (prof) {
+        rc = make_events(c);
+        if (rc != SIDCO_OK) return rc;
+    }
+    int kn = 0;
+    auto mark = [&](const char* name) {
+        if (!prof) return;
+        if (name) c.prof_name[kn - 1] = name;
+        (void)hipEventRecord(c.ev[kn], s);
+    };
+    mark(nullptr);
+    launch_dgc_zero(p, s);
+    ++kn;
+    mark("k_dgc_zero");
+    launch_dgc_sample(p, s);
+    ++kn;
+    mark("k_dgc_sample");
+    launch_dgc_digit(p, 1, s);
+    ++kn;
+    mark("k_dgc_digit1");
+    launch_dgc_digit(p, 2, s);
+    ++kn;
+    mark("k_dgc_digit2");
+    launch_dgc_dense(p, s);
+    ++kn;
+    mark("k_dgc_dense");
+    uint32_t grid = (p.nwaves + 31) / 32;  // the lists hold about k entries: few blocks
+    if (grid > p.nblocks) grid = p.nblocks;
+    if (grid < 1) grid = 1;
+    launch_dgc_lists(p, grid, s);
+    ++kn;
+    mark("k_dgc_lists");
+    launch_topk_refine(t, grid, s);
+    ++kn;
+    mark("k_topk_refine");
+    launch_topk_final(t, grid, s);
+    ++kn;
+    mark("k_topk_final");
+    c.prof_n = prof ? kn : 0;
+    c.dgc_n_s = n_s;
+    c.dgc_k_s = k_s;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "kernel launch");
+    return SIDCO_OK;
+}
+
+int sidco_dgc_result(void* stream, int64_t* host_out)
+{
+    if (!host_out) return SIDCO_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx* cp = nullptr;
+    int rc = current_ctx(&cp);
+    if (rc != SIDCO_OK) return rc;
+    if (!cp->ws || cp->dgc_n_s == 0) return SIDCO_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    DgcState st;
+    hipError_t e = hipMemcpyAsync(&st, &((WorkspaceHead*)cp->ws)->dgc, sizeof(DgcState), hipMemcpyDeviceToHost, s);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(dgc state)");
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    host_out[0] = cp->dgc_n_s;
+    host_out[1] = cp->dgc_k_s;
+    host_out[2] = (int64_t)st.first_pass;
+    host_out[3] = (int64_t)st.lists.k_eff;
     return SIDCO_OK;
 }
 

@@ -115,7 +115,7 @@ struct TopkState {
     uint32_t prefix[3];            // bin of the k-th largest key in digit 0, 1, 2
     uint32_t k_rem[3];             // rank of that key inside the bin (k_rem[2] = ties still needed)
     uint32_t kth_key;              // the k-th largest magnitude as its bit pattern
-    uint32_t reserved;
+    uint32_t k_eff;                // k when the device decides it (TopkParams::k_from_state)
     unsigned long long gt_ctr;     // output places reserved for entries above the k-th key
     unsigned long long eq_ctr;     // entries equal to the k-th key seen so far
 };
@@ -126,6 +126,7 @@ struct TopkParams {
     const float* acc;       // residual, else grad
     int64_t d;
     int64_t k;
+    int k_from_state;       // the last kernel takes k from st->k_eff (may be 0) instead of `k`
     uint32_t ntiles, nfull, nwaves, nblocks;
     int vec_ok;
     uint32_t* hist;         // [3][kTopkBins]
@@ -143,6 +144,40 @@ void launch_topk_hist(const TopkParams& p, hipStream_t s);
 void launch_topk_compact(const TopkParams& p, hipStream_t s);
 void launch_topk_refine(const TopkParams& p, uint32_t grid, hipStream_t s);
 void launch_topk_final(const TopkParams& p, uint32_t grid, hipStream_t s);
+
+// ---- DGC comparator: threshold from a radix select on a random subset, first pass over the vector,
+// second radix select on the first pass's entries ----
+struct DgcState {
+    TopkState sample;               // select of the k_s-th largest magnitude of the subset
+    TopkState lists;                // select among the entries of the first pass
+    unsigned long long first_pass;  // entries above the subset's threshold
+    float eta;                      // that threshold
+    float kth;                      // smallest magnitude that stayed
+};
+
+struct DgcParams {
+    const float* grad;
+    float* residual;  // NULL: memoryless
+    int64_t d;
+    int64_t k;        // target number of entries
+    uint32_t ntiles, nfull, nwaves, nblocks;
+    int vec_ok;
+    uint64_t seed;
+    uint32_t n_s, k_s;  // subset size, rank of the threshold in it
+    uint32_t* keys;     // [n_s] magnitude keys of the subset
+    uint32_t* hist_s;   // [3][kTopkBins] digit histograms of the subset
+    uint32_t* hist_l;   // [3][kTopkBins] digit histograms of the first pass's entries
+    DgcState* st;
+    uint32_t* cnt;      // [kMaxWaves] list lengths
+    int2* seg;          // per-wave lists
+    float* out_eta;
+};
+
+void launch_dgc_zero(const DgcParams& p, hipStream_t s);
+void launch_dgc_sample(const DgcParams& p, hipStream_t s);
+void launch_dgc_digit(const DgcParams& p, int digit, hipStream_t s);
+void launch_dgc_dense(const DgcParams& p, hipStream_t s);
+void launch_dgc_lists(const DgcParams& p, uint32_t grid, hipStream_t s);
 
 // A block's place in its vector's grid (the whole launch for a single call, a slice of it in a batch).
 struct Blk {

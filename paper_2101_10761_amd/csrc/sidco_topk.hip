@@ -28,64 +28,9 @@
 
 #include "sidco_internal.h"
 #include "sidco_device.h"
+#include "sidco_select.h"
 
 namespace sidco {
-
-__device__ __forceinline__ uint32_t mag_key(float x) { return (uint32_t)__float_as_int(x) & 0x7fffffffu; }
-
-// Bin of `hist` (nb bins, nb = kBlock * PER) that holds the k-th largest entry, counted from the top
-// bin downwards, and the rank the entry has inside that bin.  Every thread of the block returns the
-// same pair.  Needs sum(hist) >= k >= 1.
-template <int PER>
-__device__ __forceinline__ void pick_bin(const uint32_t* __restrict__ hist, unsigned long long k, uint32_t* sh_scan,
-                                         uint32_t* sh_out, uint32_t& bin, uint32_t& k_in_bin)
-{
-    const uint32_t t = threadIdx.x;
-    uint32_t local[PER];
-    uint32_t tsum = 0;
-#pragma unroll
-    for (int j = 0; j < PER; ++j) {
-        local[j] = hist[t * PER + j];
-        tsum += local[j];
-    }
-    // inclusive suffix sums over the threads (counts are at most d < 2^31: no overflow)
-    __syncthreads();  // protects sh_scan / sh_out against a previous use
-    sh_scan[t] = tsum;
-    if (t == 0) sh_out[0] = sh_out[1] = 0;  // only reached if the histogram holds fewer than k entries
-    __syncthreads();
-    uint32_t s = tsum;
-    for (uint32_t o = 1; o < (uint32_t)kBlock; o <<= 1) {
-        const uint32_t other = t + o < (uint32_t)kBlock ? sh_scan[t + o] : 0u;
-        __syncthreads();
-        s += other;
-        sh_scan[t] = s;
-        __syncthreads();
-    }
-    const unsigned long long above = (unsigned long long)s - tsum;  // entries in the bins of later threads
-    if (above < k && k <= (unsigned long long)s) {                  // exactly one thread
-        unsigned long long acc = above;
-#pragma unroll
-        for (int j = PER - 1; j >= 0; --j) {
-            if (acc < k && k <= acc + local[j]) {
-                sh_out[0] = t * PER + j;
-                sh_out[1] = (uint32_t)(k - acc);
-            }
-            acc += local[j];
-        }
-    }
-    __syncthreads();
-    bin = sh_out[0];
-    k_in_bin = sh_out[1];
-}
-
-// adds a block's LDS histogram to the global one
-__device__ __forceinline__ void merge_hist(const uint32_t* sh_hist, uint32_t* __restrict__ hist, int nb)
-{
-    for (int i = threadIdx.x; i < nb; i += kBlock) {
-        const uint32_t c = sh_hist[i];
-        if (c) atomicAdd(&hist[i], c);
-    }
-}
 
 __global__ __launch_bounds__(kBlock) void k_topk_zero(TopkParams p)
 {
@@ -97,6 +42,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_zero(TopkParams p)
         p.st->prefix[0] = p.st->prefix[1] = p.st->prefix[2] = 0;
         p.st->k_rem[0] = p.st->k_rem[1] = p.st->k_rem[2] = 0;
         p.st->kth_key = 0;
+        p.st->k_eff = 0;
     }
 }
 
@@ -256,22 +202,6 @@ __global__ __launch_bounds__(kBlock, 4) void k_topk_compact(TopkParams p)
     merge_hist(sh_hist, p.hist + kTopkBins, 1024);
 }
 
-// ---------------------------------------------------------------------------------------------
-// list traversal shared by the last two kernels: source lists first, first + 8, ... below last
-// ---------------------------------------------------------------------------------------------
-struct ListRange {
-    uint32_t first, last;
-};
-__device__ __forceinline__ ListRange my_lists(const TopkParams& p)
-{
-    const uint32_t per_block = (p.nwaves + gridDim.x - 1) / gridDim.x;
-    ListRange r;
-    r.first = blockIdx.x * per_block + (threadIdx.x >> 6);
-    const uint32_t end = (blockIdx.x + 1) * per_block;
-    r.last = end < p.nwaves ? end : p.nwaves;
-    return r;
-}
-
 // k_topk_refine: digit-2 histogram of the list entries whose digits 0 and 1 are b0 and b1
 __global__ __launch_bounds__(kBlock) void k_topk_refine(TopkParams p)
 {
@@ -289,7 +219,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_refine(TopkParams p)
     }
     const int lane = threadIdx.x & 63;
     const uint32_t want = (b0 << 10) | b1;  // key >> 10
-    const ListRange r = my_lists(p);
+    const ListRange r = my_lists(p.nwaves);
     for (uint32_t sw = r.first; sw < r.last; sw += kWavesPerBlock) {
         const int2* __restrict__ list = p.seg + (size_t)tile_begin(sw, p.ntiles, p.nwaves) * kTile;
         const uint32_t n = p.cnt[sw];
@@ -314,8 +244,9 @@ __global__ __launch_bounds__(kBlock) void k_topk_final(TopkParams p)
     uint32_t b2, need;
     pick_bin<1024 / kBlock>(p.hist + 2 * kTopkBins, (unsigned long long)k2, sh_scan, sh_out, b2, need);
     const uint32_t kappa = (b0 << 20) | (b1 << 10) | b2;
+    const unsigned long long K = p.k_from_state ? (unsigned long long)p.st->k_eff : (unsigned long long)p.k;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    const ListRange r = my_lists(p);
+    const ListRange r = my_lists(p.nwaves);
 
     // pass A: entries above kappa and entries equal to it, per wave
     uint32_t n_gt = 0, n_eq = 0;
@@ -352,7 +283,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_final(TopkParams p)
             p.st->prefix[2] = b2;
             p.st->k_rem[2] = need;
             p.st->kth_key = kappa;
-            *p.out_count = (int32_t)p.k;
+            *p.out_count = (int32_t)K;
             *p.out_kth = __int_as_float((int)kappa);
         }
     }
@@ -360,7 +291,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_final(TopkParams p)
     // the k - need entries above kappa fill the front of the output, the ties the last `need` places
     unsigned long long pos_gt = sh_base[0] + off_gt;
     unsigned long long pos_eq = sh_base[1] + off_eq;
-    const unsigned long long tie_base = (unsigned long long)p.k - need;
+    const unsigned long long tie_base = K - need;
 
     // pass B: same traversal, writing
     for (uint32_t sw = r.first; sw < r.last; sw += kWavesPerBlock) {

@@ -167,3 +167,23 @@ def test_batched_argument_errors_and_helpers(lib):
     assert got == [0, caps[0], caps[0] + caps[1], sum(caps)]
     assert sidco.sidco_workspace_bytes_batched(offs) >= 2 * 8 * (1024 + 2048 + 256)
     assert lib.sidco_read_diag_batched(None, 0, None) == -1
+
+
+def test_dgc_argument_errors_and_sizes(lib, oracle):
+    ok = C.c_void_p(256)
+    f = lib.sidco_dgc
+    assert f(None, None, None, 1000, 0.01, 0.01, 1, ok, ok, ok, ok) == -1
+    assert f(None, ok, None, 1000, 0.01, 0.01, 1, ok, ok, ok, None) == -1
+    assert f(None, ok, None, 0, 0.01, 0.01, 1, ok, ok, ok, ok) == -2
+    assert f(None, ok, None, 2 ** 31, 0.01, 0.01, 1, ok, ok, ok, ok) == -2
+    for bad in (0.0, 1.0, -1.0, math.nan):
+        assert f(None, ok, None, 1000, bad, 0.01, 1, ok, ok, ok, ok) == -3
+    for bad in (0.0, 1.5, -0.1, math.nan):
+        assert f(None, ok, None, 1000, 0.01, bad, 1, ok, ok, ok, ok) == -3
+    assert f(None, C.c_void_p(258), None, 1000, 0.01, 0.01, 1, ok, ok, ok, ok) == -8
+    assert f(None, ok, ok, 1000, 0.01, 0.01, 1, ok, ok, ok, ok) == -9
+    assert lib.sidco_dgc_sizes(1000, 0.01, 0.01, None) == -1
+    assert lib.sidco_dgc_result(None, None) == -1
+    for d, delta, rho in ((1_000_000, 0.001, 0.01), (269_722, 0.01, 0.01), (10, 0.001, 0.01), (25_557_032, 0.001, 0.01),
+                          (138_357_544, 0.1, 0.01), (1, 0.5, 1.0), (12345, 0.3, 0.7)):
+        assert sidco.sidco_dgc_sizes(d, delta, rho) == oracle.dgc_sizes(d, delta, rho)
