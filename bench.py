@@ -41,11 +41,11 @@ def make_workload(name: str):
     return table[name]()
 
 
-def algorithmic_bytes(d, ec, n_stage, khat):
+def algorithmic_bytes(d, ec, n_stage, khat, fit_bpe=None):
     """Bytes the method itself must move: gradient (+ residual read and acc write), the second pass over
     acc, every intermediate survivor list written once and read once (8 B pairs), output pairs and
-    residual zero-stores."""
-    b = 4 * d * (3 if ec else 1) + 4 * d
+    residual zero-stores.  fit_bpe: bytes per element of the first pass when the gradient is not fp32."""
+    b = d * (fit_bpe if fit_bpe is not None else 4 * (3 if ec else 1)) + 4 * d
     b += sum(16 * int(n) for n in n_stage[1:])
     b += 12 * khat
     return b
@@ -62,6 +62,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-topk", action="store_true", help="skip the exact Top-k comparator leg")
     ap.add_argument("--no-dgc", action="store_true", help="skip the DGC comparator leg")
+    ap.add_argument("--grad-dtype", choices=["f32", "f16", "bf16"], default="f32",
+                    help="element type of the gradient buffer (the residual and all arithmetic stay fp32/fp64); "
+                         "16-bit gradients use the default stage schedule (delta_1 = 0.25) and skip the comparators")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (the sparsifier is local to a worker: no collectives, "
@@ -85,6 +88,14 @@ def main():
         f"(generated in {time.time() - t0:.1f}s)")
     ratios = sidco.sidco_stage_ratios(w.delta, w.stages, w.delta1)
     g0 = torch.from_numpy(w.grad).to(dev)
+    typed = args.grad_dtype != "f32"
+    gbytes = 2 if typed else 4
+    if typed:
+        if w.delta1 != 0.25:
+            log("bench.py: --grad-dtype f16/bf16 needs a workload with delta_1 = 0.25")
+            sys.exit(2)
+        g0 = g0.to(torch.float16 if args.grad_dtype == "f16" else torch.bfloat16)
+        args.no_topk = args.no_dgc = True
     nbuf = max(2, min(16, ROTATE_BYTES // (4 * d) + 1))
     # The same gradient in several buffers: every step reads its gradient from another address range, and the
     # carried residual reaches a steady state the way it does under a persistent gradient direction (an entry
@@ -101,8 +112,12 @@ def main():
     stream = torch.cuda.current_stream()
 
     def step(i):
-        sidco.sidco_compress_ex(grads[i % nbuf], residual, w.dist, ratios, out_idx, out_val, out_count, out_eta,
-                                stream=stream)
+        if typed:
+            sidco.sidco_compress_typed(grads[i % nbuf], residual, w.delta, w.dist, w.stages, out_idx, out_val,
+                                       out_count, out_eta, stream=stream)
+        else:
+            sidco.sidco_compress_ex(grads[i % nbuf], residual, w.dist, ratios, out_idx, out_val, out_count, out_eta,
+                                    stream=stream)
 
     for i in range(args.warmup):
         step(i)
@@ -162,7 +177,8 @@ def main():
         ev_b.synchronize()
         if rep >= 2:
             fit_ms.append(ev_a.elapsed_time(ev_b) / batch)
-    fit_bytes = (12 if ec else 4) * d
+    fit_bpe = gbytes + (8 if ec else (4 if typed else 0))   # read g [, read r], write acc unless acc is g itself
+    fit_bytes = fit_bpe * d
     fit_us = float(np.mean(fit_ms)) * 1e3
     log(f"k_fit alone: {fit_us:.1f} us per launch (HIP events around batches of {batch})")
     achieved = fit_bytes / (fit_us * 1e-6) / 1e9
@@ -170,15 +186,15 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.workload, {}).get("k_fit")
+            traffic = None if typed else json.load(open(tpath)).get(args.workload, {}).get("k_fit")
         except Exception:
             traffic = None
     roofline = {
         "kernel": "k_fit", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-        "bytes_per_elem": 12 if ec else 4, "elems_per_launch": d, "avg_launch_us": round(fit_us, 2),
+        "bytes_per_elem": fit_bpe, "elems_per_launch": d, "avg_launch_us": round(fit_us, 2),
     }
-    path_bytes = algorithmic_bytes(d, ec, n_stage, int(np.mean(khat)))
+    path_bytes = algorithmic_bytes(d, ec, n_stage, int(np.mean(khat)), fit_bpe)
     path = {
         "algorithmic_bytes": path_bytes, "bytes_per_elem": round(path_bytes / d, 2),
         "achieved": round(path_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
@@ -327,17 +343,18 @@ def main():
         log(f"cpu oracle: {cpu_baseline['value']} G elem/s on 1 core ({reps} reps, {t_cpu:.1f}s)")
 
     result = {
-        "metric": "G gradient elems/s compressed (d=25.6M fp32, delta=0.001)" if args.workload == "cfg3"
-                  else f"G gradient elems/s compressed ({args.workload})",
+        "metric": "G gradient elems/s compressed (d=25.6M fp32, delta=0.001)" if args.workload == "cfg3" and not typed
+                  else f"G gradient elems/s compressed ({args.workload}" + (f", {args.grad_dtype} gradient)" if typed else ")"),
         "value": round(value, 2), "unit": "G elem/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {
-            "workload": f"{w.name}: d={d} fp32, delta={w.delta}, dist={['exp', 'gamma-gpd', 'gpd'][w.dist]}, "
+            "workload": f"{w.name}: d={d} {'fp32' if not typed else args.grad_dtype + ' gradient, fp32 residual'}, delta={w.delta}, dist={['exp', 'gamma-gpd', 'gpd'][w.dist]}, "
                         f"stages={w.stages}, delta1={w.delta1}, error_feedback={'on' if ec else 'off'}",
             "gradient_buffers_in_rotation": nbuf, "khat_over_k": round(float(np.mean(khat)) / (w.delta * d), 4),
         },
-        "roofline": roofline, "path": path, "cpu_baseline": cpu_baseline, "topk_comparator": topk, "dgc_comparator": dgc, "per_tensor": per_tensor,
+        "roofline": roofline, "path": path, "cpu_baseline": cpu_baseline, "topk_comparator": topk,
+        "dgc_comparator": dgc, "per_tensor": per_tensor,
         "paper_context": "the paper prints no absolute compression rate in text (its figures are the only source); it "
                          "states that on a V100 (PyTorch 1.1, CUDA 10.2) every threshold estimator is far faster than "
                          "Top-k and that SIDCo compresses at least 2x faster than DGC (Sec. 4.2, App. E)",

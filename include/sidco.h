@@ -127,6 +127,28 @@ int sidco_compress_ex(void *stream, const float *grad, float *residual, int64_t 
                       int32_t *out_count, float *out_eta);
 
 /*
+ * The sparsifier on a gradient stored in 16 bits (fp16 or bf16, the types
+ * mixed-precision training produces).  The gradient is widened to fp32 as it is
+ * read - exactly - and everything else is sidco_compress: acc = fp32(grad) +
+ * residual in fp32, fits in fp64, fp32 thresholds, fp32 residual and values.
+ *
+ *  grad        device, d elements of grad_dtype, read only, aligned to its
+ *              element size (8-byte alignment enables the vector path)
+ *  grad_dtype  SIDCO_GRAD_F32 (then this is sidco_compress), _F16 or _BF16
+ *  residual    device, d floats, in/out, or NULL.  Without a residual the
+ *              widened vector is kept in the workspace, which then needs
+ *              sidco_workspace_bytes_typed(d, grad_dtype, 0) bytes.
+ * Everything else as in sidco_compress.
+ */
+#define SIDCO_GRAD_F32  0
+#define SIDCO_GRAD_F16  1
+#define SIDCO_GRAD_BF16 2
+int sidco_compress_typed(void *stream, const void *grad, int grad_dtype, float *residual, int64_t d,
+                         double delta, int dist, int stages,
+                         int32_t *out_idx, float *out_val, int32_t *out_count, float *out_eta);
+size_t sidco_workspace_bytes_typed(int64_t d, int grad_dtype, int has_residual);
+
+/*
  * Several vectors in one launch sequence: the tensors of one flat gradient
  * buffer, each sparsified on its own exactly as sidco_compress would (the cost of
  * the compressor depends only on the vector's size, App. A, so layer-wise
@@ -272,6 +294,8 @@ int sidco_dgc_result(void *stream, int64_t *host_out);
  * workspace until the next call on the device.
  */
 int sidco_fit(void *stream, const float *grad, float *residual, int64_t d, int dist);
+/* The same on a gradient of element type grad_dtype (SIDCO_GRAD_*), as in sidco_compress_typed. */
+int sidco_fit_typed(void *stream, const void *grad, int grad_dtype, float *residual, int64_t d, int dist);
 
 /* Sums of the last sidco_fit on the current device, reduced on the host in a
  * fixed order.  host_sums (host, 4 doubles) receives sum|acc|, sum acc^2

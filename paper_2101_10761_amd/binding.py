@@ -17,11 +17,11 @@ DIST_EXP, DIST_GAMMA_GPD, DIST_GPD = 0, 1, 2
 ST_NONFINITE, ST_VAR_ZERO, ST_GAMMA_S, ST_GAMMA_CLAMP, ST_STOPPED, ST_OVERFLOW, ST_FALLBACK = 1, 2, 4, 8, 16, 32, 64
 
 EXPORTS = [
-    "sidco_compress", "sidco_compress_ex", "sidco_compress_batched", "sidco_batched_out_offsets",
+    "sidco_compress", "sidco_compress_typed", "sidco_workspace_bytes_typed", "sidco_compress_ex", "sidco_compress_batched", "sidco_batched_out_offsets",
     "sidco_workspace_bytes_batched", "sidco_read_diag_batched", "sidco_topk", "sidco_dgc", "sidco_dgc_sizes", "sidco_dgc_result", "sidco_adapt_stages", "sidco_controller_create",
     "sidco_controller_destroy", "sidco_controller_stages", "sidco_controller_iteration",
     "sidco_controller_last_average", "sidco_controller_compress", "sidco_scatter_add", "sidco_scatter_check",
-    "sidco_fit", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
+    "sidco_fit", "sidco_fit_typed", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
     "sidco_workspace_bytes", "sidco_set_workspace", "sidco_set_speculation", "sidco_read_diag", "sidco_set_profiling",
     "sidco_get_profile", "sidco_strerror", "sidco_last_hip_error", "sidco_version", "sidco_shutdown",
 ]
@@ -77,6 +77,11 @@ def load() -> C.CDLL:
     lib.sidco_compress_ex.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int, f64p, C.c_int, i32p, f32p, C.c_int64,
                                       i32p, f32p]
     lib.sidco_compress_ex.restype = C.c_int
+    lib.sidco_compress_typed.argtypes = [vp, vp, C.c_int, f32p, C.c_int64, C.c_double, C.c_int, C.c_int, i32p, f32p,
+                                         i32p, f32p]
+    lib.sidco_compress_typed.restype = C.c_int
+    lib.sidco_workspace_bytes_typed.argtypes = [C.c_int64, C.c_int, C.c_int]
+    lib.sidco_workspace_bytes_typed.restype = C.c_size_t
     lib.sidco_topk.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int64, i32p, f32p, i32p, f32p]
     lib.sidco_topk.restype = C.c_int
     i64p = C.POINTER(C.c_int64)
@@ -116,6 +121,8 @@ def load() -> C.CDLL:
     lib.sidco_scatter_check.restype = C.c_int
     lib.sidco_fit.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int]
     lib.sidco_fit.restype = C.c_int
+    lib.sidco_fit_typed.argtypes = [vp, vp, C.c_int, f32p, C.c_int64, C.c_int]
+    lib.sidco_fit_typed.restype = C.c_int
     lib.sidco_fit_result.argtypes = [vp, f64p]
     lib.sidco_fit_result.restype = C.c_int
     lib.sidco_stage_ratios.argtypes = [C.c_double, C.c_int, C.c_double, f64p]
@@ -213,6 +220,30 @@ def sidco_compress(grad, residual, delta: float, dist: int, stages: int, out_idx
     _check_tensor(out_eta, torch.float32, "out_eta", 1)
     _check(load().sidco_compress(_stream_handle(stream), _ptr(grad), _ptr(residual), d, delta, dist, stages,
                                  _ptr(out_idx), _ptr(out_val), _ptr(out_count), _ptr(out_eta)), "sidco_compress")
+
+
+GRAD_F32, GRAD_F16, GRAD_BF16 = 0, 1, 2
+
+
+def sidco_compress_typed(grad, residual, delta: float, dist: int, stages: int, out_idx, out_val, out_count, out_eta,
+                         stream=None) -> None:
+    """sidco_compress on a gradient tensor of dtype float32, float16 or bfloat16 (the residual stays float32)."""
+    import torch
+    codes = {torch.float32: GRAD_F32, torch.float16: GRAD_F16, torch.bfloat16: GRAD_BF16}
+    if not isinstance(grad, torch.Tensor) or grad.dtype not in codes:
+        raise TypeError("grad must be a CUDA tensor of dtype float32, float16 or bfloat16")
+    d = grad.numel()
+    _check_tensor(grad, grad.dtype, "grad")
+    if residual is not None:
+        _check_tensor(residual, torch.float32, "residual", d)
+    cap = sidco_out_capacity(d, delta)
+    _check_tensor(out_idx, torch.int32, "out_idx", cap)
+    _check_tensor(out_val, torch.float32, "out_val", cap)
+    _check_tensor(out_count, torch.int32, "out_count", 1)
+    _check_tensor(out_eta, torch.float32, "out_eta", 1)
+    _check(load().sidco_compress_typed(_stream_handle(stream), _ptr(grad), codes[grad.dtype], _ptr(residual), d, delta,
+                                       dist, stages, _ptr(out_idx), _ptr(out_val), _ptr(out_count), _ptr(out_eta)),
+           "sidco_compress_typed")
 
 
 def sidco_compress_ex(grad, residual, dist: int, ratios, out_idx, out_val, out_count, out_eta, stream=None) -> None:
@@ -391,12 +422,17 @@ def sidco_scatter_check(stream=None) -> bool:
 
 
 def sidco_fit(grad, residual, dist: int, stream=None) -> None:
-    """Enqueues steps 1-2 alone (error-compensation add fused with the stage-1 sums)."""
+    """Enqueues steps 1-2 alone (error-compensation add fused with the stage-1 sums); the gradient may be
+    float32, float16 or bfloat16."""
     import torch
-    _check_tensor(grad, torch.float32, "grad")
+    codes = {torch.float32: GRAD_F32, torch.float16: GRAD_F16, torch.bfloat16: GRAD_BF16}
+    if not isinstance(grad, torch.Tensor) or grad.dtype not in codes:
+        raise TypeError("grad must be a CUDA tensor of dtype float32, float16 or bfloat16")
+    _check_tensor(grad, grad.dtype, "grad")
     if residual is not None:
         _check_tensor(residual, torch.float32, "residual", grad.numel())
-    _check(load().sidco_fit(_stream_handle(stream), _ptr(grad), _ptr(residual), grad.numel(), dist), "sidco_fit")
+    _check(load().sidco_fit_typed(_stream_handle(stream), _ptr(grad), codes[grad.dtype], _ptr(residual), grad.numel(),
+                                  dist), "sidco_fit")
 
 
 def sidco_fit_result(stream=None) -> tuple[float, float, float, float]:

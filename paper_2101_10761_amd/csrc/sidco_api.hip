@@ -121,18 +121,22 @@ int ensure_workspace(DeviceCtx& c, size_t need)
 }
 
 // Fills the launch geometry and buffer pointers that every kernel of a call shares.
-void fill_common(Params& p, WorkspaceHead* h, const float* grad, float* residual, int64_t d, int dist)
+// `acc_scratch`: fp32 buffer of the workspace that receives acc when the gradient is 16-bit and there is no residual.
+void fill_common(Params& p, WorkspaceHead* h, const void* grad, float* residual, int64_t d, int dist,
+                 int gt = kGradF32, float* acc_scratch = nullptr)
 {
     memset(&p, 0, sizeof(p));
     p.grad = grad;
+    p.gt = gt;
     p.residual = residual;
-    p.acc = residual ? residual : grad;
+    p.acc_w = residual ? residual : (gt != kGradF32 ? acc_scratch : nullptr);
+    p.acc = p.acc_w ? p.acc_w : (const float*)grad;
     p.d = d;
     p.ntiles = (uint32_t)((d + kTile - 1) / kTile);
     p.nfull = (uint32_t)(d / kTile);
     p.nwaves = p.ntiles < (uint32_t)kMaxWaves ? p.ntiles : (uint32_t)kMaxWaves;
     p.nblocks = (p.nwaves + kWavesPerBlock - 1) / kWavesPerBlock;
-    p.vec_ok = aligned16(grad) && aligned16(residual);
+    p.vec_ok = (gt == kGradF32 ? aligned16(grad) : ((uintptr_t)grad & 7u) == 0) && aligned16(residual);
     p.dist = dist;
     p.st = &h->st;
 }
@@ -196,8 +200,11 @@ int make_events(DeviceCtx& c)
     return SIDCO_OK;
 }
 
-int run(void* stream, const float* grad, float* residual, int64_t d, int dist, const double* ratios, int M,
-        int32_t* out_idx, float* out_val, int64_t out_cap, int32_t* out_count, float* out_eta, bool acc_reset = true)
+size_t acc_bytes(int64_t d) { return seg_bytes(d) / 2; }  // one float per list slot
+
+int run(void* stream, const void* grad, float* residual, int64_t d, int dist, const double* ratios, int M,
+        int32_t* out_idx, float* out_val, int64_t out_cap, int32_t* out_count, float* out_eta, bool acc_reset = true,
+        int gt = kGradF32)
 {
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceCtx* cp = nullptr;
@@ -205,7 +212,8 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
     if (rc != SIDCO_OK) return rc;
     DeviceCtx& c = *cp;
     const size_t seg = seg_bytes(d);
-    rc = ensure_workspace(c, head_bytes() + 2 * seg);
+    const bool own_acc = gt != kGradF32 && !residual;  // the widened vector needs a home
+    rc = ensure_workspace(c, head_bytes() + 2 * seg + (own_acc ? acc_bytes(d) : 0));
     if (rc != SIDCO_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
@@ -214,7 +222,7 @@ int run(void* stream, const float* grad, float* residual, int64_t d, int dist, c
     int2* segbuf[2] = {(int2*)((char*)c.ws + head_bytes()), (int2*)((char*)c.ws + head_bytes() + seg)};
 
     Params p;
-    fill_common(p, h, grad, residual, d, dist);
+    fill_common(p, h, grad, residual, d, dist, gt, own_acc ? (float*)((char*)c.ws + head_bytes() + 2 * seg) : nullptr);
     p.M = M;
     for (int m = 0; m < M; ++m) p.L[m] = log(1.0 / ratios[m]);
     p.out_idx = out_idx;
@@ -392,7 +400,6 @@ int sidco_set_workspace(void* device_ptr, size_t bytes)
     c.bad_cleared = false;
     c.dgc_n_s = 0;
     c.batch_image.clear();
-    c.bad_cleared = false;
     return SIDCO_OK;
 }
 
@@ -422,6 +429,35 @@ int sidco_compress(void* stream, const float* grad, float* residual, int64_t d, 
     if (M < 1) return M;
     return run(stream, grad, residual, d, dist, ratios, M, out_idx, out_val, sidco_out_capacity(d, delta), out_count,
                out_eta);
+}
+
+int sidco_compress_typed(void* stream, const void* grad, int grad_dtype, float* residual, int64_t d, double delta,
+                         int dist, int stages, int32_t* out_idx, float* out_val, int32_t* out_count, float* out_eta)
+{
+    if (grad_dtype == SIDCO_GRAD_F32)
+        return sidco_compress(stream, (const float*)grad, residual, d, delta, dist, stages, out_idx, out_val, out_count,
+                              out_eta);
+    if (grad_dtype != SIDCO_GRAD_F16 && grad_dtype != SIDCO_GRAD_BF16) return SIDCO_ERR_ARG;
+    // the common checks want a 4-byte aligned gradient: hand them a stand-in and check the 2-byte alignment here
+    int rc = check_common(grad ? (const float*)out_val : nullptr, residual, d, dist, out_idx, out_val, out_count, out_eta);
+    if (rc != SIDCO_OK) return rc;
+    if (((uintptr_t)grad & 1u) != 0) return SIDCO_ERR_ALIGN;
+    if (residual && (const void*)residual == grad) return SIDCO_ERR_ARG;
+    if (!(delta > 0.0 && delta < 1.0)) return SIDCO_ERR_DELTA;
+    if (stages < 1 || stages > SIDCO_MAX_STAGES) return SIDCO_ERR_STAGES;
+    double ratios[SIDCO_MAX_STAGES];
+    const int M = sidco_stage_ratios(delta, stages, 0.25, ratios);
+    if (M < 1) return M;
+    return run(stream, grad, residual, d, dist, ratios, M, out_idx, out_val, sidco_out_capacity(d, delta), out_count,
+               out_eta, true, grad_dtype == SIDCO_GRAD_F16 ? kGradF16 : kGradBf16);
+}
+
+size_t sidco_workspace_bytes_typed(int64_t d, int grad_dtype, int has_residual)
+{
+    if (d < 1 || d > (int64_t)INT32_MAX) return 0;
+    if (grad_dtype != SIDCO_GRAD_F32 && grad_dtype != SIDCO_GRAD_F16 && grad_dtype != SIDCO_GRAD_BF16) return 0;
+    const bool own_acc = grad_dtype != SIDCO_GRAD_F32 && !has_residual;
+    return head_bytes() + 2 * seg_bytes(d) + (own_acc ? acc_bytes(d) : 0);
 }
 
 int sidco_adapt_stages(int stages, double khat_avg, double k, double eps_high, double eps_low, int max_stages)
@@ -1034,22 +1070,27 @@ int sidco_dgc_result(void* stream, int64_t* host_out)
     return SIDCO_OK;
 }
 
-int sidco_fit(void* stream, const float* grad, float* residual, int64_t d, int dist)
+int sidco_fit_typed(void* stream, const void* grad, int grad_dtype, float* residual, int64_t d, int dist)
 {
     if (!grad) return SIDCO_ERR_NULL;
+    if (grad_dtype != SIDCO_GRAD_F32 && grad_dtype != SIDCO_GRAD_F16 && grad_dtype != SIDCO_GRAD_BF16)
+        return SIDCO_ERR_ARG;
     if (d < 1 || d > (int64_t)INT32_MAX) return SIDCO_ERR_SIZE;
     if (dist != SIDCO_DIST_EXP && dist != SIDCO_DIST_GAMMA_GPD && dist != SIDCO_DIST_GPD) return SIDCO_ERR_DIST;
-    if (!aligned4(grad) || !aligned4(residual)) return SIDCO_ERR_ALIGN;
-    if (residual && (const void*)residual == (const void*)grad) return SIDCO_ERR_ARG;
+    const bool f32 = grad_dtype == SIDCO_GRAD_F32;
+    if (((uintptr_t)grad & (f32 ? 3u : 1u)) != 0 || !aligned4(residual)) return SIDCO_ERR_ALIGN;
+    if (residual && (const void*)residual == grad) return SIDCO_ERR_ARG;
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceCtx* cp = nullptr;
     int rc = current_ctx(&cp);
     if (rc != SIDCO_OK) return rc;
-    rc = ensure_workspace(*cp, head_bytes() + 2 * seg_bytes(d));
+    const bool own_acc = !f32 && !residual;
+    rc = ensure_workspace(*cp, head_bytes() + 2 * seg_bytes(d) + (own_acc ? acc_bytes(d) : 0));
     if (rc != SIDCO_OK) return rc;
     WorkspaceHead* h = (WorkspaceHead*)cp->ws;
     Params p;
-    fill_common(p, h, grad, residual, d, dist);
+    fill_common(p, h, grad, residual, d, dist, f32 ? kGradF32 : (grad_dtype == SIDCO_GRAD_F16 ? kGradF16 : kGradBf16),
+                own_acc ? (float*)((char*)cp->ws + head_bytes() + 2 * seg_bytes(d)) : nullptr);
     p.M = 1;
     p.acc_reset = 1;
     p.part_out = h->part[0];
@@ -1060,6 +1101,11 @@ int sidco_fit(void* stream, const float* grad, float* residual, int64_t d, int d
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "kernel launch");
     return SIDCO_OK;
+}
+
+int sidco_fit(void* stream, const float* grad, float* residual, int64_t d, int dist)
+{
+    return sidco_fit_typed(stream, grad, SIDCO_GRAD_F32, residual, d, dist);
 }
 
 int sidco_fit_result(void* stream, double* host_sums)

@@ -26,6 +26,47 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
     return v;
 }
 
+// Four consecutive gradient elements as fp32, starting at element 4 * v: one 16-byte load of an fp32
+// buffer, one 8-byte load of an fp16 / bf16 buffer (widening either type is exact).  `stream`: the
+// buffer is read once per call, keep it out of the caches' way.
+template <int GT>
+__device__ __forceinline__ f4 load_grad4(const void* __restrict__ g, size_t v, bool stream)
+{
+    if constexpr (GT == kGradF32) {
+        const f4* g4 = reinterpret_cast<const f4*>(g);
+        return stream ? __builtin_nontemporal_load(g4 + v) : g4[v];
+    } else {
+        const uint64_t* g8 = reinterpret_cast<const uint64_t*>(g);
+        const uint64_t w = stream ? __builtin_nontemporal_load(g8 + v) : g8[v];
+        const uint32_t w0 = (uint32_t)w, w1 = (uint32_t)(w >> 32);  // elements 0,1 and 2,3
+        f4 c;
+        if constexpr (GT == kGradBf16) {
+            c.x = __uint_as_float(w0 << 16);
+            c.y = __uint_as_float(w0 & 0xffff0000u);
+            c.z = __uint_as_float(w1 << 16);
+            c.w = __uint_as_float(w1 & 0xffff0000u);
+        } else {
+            typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+            const h2 lo = __builtin_bit_cast(h2, w0), hi = __builtin_bit_cast(h2, w1);
+            c.x = (float)lo.x;
+            c.y = (float)lo.y;
+            c.z = (float)hi.x;
+            c.w = (float)hi.y;
+        }
+        return c;
+    }
+}
+
+// one gradient element as fp32
+template <int GT>
+__device__ __forceinline__ float load_grad1(const void* __restrict__ g, int64_t i)
+{
+    if constexpr (GT == kGradF32) return reinterpret_cast<const float*>(g)[i];
+    else if constexpr (GT == kGradBf16)
+        return __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(g)[i] << 16);
+    else return (float)reinterpret_cast<const _Float16*>(g)[i];
+}
+
 // number of set bits of `mask` below this lane
 __device__ __forceinline__ uint32_t lane_prefix(unsigned long long mask)
 {

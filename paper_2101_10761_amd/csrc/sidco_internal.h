@@ -72,16 +72,22 @@ struct DevState {
 };
 
 // Kernel arguments (passed by value).
+// element type of the gradient buffer (the accumulated vector and the residual are always fp32)
+constexpr int kGradF32 = 0, kGradF16 = 1, kGradBf16 = 2;
+
 struct Params {
-    const float* grad;
+    const void* grad;       // d elements of type `gt`
+    int gt;                 // kGrad*
     float* residual;        // NULL: memoryless
-    const float* acc;       // dense working vector read by stage 1's compaction: residual, else grad
+    float* acc_w;           // where k_fit stores acc: residual; for a 16-bit gradient without residual a
+                            // workspace buffer; NULL when acc is the fp32 gradient itself
+    const float* acc;       // dense working vector read by stage 1's compaction: acc_w, else grad
     int64_t d;
     uint32_t ntiles;        // ceil(d / kTile)
     uint32_t nfull;         // d / kTile: tiles below this index are complete
     uint32_t nwaves;        // waves that own tiles
     uint32_t nblocks;       // grid size of the kernels that read the dense vector or write partial sums
-    int vec_ok;             // all dense buffers 16-byte aligned: float4 accesses allowed
+    int vec_ok;             // all dense buffers aligned for 4-element accesses (16 bytes; 8 for a 16-bit gradient)
     int reverse;            // a dense stage kernel walks every wave's tiles from the last to the first
     int acc_reset;          // k_fit: start the controller's count of reported pairs over instead of adding to it
     int dist;

@@ -322,27 +322,27 @@ __device__ __forceinline__ void fit_accum(float x, double& s1, double& s2, doubl
     }
 }
 
-// U complete tiles starting at tile t, float4 accesses
-template <int DIST, bool EC, int U>
-__device__ __forceinline__ void fit_tiles(const f4* __restrict__ g4, f4* __restrict__ r4, uint32_t t, int lane,
-                                          double& s1, double& s2, double& sl, int& se)
+// U complete tiles starting at tile t, 4-element accesses.  EC: acc = g + residual, stored back.  A
+// 16-bit gradient is widened to fp32 first and acc is always stored (into the residual, or, without
+// one, into the workspace's own buffer), because every later kernel reads an fp32 vector.
+template <int DIST, bool EC, int GT, int U>
+__device__ __forceinline__ void fit_tiles(const void* __restrict__ g, f4* a4, uint32_t t, int lane, double& s1,
+                                          double& s2, double& sl, int& se)
 {
+    constexpr bool WRITE = EC || GT != kGradF32;
     f4 a[U], b[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const size_t i = (size_t)(t + u) * 64 + lane;
-        // the gradient is read once per call when error compensation re-materialises acc in the
-        // residual: keep it out of the caches' way
-        a[u] = EC ? __builtin_nontemporal_load(g4 + i) : g4[i];
-        if (EC) b[u] = r4[i];
+        // the gradient is read once per call when acc is re-materialised elsewhere
+        a[u] = load_grad4<GT>(g, i, WRITE);
+        if (EC) b[u] = a4[i];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         f4 c = a[u];
-        if (EC) {
-            c = a[u] + b[u];
-            r4[(size_t)(t + u) * 64 + lane] = c;
-        }
+        if (EC) c = a[u] + b[u];
+        if (WRITE) a4[(size_t)(t + u) * 64 + lane] = c;
         fit_accum<DIST>(c.x, s1, s2, sl, se);
         fit_accum<DIST>(c.y, s1, s2, sl, se);
         fit_accum<DIST>(c.z, s1, s2, sl, se);
@@ -366,7 +366,17 @@ __device__ __forceinline__ void fit_reset_state(const Params& p)
     if (p.out_count) *p.out_count = 0;
 }
 
-template <int DIST, bool EC>
+// one element through the guarded scalar path
+template <int DIST, bool EC, int GT>
+__device__ __forceinline__ void fit_one(const Params& p, int64_t i, double& s1, double& s2, double& sl, int& se)
+{
+    float c = load_grad1<GT>(p.grad, i);
+    if (EC) c = c + p.acc_w[i];
+    if (EC || GT != kGradF32) p.acc_w[i] = c;
+    fit_accum<DIST>(c, s1, s2, sl, se);
+}
+
+template <int DIST, bool EC, int GT>
 __device__ __forceinline__ void fit_body(const Params& p, Blk b)
 {
     __shared__ double sh[kWavesPerBlock][4];
@@ -379,25 +389,17 @@ __device__ __forceinline__ void fit_body(const Params& p, Blk b)
         const uint32_t tf = t1 < p.nfull ? t1 : p.nfull;  // tiles [t0,tf) are complete
         uint32_t t = t0;
         if (p.vec_ok) {
-            const f4* __restrict__ g4 = reinterpret_cast<const f4*>(p.grad);
-            f4* __restrict__ r4 = reinterpret_cast<f4*>(p.residual);
+            f4* a4 = reinterpret_cast<f4*>(p.acc_w);
             // no second register buffer: with 16 waves per CU in flight it gained nothing (measured)
-            for (; t + 4 <= tf; t += 4) fit_tiles<DIST, EC, 4>(g4, r4, t, lane, s1, s2, sl, se);
-            for (; t < tf; ++t) fit_tiles<DIST, EC, 1>(g4, r4, t, lane, s1, s2, sl, se);
+            for (; t + 4 <= tf; t += 4) fit_tiles<DIST, EC, GT, 4>(p.grad, a4, t, lane, s1, s2, sl, se);
+            for (; t < tf; ++t) fit_tiles<DIST, EC, GT, 1>(p.grad, a4, t, lane, s1, s2, sl, se);
         }
         // unaligned buffers and the ragged last tile: guarded scalar accesses
         for (; t < t1; ++t) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int64_t i = (int64_t)t * kTile + lane * 4 + j;
-                if (i < p.d) {
-                    float c = p.grad[i];
-                    if (EC) {
-                        c = c + p.residual[i];
-                        p.residual[i] = c;
-                    }
-                    fit_accum<DIST>(c, s1, s2, sl, se);
-                }
+                if (i < p.d) fit_one<DIST, EC, GT>(p, i, s1, s2, sl, se);
             }
         }
     }
@@ -428,7 +430,7 @@ __device__ __forceinline__ void fit_body(const Params& p, Blk b)
 // The price is one partial sum per 256-thread block - far too many for every block of the next
 // kernel to add up - so a second, small kernel folds them into the usual 512 slots, in a fixed order.
 // ---------------------------------------------------------------------------------------------
-template <int DIST, bool EC>
+template <int DIST, bool EC, int GT>
 __global__ __launch_bounds__(kFlatBlock) void k_fit_flat(Params p, double* __restrict__ flat_part, uint32_t nflat)
 {
     __shared__ double sh[kFlatBlock / 64][4];
@@ -438,27 +440,18 @@ __global__ __launch_bounds__(kFlatBlock) void k_fit_flat(Params p, double* __res
     double s1 = 0.0, s2 = 0.0, sl = 0.0;
     int se = 0;
     if (i < nvec) {
-        const f4* __restrict__ g4 = reinterpret_cast<const f4*>(p.grad);
-        f4* __restrict__ r4 = reinterpret_cast<f4*>(p.residual);
-        f4 c = EC ? __builtin_nontemporal_load(g4 + i) : g4[i];
-        if (EC) {
-            c = c + r4[i];
-            r4[i] = c;
-        }
+        constexpr bool WRITE = EC || GT != kGradF32;
+        f4* a4 = reinterpret_cast<f4*>(p.acc_w);
+        f4 c = load_grad4<GT>(p.grad, i, WRITE);
+        if (EC) c = c + a4[i];
+        if (WRITE) a4[i] = c;
         fit_accum<DIST>(c.x, s1, s2, sl, se);
         fit_accum<DIST>(c.y, s1, s2, sl, se);
         fit_accum<DIST>(c.z, s1, s2, sl, se);
         fit_accum<DIST>(c.w, s1, s2, sl, se);
     }
     if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {  // the last d % 4 elements
-        for (int64_t j = (int64_t)nvec * 4; j < p.d; ++j) {
-            float c = p.grad[j];
-            if (EC) {
-                c = c + p.residual[j];
-                p.residual[j] = c;
-            }
-            fit_accum<DIST>(c, s1, s2, sl, se);
-        }
+        for (int64_t j = (int64_t)nvec * 4; j < p.d; ++j) fit_one<DIST, EC, GT>(p, j, s1, s2, sl, se);
     }
     double v[3] = {s1, s2, sl + (double)se};
     v[0] = wave_sum(v[0]);
@@ -1110,8 +1103,10 @@ __device__ __forceinline__ Params batch_params(const BatchArgs& a, bool final_gr
     const TensorDesc& ds = a.tb->desc[t];
     Params p;
     p.grad = a.grad + ds.offset;
+    p.gt = kGradF32;
     p.residual = a.residual ? a.residual + ds.offset : nullptr;
-    p.acc = p.residual ? p.residual : p.grad;
+    p.acc_w = p.residual;
+    p.acc = p.residual ? p.residual : a.grad + ds.offset;
     p.d = ds.d;
     p.ntiles = (uint32_t)((ds.d + kTile - 1) / kTile);
     p.nfull = (uint32_t)(ds.d / kTile);
@@ -1148,8 +1143,8 @@ __device__ __forceinline__ Params batch_params(const BatchArgs& a, bool final_gr
     return p;
 }
 
-template <int DIST, bool EC>
-__global__ __launch_bounds__(kBlock) void k_fit(Params p) { fit_body<DIST, EC>(p, whole_grid()); }
+template <int DIST, bool EC, int GT>
+__global__ __launch_bounds__(kBlock) void k_fit(Params p) { fit_body<DIST, EC, GT>(p, whole_grid()); }
 template <bool STATS, bool WRITE>
 __global__ __launch_bounds__(kBlock, 4) void k_compact(Params p) { compact_body<STATS, WRITE>(p, whole_grid()); }
 __global__ __launch_bounds__(kBlock, 4) void k_lists(Params p) { lists_body(p, whole_grid()); }
@@ -1161,7 +1156,7 @@ __global__ __launch_bounds__(kBlock) void k_fit_batched(BatchArgs a)
 {
     Blk b;
     const Params p = batch_params(a, false, b);
-    fit_body<DIST, EC>(p, b);
+    fit_body<DIST, EC, kGradF32>(p, b);
 }
 template <bool STATS, bool WRITE>
 __global__ __launch_bounds__(kBlock, 4) void k_compact_batched(BatchArgs a)
@@ -1192,41 +1187,60 @@ __global__ __launch_bounds__(kBlock) void k_gather_batched(BatchArgs a)
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
-template <bool EC>
-static void launch_fit_ec(const Params& p, hipStream_t s)
+template <bool EC, int GT>
+static void launch_fit_as(const Params& p, hipStream_t s)
 {
     const dim3 grid(p.nblocks), block(kBlock);
     switch (p.dist) {
-        case kDistExp: hipLaunchKernelGGL((k_fit<kDistExp, EC>), grid, block, 0, s, p); break;
-        case kDistGamma: hipLaunchKernelGGL((k_fit<kDistGamma, EC>), grid, block, 0, s, p); break;
-        default: hipLaunchKernelGGL((k_fit<kDistGpd, EC>), grid, block, 0, s, p); break;
+        case kDistExp: hipLaunchKernelGGL((k_fit<kDistExp, EC, GT>), grid, block, 0, s, p); break;
+        case kDistGamma: hipLaunchKernelGGL((k_fit<kDistGamma, EC, GT>), grid, block, 0, s, p); break;
+        default: hipLaunchKernelGGL((k_fit<kDistGpd, EC, GT>), grid, block, 0, s, p); break;
     }
 }
 
-template <bool EC>
-static void launch_fit_flat_ec(const Params& p, double* flat_part, uint32_t nflat, hipStream_t s)
+template <bool EC, int GT>
+static void launch_fit_flat_as(const Params& p, double* flat_part, uint32_t nflat, hipStream_t s)
 {
     const dim3 grid(nflat), block(kFlatBlock);
     switch (p.dist) {
-        case kDistExp: hipLaunchKernelGGL((k_fit_flat<kDistExp, EC>), grid, block, 0, s, p, flat_part, nflat); break;
-        case kDistGamma: hipLaunchKernelGGL((k_fit_flat<kDistGamma, EC>), grid, block, 0, s, p, flat_part, nflat); break;
-        default: hipLaunchKernelGGL((k_fit_flat<kDistGpd, EC>), grid, block, 0, s, p, flat_part, nflat); break;
+        case kDistExp:
+            hipLaunchKernelGGL((k_fit_flat<kDistExp, EC, GT>), grid, block, 0, s, p, flat_part, nflat);
+            break;
+        case kDistGamma:
+            hipLaunchKernelGGL((k_fit_flat<kDistGamma, EC, GT>), grid, block, 0, s, p, flat_part, nflat);
+            break;
+        default: hipLaunchKernelGGL((k_fit_flat<kDistGpd, EC, GT>), grid, block, 0, s, p, flat_part, nflat); break;
     }
+}
+
+template <bool EC, int GT>
+static void launch_fit_shape(const Params& p, double* scratch, hipStream_t s)
+{
+    if (fit_uses_flat(p.d, p.vec_ok != 0)) {
+        const uint32_t nflat = fit_flat_blocks(p.d);
+        launch_fit_flat_as<EC, GT>(p, scratch, nflat, s);
+        const uint32_t per = (nflat + kMaxBlocks - 1) / kMaxBlocks;
+        hipLaunchKernelGGL(k_fit_reduce, dim3(kMaxBlocks / kWavesPerBlock), dim3(kBlock), 0, s, p, scratch, nflat, per);
+        return;
+    }
+    launch_fit_as<EC, GT>(p, s);
+}
+
+template <int GT>
+static void launch_fit_type(const Params& p, double* scratch, hipStream_t s)
+{
+    if (p.residual) launch_fit_shape<true, GT>(p, scratch, s);
+    else launch_fit_shape<false, GT>(p, scratch, s);
 }
 
 // `scratch`: device memory for 3 * fit_flat_blocks(d) doubles when the flat shape is used (else unused)
 void launch_fit(const Params& p, double* scratch, hipStream_t s)
 {
-    if (fit_uses_flat(p.d, p.vec_ok != 0)) {
-        const uint32_t nflat = fit_flat_blocks(p.d);
-        if (p.residual) launch_fit_flat_ec<true>(p, scratch, nflat, s);
-        else launch_fit_flat_ec<false>(p, scratch, nflat, s);
-        const uint32_t per = (nflat + kMaxBlocks - 1) / kMaxBlocks;
-        hipLaunchKernelGGL(k_fit_reduce, dim3(kMaxBlocks / kWavesPerBlock), dim3(kBlock), 0, s, p, scratch, nflat, per);
-        return;
+    switch (p.gt) {
+        case kGradF16: launch_fit_type<kGradF16>(p, scratch, s); break;
+        case kGradBf16: launch_fit_type<kGradBf16>(p, scratch, s); break;
+        default: launch_fit_type<kGradF32>(p, scratch, s); break;
     }
-    if (p.residual) launch_fit_ec<true>(p, s);
-    else launch_fit_ec<false>(p, s);
 }
 
 void launch_compact(const Params& p, bool stats, bool write, hipStream_t s)

@@ -187,3 +187,25 @@ def test_dgc_argument_errors_and_sizes(lib, oracle):
     for d, delta, rho in ((1_000_000, 0.001, 0.01), (269_722, 0.01, 0.01), (10, 0.001, 0.01), (25_557_032, 0.001, 0.01),
                           (138_357_544, 0.1, 0.01), (1, 0.5, 1.0), (12345, 0.3, 0.7)):
         assert sidco.sidco_dgc_sizes(d, delta, rho) == oracle.dgc_sizes(d, delta, rho)
+
+
+def test_typed_argument_errors(lib):
+    ok = C.c_void_p(256)
+    f = lib.sidco_compress_typed
+    assert f(None, ok, 3, None, 1000, 0.01, 0, 1, ok, ok, ok, ok) == -9        # unknown element type
+    assert f(None, ok, -1, None, 1000, 0.01, 0, 1, ok, ok, ok, ok) == -9
+    for code in (1, 2):
+        assert f(None, None, code, None, 1000, 0.01, 0, 1, ok, ok, ok, ok) == -1
+        assert f(None, ok, code, None, 1000, 0.01, 0, 1, ok, ok, ok, None) == -1
+        assert f(None, ok, code, None, 0, 0.01, 0, 1, ok, ok, ok, ok) == -2
+        assert f(None, ok, code, None, 1000, 0.0, 0, 1, ok, ok, ok, ok) == -3
+        assert f(None, ok, code, None, 1000, 0.01, 0, 0, ok, ok, ok, ok) == -4
+        assert f(None, ok, code, None, 1000, 0.01, 5, 1, ok, ok, ok, ok) == -5
+        assert f(None, C.c_void_p(257), code, None, 1000, 0.01, 0, 1, ok, ok, ok, ok) == -8   # odd address
+        assert f(None, ok, code, ok, 1000, 0.01, 0, 1, C.c_void_p(512), C.c_void_p(512), ok, ok) == -9   # aliasing
+    assert f(None, None, 0, None, 1000, 0.01, 0, 1, ok, ok, ok, ok) == -1       # fp32 code: the plain call's checks
+    w = lib.sidco_workspace_bytes_typed
+    base = lib.sidco_workspace_bytes(1_000_000)
+    assert w(1_000_000, 0, 0) == base and w(1_000_000, 1, 1) == base and w(1_000_000, 2, 1) == base
+    assert w(1_000_000, 1, 0) == w(1_000_000, 2, 0) >= base + 4 * 1_000_000
+    assert w(0, 1, 0) == 0 and w(1000, 7, 0) == 0

@@ -1,0 +1,149 @@
+"""GPU parity of the sparsifier on 16-bit gradients (fp16 / bf16 inputs widened exactly to fp32 on the fly),
+through the C ABI, against the oracle run on the widened values."""
+import numpy as np
+import pytest
+
+from gpu_harness import GpuResult, check_parity
+
+pytestmark = pytest.mark.gpu
+
+
+def narrow(g32, kind):
+    """(torch CPU tensor of the 16-bit type, the same values widened back to float32 as numpy)."""
+    import torch
+    t = torch.from_numpy(g32).to(torch.float16 if kind == "f16" else torch.bfloat16)
+    return t, t.to(torch.float32).numpy()
+
+
+def run_typed(g16, r, dist, delta, stages, *, grad_offset=0, res_offset=0):
+    import torch
+    import paper_2101_10761_amd as sidco
+
+    dev = torch.device("cuda:0")
+    d = g16.numel()
+    gbuf = torch.zeros(d + grad_offset + 8, dtype=g16.dtype, device=dev)
+    gt = gbuf[grad_offset:grad_offset + d]
+    gt.copy_(g16)
+    rt = None
+    if r is not None:
+        rbuf = torch.zeros(d + res_offset + 8, dtype=torch.float32, device=dev)
+        rt = rbuf[res_offset:res_offset + d]
+        rt.copy_(torch.from_numpy(r))
+    cap = sidco.sidco_out_capacity(d, delta)
+    guard = 64
+    out_idx = torch.full((cap + guard,), -7, dtype=torch.int32, device=dev)
+    out_val = torch.full((cap + guard,), 7.0, dtype=torch.float32, device=dev)
+    out_count = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    out_eta = torch.full((1,), -1.0, dtype=torch.float32, device=dev)
+    sidco.sidco_compress_typed(gt, rt, delta, dist, stages, out_idx[:cap], out_val[:cap], out_count, out_eta)
+    diag = sidco.sidco_read_diag()
+    torch.cuda.synchronize()
+    k = int(out_count.item())
+    assert 0 <= k <= cap
+    assert torch.all(out_idx[cap:] == -7) and torch.all(out_val[cap:] == 7.0) and torch.all(out_idx[k:cap] == -7)
+    assert torch.equal(gt.cpu().view(torch.int16), g16.view(torch.int16))        # the gradient is read-only
+    assert torch.all(gbuf[:grad_offset].view(torch.int16) == 0) and torch.all(gbuf[grad_offset + d:].view(torch.int16) == 0)
+    if rt is not None:
+        assert torch.all(rbuf[res_offset + d:] == 0) and torch.all(rbuf[:res_offset] == 0)
+    M = diag.stages
+    return GpuResult(
+        idx=out_idx[:k].cpu().numpy(), val=out_val[:k].cpu().numpy(), count=k, eta=float(out_eta.item()),
+        residual=None if rt is None else rt.cpu().numpy(),
+        etas=np.array(diag.eta[:M], dtype=np.float32), n=np.array(diag.n[:M], dtype=np.int64),
+        stats=np.array([[diag.stats[m][q] for q in range(3)] for m in range(M)]), status=diag.status,
+        selected=diag.selected)
+
+
+def _grad(seed, d, scale=1e-3):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return (rng.standard_t(3.0, d) * scale).astype(np.float32), rng
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("dist", [0, 1, 2])
+@pytest.mark.parametrize("with_residual", [True, False])
+def test_laws_and_types(oracle, kind, dist, with_residual):
+    import paper_2101_10761_amd as sidco
+    d = 1_500_003
+    g32, rng = _grad(31 + dist, d)            # at this scale many fp16 values are subnormal
+    g16, gw = narrow(g32, kind)
+    r = rng.laplace(0.0, 2e-4, d).astype(np.float32) if with_residual else None
+    delta, stages = 0.002, 3
+    res = run_typed(g16, r, dist, delta, stages)
+    ratios = sidco.sidco_stage_ratios(delta, stages)
+    check_parity(oracle, gw, r, dist, ratios, res, capacity=sidco.sidco_out_capacity(d, delta),
+                 label=f"{kind} dist {dist} residual {with_residual}")
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("d", [1, 3, 255, 256, 257, 1025, 70_001])
+def test_small_and_ragged_sizes(oracle, kind, d):
+    import paper_2101_10761_amd as sidco
+    g32, rng = _grad(d, d)
+    g16, gw = narrow(g32, kind)
+    r = rng.laplace(0.0, 1e-3, d).astype(np.float32)
+    for with_r in (True, False):
+        res = run_typed(g16, r if with_r else None, 0, 0.05, 2)
+        check_parity(oracle, gw, r if with_r else None, 0, sidco.sidco_stage_ratios(0.05, 2), res,
+                     capacity=sidco.sidco_out_capacity(d, 0.05), label=f"{kind} d {d} residual {with_r}")
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("go,ro", [(1, 0), (4, 0), (0, 1), (3, 2), (4, 4)])
+def test_unaligned_buffers(oracle, kind, go, ro):
+    """A gradient offset of 4 elements keeps the 8-byte alignment of the vector path; 1 and 3 do not."""
+    import paper_2101_10761_amd as sidco
+    d = 400_009
+    g32, rng = _grad(5, d)
+    g16, gw = narrow(g32, kind)
+    r = rng.laplace(0.0, 3e-4, d).astype(np.float32)
+    res = run_typed(g16, r, 2, 0.005, 2, grad_offset=go, res_offset=ro)
+    check_parity(oracle, gw, r, 2, sidco.sidco_stage_ratios(0.005, 2), res,
+                 capacity=sidco.sidco_out_capacity(d, 0.005), label=f"{kind} offsets {go},{ro}")
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_special_values(oracle, kind):
+    """Zeros, signed zeros, the type's extremes and subnormals widen exactly; an infinity makes the sums non-finite."""
+    import torch
+    import paper_2101_10761_amd as sidco
+    d = 50_000
+    g32, rng = _grad(9, d, 1e-2)
+    g16, _ = narrow(g32, kind)
+    raw = g16.view(torch.int16)
+    raw[0], raw[1] = 0, -32768                      # +0, -0
+    raw[2], raw[3] = 1, -32767                      # smallest subnormals of either sign
+    raw[4] = 0x7BFF if kind == "f16" else 0x7F7F    # largest finite value
+    gw = g16.to(torch.float32).numpy()
+    res = run_typed(g16, None, 0, 0.01, 1)
+    check_parity(oracle, gw, None, 0, [0.01], res, capacity=sidco.sidco_out_capacity(d, 0.01), label=f"{kind} extremes")
+    assert 4 in res.idx
+    raw[5] = 0x7C00 if kind == "f16" else 0x7F80    # +infinity
+    gw = g16.to(torch.float32).numpy()
+    res = run_typed(g16, np.zeros(d, np.float32), 0, 0.01, 1)
+    assert res.status & 1 and res.count == 0 and np.isnan(res.eta)
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_headline_size_with_error_feedback(oracle, kind):
+    import paper_2101_10761_amd as sidco
+    from paper_2101_10761_amd import workloads
+    w = workloads.config3()
+    g16, gw = narrow(w.grad, kind)
+    ratios = sidco.sidco_stage_ratios(w.delta, w.stages)
+    r = np.zeros(w.d, np.float32)
+    for it in range(2):                             # the second call carries the first one's residual
+        res = run_typed(g16, r, w.dist, w.delta, w.stages)
+        check_parity(oracle, gw, r, w.dist, ratios, res, capacity=sidco.sidco_out_capacity(w.d, w.delta),
+                     label=f"{kind} cfg3 iteration {it}")
+        r = res.residual
+
+
+def test_f32_code_is_the_plain_call(oracle):
+    import paper_2101_10761_amd as sidco
+    d = 300_000
+    g32, _ = _grad(77, d)
+    import torch
+    res = run_typed(torch.from_numpy(g32), None, 2, 0.01, 2)
+    check_parity(oracle, g32, None, 2, sidco.sidco_stage_ratios(0.01, 2), res,
+                 capacity=sidco.sidco_out_capacity(d, 0.01), label="f32 through the typed entry point")
