@@ -27,17 +27,21 @@ __device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
 }
 
 // Four consecutive gradient elements as fp32, starting at element 4 * v: one 16-byte load of an fp32
-// buffer, one 8-byte load of an fp16 / bf16 buffer (widening either type is exact).  `stream`: the
-// buffer is read once per call, keep it out of the caches' way.
-template <int GT>
-__device__ __forceinline__ f4 load_grad4(const void* __restrict__ g, size_t v, bool stream)
+// buffer, one 8-byte load of an fp16 / bf16 buffer (widening either type is exact).  STREAM: the
+// buffer is read once per call, keep it out of the caches' way (a template parameter: as a run-time
+// flag the two loads are merged and the non-temporal hint is lost).
+template <int GT, bool STREAM>
+__device__ __forceinline__ f4 load_grad4(const void* __restrict__ g, size_t v)
 {
     if constexpr (GT == kGradF32) {
         const f4* g4 = reinterpret_cast<const f4*>(g);
-        return stream ? __builtin_nontemporal_load(g4 + v) : g4[v];
+        if constexpr (STREAM) return __builtin_nontemporal_load(g4 + v);
+        else return g4[v];
     } else {
         const uint64_t* g8 = reinterpret_cast<const uint64_t*>(g);
-        const uint64_t w = stream ? __builtin_nontemporal_load(g8 + v) : g8[v];
+        uint64_t w;
+        if constexpr (STREAM) w = __builtin_nontemporal_load(g8 + v);
+        else w = g8[v];
         const uint32_t w0 = (uint32_t)w, w1 = (uint32_t)(w >> 32);  // elements 0,1 and 2,3
         f4 c;
         if constexpr (GT == kGradBf16) {

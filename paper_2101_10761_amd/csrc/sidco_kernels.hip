@@ -326,7 +326,7 @@ __device__ __forceinline__ void fit_accum(float x, double& s1, double& s2, doubl
 // 16-bit gradient is widened to fp32 first and acc is always stored (into the residual, or, without
 // one, into the workspace's own buffer), because every later kernel reads an fp32 vector.
 template <int DIST, bool EC, int GT, int U>
-__device__ __forceinline__ void fit_tiles(const void* __restrict__ g, f4* a4, uint32_t t, int lane, double& s1,
+__device__ __forceinline__ void fit_tiles(const void* __restrict__ g, f4* __restrict__ a4, uint32_t t, int lane, double& s1,
                                           double& s2, double& sl, int& se)
 {
     constexpr bool WRITE = EC || GT != kGradF32;
@@ -335,7 +335,7 @@ __device__ __forceinline__ void fit_tiles(const void* __restrict__ g, f4* a4, ui
     for (int u = 0; u < U; ++u) {
         const size_t i = (size_t)(t + u) * 64 + lane;
         // the gradient is read once per call when acc is re-materialised elsewhere
-        a[u] = load_grad4<GT>(g, i, WRITE);
+        a[u] = load_grad4<GT, WRITE>(g, i);
         if (EC) b[u] = a4[i];
     }
 #pragma unroll
@@ -442,7 +442,7 @@ __global__ __launch_bounds__(kFlatBlock) void k_fit_flat(Params p, double* __res
     if (i < nvec) {
         constexpr bool WRITE = EC || GT != kGradF32;
         f4* a4 = reinterpret_cast<f4*>(p.acc_w);
-        f4 c = load_grad4<GT>(p.grad, i, WRITE);
+        f4 c = load_grad4<GT, WRITE>(p.grad, i);
         if (EC) c = c + a4[i];
         if (WRITE) a4[i] = c;
         fit_accum<DIST>(c.x, s1, s2, sl, se);

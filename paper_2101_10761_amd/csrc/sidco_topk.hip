@@ -70,7 +70,8 @@ __global__ __launch_bounds__(kBlock) void k_topk_hist(TopkParams p)
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const size_t i = (size_t)(t + u) * 64 + lane;
-                    a[u] = g4[i];
+                    // read once per call when acc is stored elsewhere: keep it out of the caches' way
+                    a[u] = EC ? __builtin_nontemporal_load(g4 + i) : g4[i];
                     if (EC) b[u] = r4[i];
                 }
 #pragma unroll
