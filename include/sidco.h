@@ -73,6 +73,11 @@ extern "C" {
                                            dense vector again (see sidco_set_speculation); the result
                                            is the same either way                                     */
 
+#define SIDCO_ST_FUSED        (1u << 7) /* performance only: the first pass also did the first stage's
+                                           work (statistics above eta_1, candidate lists) from the
+                                           previous call's thresholds, so no second pass over the
+                                           vector was needed (see sidco_set_fusion)                   */
+
 /* Per-call diagnostics, filled on the device by the kernels of the last call. */
 typedef struct sidco_diag {
     float    eta[SIDCO_MAX_STAGES];      /* eta_m, fp32, m = 1..M (Lemma 2: absolute thresholds)      */
@@ -337,6 +342,18 @@ int sidco_set_workspace(void *device_ptr, size_t bytes);
  * to the calls that follow, on every device.
  */
 int sidco_set_speculation(double theta);
+
+/*
+ * Fused first stage (default on).  A call that repeats the previous call's
+ * shape on the device lets its first pass do the first stage's work as well:
+ * the statistics of the exceedances of eta_1 come from moments above, and the
+ * entries inside, a narrow band around the previous call's eta_1, and the
+ * candidate lists for stage 2 from the previous call's thresholds.  When this
+ * call's eta_1 falls inside the band no second pass over the vector is needed
+ * (SIDCO_ST_FUSED); otherwise the first stage reads the vector as usual
+ * (SIDCO_ST_FALLBACK).  The result is the same either way.  0 switches it off.
+ */
+int sidco_set_fusion(int enable);
 
 /* Copy the diagnostics of the last call on the current device to host memory.
  * Synchronises `stream`.                                                      */

@@ -49,6 +49,7 @@ struct DeviceCtx {
     int prof_n = 0;            // kernels of the last profiled call
     const char* prof_name[kMaxKernels] = {};
     int64_t dgc_n_s = 0, dgc_k_s = 0;  // sizes of the last sidco_dgc call
+    bool fused_primed = false;         // the previous call of this shape ran with the fused first stage
     bool bad_cleared = false;  // the scatter kernels' bad-index flag has been initialised in this workspace
     int64_t last_cap = 0;      // output capacity of the last compress call
     // shape of the last compress call: a call that repeats it may use the device's record of where the
@@ -72,6 +73,7 @@ std::mutex g_mu;
 DeviceCtx g_ctx[kMaxDevices];
 bool g_profiling = false;
 double g_speculation = kSpeculation;
+bool g_fusion = true;
 thread_local char g_hip_msg[256] = "";
 
 int hip_fail(hipError_t e, const char* what)
@@ -241,6 +243,26 @@ int run(void* stream, const void* grad, float* residual, int64_t d, int dist, co
     c.sig_theta = theta;
     for (int m = 0; m < M; ++m) c.sig_ratios[m] = ratios[m];
     p.use_hint = same_shape ? 1 : 0;
+    // Fused first stage: k_fit also prepares what the first stage's kernel needs, from the previous call's
+    // thresholds.  Only for a call that repeats the previous call's shape and whose first stage writes
+    // candidate lists; not in the large-vector launch shape of k_fit, which has no per-wave lists.
+    bool fused = false;
+    if (g_fusion && same_shape && M >= 2 && theta > 0.0 && !fit_uses_flat(d, p.vec_ok != 0))
+        fused = exp(-(p.L[0] + theta * p.L[1])) <= kMaterializeBelow;
+    p.fused = fused ? 1 : 0;
+    p.fused_first = (fused && !c.fused_primed) ? 1 : 0;
+    c.fused_primed = fused;
+    if (fused) {
+        // the candidate threshold's rule needs the first stage's theta range before the first kernel
+        p.theta = (float)theta;
+        p.theta_min = hint_floor(1.0, p.L[0], p.L[1]);
+        // where the first stage's kernel (buffers: in = 0, out = 1) expects each piece
+        p.band_out = (float*)segbuf[0];
+        p.band_cnt = h->cnt[0];
+        p.cand_out = segbuf[1];
+        p.cand_cnt = h->cnt[1];
+        p.raw_out = h->part[1];
+    }
 
     const bool prof = g_profiling;
     if (prof) {
@@ -1157,6 +1179,13 @@ int sidco_set_speculation(double theta)
     if (!(theta >= 0.0 && theta <= 1.0)) return SIDCO_ERR_ARG;
     std::lock_guard<std::mutex> lock(g_mu);
     g_speculation = theta;
+    return SIDCO_OK;
+}
+
+int sidco_set_fusion(int enable)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_fusion = enable != 0;
     return SIDCO_OK;
 }
 

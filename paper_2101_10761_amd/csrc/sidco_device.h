@@ -90,22 +90,31 @@ __device__ __forceinline__ uint32_t tile_begin(uint32_t w, uint32_t ntiles, uint
 // 1.6 M entries out of 25.6 M elements add 9 us as they come and 3 us staged).
 constexpr uint32_t kRingFlush = 512;                // staged entries that trigger a write-out
 constexpr uint32_t kRingSize = kRingFlush + kTile;  // a whole tile can arrive between two checks
-struct ListWriter {
-    int2* __restrict__ list;  // the wave's list in global memory (room for every element of its tiles)
-    int2* ring;               // the wave's staging area in LDS, kRingSize entries
-    uint32_t run;             // entries already written to `list` (wave-uniform)
-    uint32_t fill;            // entries staged in `ring` (wave-uniform, < kRingFlush after list_flush)
+template <typename T>
+struct ListWriterT {
+    T* __restrict__ list;  // the wave's list in global memory (room for every element of its tiles)
+    T* ring;               // the wave's staging area in LDS, kRingSize entries
+    uint32_t run;          // entries already written to `list` (wave-uniform)
+    uint32_t fill;         // entries staged in `ring` (wave-uniform, < kRingFlush after list_flush)
 };
+typedef ListWriterT<int2> ListWriter;  // (index, value bits) pairs
 
-__device__ __forceinline__ void list_push(ListWriter& lw, bool keep, int32_t idx, float x, int lane)
+template <typename T>
+__device__ __forceinline__ void list_push_entry(ListWriterT<T>& lw, bool keep, T e, int lane)
 {
     const unsigned long long mask = __ballot(keep);
-    if (keep) lw.ring[lw.fill + lane_prefix(mask)] = make_int2(idx, __float_as_int(x));
+    if (keep) lw.ring[lw.fill + lane_prefix(mask)] = e;
     lw.fill += (uint32_t)__popcll(mask);
 }
 
+__device__ __forceinline__ void list_push(ListWriter& lw, bool keep, int32_t idx, float x, int lane)
+{
+    list_push_entry(lw, keep, make_int2(idx, __float_as_int(x)), lane);
+}
+
 // After at most kTile pushes: writes out kRingFlush entries at a time while that many are staged.
-__device__ __forceinline__ void list_flush(ListWriter& lw, int lane)
+template <typename T>
+__device__ __forceinline__ void list_flush(ListWriterT<T>& lw, int lane)
 {
     if (lw.fill < kRingFlush) return;  // wave-uniform
     const uint32_t whole = lw.fill & ~(kRingFlush - 1);
@@ -121,7 +130,8 @@ __device__ __forceinline__ void list_flush(ListWriter& lw, int lane)
 }
 
 // writes out what is still staged; returns the list's length
-__device__ __forceinline__ uint32_t list_finish(ListWriter& lw, int lane)
+template <typename T>
+__device__ __forceinline__ uint32_t list_finish(ListWriterT<T>& lw, int lane)
 {
 #pragma unroll 1
     for (uint32_t c = 0; c < lw.fill; c += 64)

@@ -1,0 +1,163 @@
+"""GPU parity of calls that take the fused first stage: a call that repeats the previous call's shape lets its
+first pass prepare the first stage's statistics and the candidate lists from the previous call's thresholds.
+Whether that preparation is used (eta_1 inside the band) or not (fallback to the dense pass), the result must be
+the oracle's."""
+import numpy as np
+import pytest
+
+from gpu_harness import check_parity, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+ST_FALLBACK, ST_FUSED = 64, 128
+
+
+def _student(seed, d, scale=1e-3):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return (rng.standard_t(3.0, d) * scale).astype(np.float32)
+
+
+@pytest.fixture(autouse=True)
+def _fusion_on():
+    import paper_2101_10761_amd as sidco
+    sidco.sidco_set_fusion(True)
+    sidco.sidco_set_speculation(0.5)
+    yield
+    sidco.sidco_set_fusion(True)
+
+
+def _reset_shape():
+    """A call of another shape: the next call starts without any record of an earlier one."""
+    run_gpu(_student(1, 1000), None, 0, [0.1])
+
+
+@pytest.mark.parametrize("dist", [0, 1, 2])
+@pytest.mark.parametrize("stages", [2, 3])
+def test_repeated_calls_take_the_fused_stage_and_match_the_oracle(oracle, dist, stages):
+    import paper_2101_10761_amd as sidco
+    d = 2_000_003
+    g = _student(10 + dist, d)
+    ratios = sidco.sidco_stage_ratios(0.002, stages)
+    _reset_shape()
+    flags = []
+    for it in range(4):
+        gi = (g * np.float32(1.0 + 0.003 * it)).astype(np.float32)   # eta_1 moves by 0.3 % per call
+        res = run_gpu(gi, None, dist, ratios)
+        check_parity(oracle, gi, None, dist, ratios, res, label=f"dist {dist} M {stages} call {it}")
+        flags.append(res.status & (ST_FUSED | ST_FALLBACK))
+    assert flags[0] == 0                       # nothing to go by
+    assert flags[2] == ST_FUSED and flags[3] == ST_FUSED, flags
+    assert flags[1] in (ST_FUSED, ST_FALLBACK, ST_FUSED | ST_FALLBACK, 0), flags
+
+
+def test_error_feedback_loop_with_fusion(oracle):
+    """The residual is carried: acc changes from call to call, and with it every threshold.  Under a constant
+    gradient the accumulated vector grows like the iteration count t, so eta_1 moves by about 1/t per call: the
+    first dozen calls fall outside any band (fallback), later ones inside."""
+    import paper_2101_10761_amd as sidco
+    d = 1_000_001
+    g = _student(21, d)
+    ratios = sidco.sidco_stage_ratios(0.001, 3)
+    r = np.zeros(d, np.float32)
+    _reset_shape()
+    flags = []
+    for it in range(20):
+        res = run_gpu(g, r, 2, ratios)
+        check_parity(oracle, g, r, 2, ratios, res, label=f"EC call {it}")
+        r = res.residual
+        flags.append(res.status & (ST_FUSED | ST_FALLBACK))
+    assert ST_FALLBACK in flags[1:6], flags
+    assert flags[-1] == ST_FUSED and flags[-2] == ST_FUSED, flags
+
+
+def test_threshold_outside_the_band_falls_back(oracle):
+    import paper_2101_10761_amd as sidco
+    d = 1_500_000
+    g = _student(31, d)
+    ratios = sidco.sidco_stage_ratios(0.002, 3)
+    _reset_shape()
+    seq = [1.0, 1.0, 1.5, 1.5, 0.5, 0.5, 1.019, 0.982]
+    want = [0, ST_FUSED, ST_FALLBACK, ST_FUSED, ST_FALLBACK, ST_FUSED, None, None]
+    for it, (s, w) in enumerate(zip(seq, want)):
+        gi = (g * np.float32(s)).astype(np.float32)
+        res = run_gpu(gi, None, 0, ratios)
+        check_parity(oracle, gi, None, 0, ratios, res, label=f"scale {s} call {it}")
+        got = res.status & (ST_FUSED | ST_FALLBACK)
+        if w is not None:
+            assert got & (ST_FUSED | ST_FALLBACK) == w or (w == ST_FALLBACK and got & ST_FALLBACK), (it, s, got)
+
+
+@pytest.mark.parametrize("d,go,ro", [(100_003, 0, 0), (700_001, 1, 0), (700_001, 0, 3), (257, 0, 0), (70_000, 2, 2)])
+def test_ragged_and_unaligned(oracle, d, go, ro):
+    import paper_2101_10761_amd as sidco
+    g = _student(d, d)
+    rng = np.random.Generator(np.random.PCG64(d + 1))
+    r = rng.laplace(0.0, 2e-4, d).astype(np.float32)
+    ratios = sidco.sidco_stage_ratios(0.01, 2)
+    _reset_shape()
+    seen = 0
+    for it in range(3):
+        res = run_gpu(g, r, 2, ratios, grad_offset=go, res_offset=ro)
+        check_parity(oracle, g, r, 2, ratios, res, label=f"d {d} offsets {go},{ro} call {it}")
+        seen |= res.status
+    assert seen & (ST_FUSED | ST_FALLBACK)
+
+
+def test_switched_off(oracle):
+    import paper_2101_10761_amd as sidco
+    d = 800_000
+    g = _student(41, d)
+    ratios = sidco.sidco_stage_ratios(0.002, 3)
+    sidco.sidco_set_fusion(False)
+    _reset_shape()
+    for it in range(3):
+        res = run_gpu(g, None, 2, ratios)
+        check_parity(oracle, g, None, 2, ratios, res, label=f"fusion off call {it}")
+        assert not res.status & ST_FUSED
+
+
+def test_non_finite_value_in_a_later_call(oracle):
+    import paper_2101_10761_amd as sidco
+    d = 600_000
+    g = _student(51, d)
+    ratios = sidco.sidco_stage_ratios(0.002, 2)
+    _reset_shape()
+    for it in range(2):
+        res = run_gpu(g, None, 0, ratios)
+        check_parity(oracle, g, None, 0, ratios, res, label=f"finite call {it}")
+    bad = g.copy()
+    bad[123_456] = np.nan
+    res = run_gpu(bad, None, 0, ratios)
+    assert res.status & 1 and res.count == 0 and np.isnan(res.eta)
+    res = run_gpu(g, None, 0, ratios)           # and the call after it recovers
+    check_parity(oracle, g, None, 0, ratios, res, label="after the NaN")
+
+
+def test_constant_magnitudes_and_zeros(oracle):
+    import paper_2101_10761_amd as sidco
+    d = 300_000
+    ratios = sidco.sidco_stage_ratios(0.01, 2)
+    c = np.full(d, 3e-3, dtype=np.float32)
+    c[::2] *= -1
+    _reset_shape()
+    for it in range(3):
+        res = run_gpu(c, None, 2, ratios)
+        check_parity(oracle, c, None, 2, ratios, res, label=f"constant call {it}")
+    z = np.zeros(d, np.float32)
+    for it in range(2):
+        res = run_gpu(z, None, 0, ratios)
+        check_parity(oracle, z, None, 0, ratios, res, label=f"zeros call {it}")
+
+
+def test_headline_configuration_steady_state(oracle):
+    import paper_2101_10761_amd as sidco
+    from paper_2101_10761_amd import workloads
+    w = workloads.config3()
+    ratios = sidco.sidco_stage_ratios(w.delta, w.stages, w.delta1)
+    _reset_shape()
+    flags = []
+    for it in range(3):                       # the same input every time (the residual starts from zero each call)
+        res = run_gpu(w.grad, w.residual, w.dist, ratios)
+        check_parity(oracle, w.grad, w.residual, w.dist, ratios, res, label=f"cfg3 call {it}")
+        flags.append(res.status & (ST_FUSED | ST_FALLBACK))
+    assert flags == [0, ST_FUSED, ST_FUSED], flags
