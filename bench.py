@@ -6,8 +6,12 @@ final compaction and residual update = one sidco_compress call) over one synthet
 already resident in HBM.  The default workload is the configuration the headline metric is quoted on:
 d = 25,557,032 fp32, Student-t(3) values, delta = 0.001, three generalized-Pareto stages, error feedback.
 
-Several distinct gradient buffers (more than the 256 MB of memory-side cache) are used in rotation, so
-every step reads its gradient from HBM, and the residual is carried from step to step as in training.
+Several (gradient, residual) buffer pairs - more data than the 256 MB memory-side cache holds - are used in
+rotation, as if that many workers took turns on the GPU: every step reads its gradient AND its carried
+residual from HBM, as a training step does whose forward and backward passes have flushed the caches since
+the previous compression.  Each pair carries its own residual from one of its steps to the next.
+(`--residual-buffers 1` keeps one residual for all steps: it then stays in the memory-side cache between
+steps and the first pass runs about a quarter faster - a figure that no training loop would see.)
 
 Prints ONE JSON line on stdout; everything else goes to stderr.
 """
@@ -62,6 +66,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-topk", action="store_true", help="skip the exact Top-k comparator leg")
     ap.add_argument("--no-dgc", action="store_true", help="skip the DGC comparator leg")
+    ap.add_argument("--residual-buffers", type=int, default=0,
+                    help="carried residuals in rotation (0 = as many as gradient buffers; 1 = a single residual "
+                         "that stays cache-resident between steps)")
+    ap.add_argument("--no-fusion", action="store_true",
+                    help="switch the fused first stage of repeated same-shape calls off (sidco_set_fusion)")
     ap.add_argument("--grad-dtype", choices=["f32", "f16", "bf16"], default="f32",
                     help="element type of the gradient buffer (the residual and all arithmetic stay fp32/fp64); "
                          "16-bit gradients use the default stage schedule (delta_1 = 0.25) and skip the comparators")
@@ -75,6 +84,7 @@ def main():
     import paper_2101_10761_amd as sidco
 
     sidco.load()  # fails loudly when the HIP library has not been built
+    sidco.sidco_set_fusion(not args.no_fusion)
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         sys.exit(3)
@@ -103,7 +113,15 @@ def main():
     # independent draws that are hardly ever selected.
     grads = [g0] + [g0.clone() for _ in range(nbuf - 1)]
     ec = w.residual is not None
-    residual = torch.from_numpy(w.residual).to(dev) if ec else None
+    nres = nbuf if args.residual_buffers <= 0 else min(args.residual_buffers, nbuf)
+
+    def fresh_residuals():
+        if not ec:
+            return [None] * nres
+        r0 = torch.from_numpy(w.residual).to(dev)
+        return [r0] + [r0.clone() for _ in range(nres - 1)]
+
+    residuals = fresh_residuals()
     cap = max(sidco.sidco_out_capacity(d, w.delta), 1)
     out_idx = torch.empty(cap, dtype=torch.int32, device=dev)
     out_val = torch.empty(cap, dtype=torch.float32, device=dev)
@@ -113,10 +131,10 @@ def main():
 
     def step(i):
         if typed:
-            sidco.sidco_compress_typed(grads[i % nbuf], residual, w.delta, w.dist, w.stages, out_idx, out_val,
+            sidco.sidco_compress_typed(grads[i % nbuf], residuals[i % nres], w.delta, w.dist, w.stages, out_idx, out_val,
                                        out_count, out_eta, stream=stream)
         else:
-            sidco.sidco_compress_ex(grads[i % nbuf], residual, w.dist, ratios, out_idx, out_val, out_count, out_eta,
+            sidco.sidco_compress_ex(grads[i % nbuf], residuals[i % nres], w.dist, ratios, out_idx, out_val, out_count, out_eta,
                                     stream=stream)
 
     for i in range(args.warmup):
@@ -162,25 +180,34 @@ def main():
 
     # Dominant kernel on its own: batches of back-to-back k_fit launches (sidco_fit) between two HIP
     # events on the same stream, so that the events' own dispatch latency (several microseconds, which
-    # the in-sequence figures above include) is spread over the batch.
+    # the in-sequence figures above include) is spread over the batch.  After steps that took the fused
+    # first stage, sidco_fit runs that same variant of the kernel.  Every launch of a batch gets its own
+    # copy of the carried residual (restored, untimed, before each batch), so that each one sees the
+    # values of a real step rather than a residual that has already absorbed the gradient several times.
+    fused_steps = bool(diag.status & sidco.ST_FUSED)
     batch, fit_ms = 20, []
     ev_a, ev_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    scratch_res = residual.clone() if ec else None
+    n_done = args.warmup + args.steps + args.profile_steps
+    residual = residuals[n_done % nres]          # the residual the next step would use
+    scratch_res = [residual.clone() for _ in range(batch)] if ec else [None] * batch
     for rep in range(12):
         if ec:
-            scratch_res.copy_(residual)          # untimed: keeps the values in the range of a real step
+            for sr in scratch_res:
+                sr.copy_(residual)
         torch.cuda.synchronize()
         ev_a.record(stream)
         for i in range(batch):
-            sidco.sidco_fit(grads[(rep * batch + i) % nbuf], scratch_res, w.dist, stream=stream)
+            sidco.sidco_fit(grads[(rep * batch + i) % nbuf], scratch_res[i], w.dist, stream=stream)
         ev_b.record(stream)
         ev_b.synchronize()
         if rep >= 2:
             fit_ms.append(ev_a.elapsed_time(ev_b) / batch)
+    del scratch_res
     fit_bpe = gbytes + (8 if ec else (4 if typed else 0))   # read g [, read r], write acc unless acc is g itself
     fit_bytes = fit_bpe * d
     fit_us = float(np.mean(fit_ms)) * 1e3
-    log(f"k_fit alone: {fit_us:.1f} us per launch (HIP events around batches of {batch})")
+    log(f"k_fit alone{' (fused first stage)' if fused_steps else ''}: {fit_us:.1f} us per launch "
+        f"(HIP events around batches of {batch})")
     achieved = fit_bytes / (fit_us * 1e-6) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
@@ -190,7 +217,7 @@ def main():
         except Exception:
             traffic = None
     roofline = {
-        "kernel": "k_fit", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "kernel": "k_fit (fused first stage variant)" if fused_steps else "k_fit", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
         "bytes_per_elem": fit_bpe, "elems_per_launch": d, "avg_launch_us": round(fit_us, 2),
     }
@@ -211,14 +238,14 @@ def main():
         t_val = torch.empty(k, dtype=torch.float32, device=dev)
         t_cnt = torch.zeros(1, dtype=torch.int32, device=dev)
         t_kth = torch.zeros(1, dtype=torch.float32, device=dev)
-        t_res = torch.from_numpy(w.residual).to(dev) if ec else None
+        t_res = fresh_residuals()
         n_topk = max(1, min(args.steps, 100))
         for i in range(10):
-            sidco.sidco_topk(grads[i % nbuf], t_res, k, t_idx, t_val, t_cnt, t_kth, stream=stream)
+            sidco.sidco_topk(grads[i % nbuf], t_res[i % nres], k, t_idx, t_val, t_cnt, t_kth, stream=stream)
         torch.cuda.synchronize()
         tt = time.perf_counter()
         for i in range(n_topk):
-            sidco.sidco_topk(grads[(10 + i) % nbuf], t_res, k, t_idx, t_val, t_cnt, t_kth, stream=stream)
+            sidco.sidco_topk(grads[(10 + i) % nbuf], t_res[(10 + i) % nres], k, t_idx, t_val, t_cnt, t_kth, stream=stream)
         torch.cuda.synchronize()
         topk_ms = (time.perf_counter() - tt) * 1e3 / n_topk
         topk = {
@@ -240,14 +267,14 @@ def main():
         g_val = torch.empty(k, dtype=torch.float32, device=dev)
         g_cnt = torch.zeros(1, dtype=torch.int32, device=dev)
         g_eta = torch.zeros(1, dtype=torch.float32, device=dev)
-        g_res = torch.from_numpy(w.residual).to(dev) if ec else None
+        g_res = fresh_residuals()
         n_dgc = max(1, min(args.steps, 100))
         for i in range(10):
-            sidco.sidco_dgc(grads[i % nbuf], g_res, w.delta, rho, i, g_idx, g_val, g_cnt, g_eta, stream=stream)
+            sidco.sidco_dgc(grads[i % nbuf], g_res[i % nres], w.delta, rho, i, g_idx, g_val, g_cnt, g_eta, stream=stream)
         torch.cuda.synchronize()
         tt = time.perf_counter()
         for i in range(n_dgc):
-            sidco.sidco_dgc(grads[(10 + i) % nbuf], g_res, w.delta, rho, 10 + i, g_idx, g_val, g_cnt, g_eta,
+            sidco.sidco_dgc(grads[(10 + i) % nbuf], g_res[(10 + i) % nres], w.delta, rho, 10 + i, g_idx, g_val, g_cnt, g_eta,
                             stream=stream)
         torch.cuda.synchronize()
         dgc_ms = (time.perf_counter() - tt) * 1e3 / n_dgc
@@ -255,7 +282,7 @@ def main():
         sidco.sidco_set_profiling(True)
         dgc_kern: dict[str, list[float]] = {}
         for i in range(min(args.profile_steps, 20)):
-            sidco.sidco_dgc(grads[i % nbuf], g_res, w.delta, rho, 1000 + i, g_idx, g_val, g_cnt, g_eta, stream=stream)
+            sidco.sidco_dgc(grads[i % nbuf], g_res[i % nres], w.delta, rho, 1000 + i, g_idx, g_val, g_cnt, g_eta, stream=stream)
             for name, ms in sidco.sidco_get_profile():
                 dgc_kern.setdefault(name, []).append(ms)
             firsts.append(sidco.sidco_dgc_result(stream)[2] / k)
@@ -284,18 +311,19 @@ def main():
         b_val = torch.empty(o_offs[-1], dtype=torch.float32, device=dev)
         b_cnt = torch.zeros(nt, dtype=torch.int32, device=dev)
         b_eta = torch.zeros(nt, dtype=torch.float32, device=dev)
-        b_res = torch.from_numpy(w.residual).to(dev) if ec else None
+        b_res = fresh_residuals()
         n_b = max(1, min(args.steps, 100))
 
         def batched(i):
-            sidco.sidco_compress_batched(grads[i % nbuf], b_res, offs, w.delta, w.dist, w.stages, b_idx, b_val, o_offs,
+            sidco.sidco_compress_batched(grads[i % nbuf], b_res[i % nres], offs, w.delta, w.dist, w.stages, b_idx, b_val, o_offs,
                                          b_cnt, b_eta, stream=stream)
 
         def looped(i):
             g = grads[i % nbuf]
+            br = b_res[i % nres]
             for t in range(nt):
                 a, b = offs[t], offs[t + 1]
-                sidco.sidco_compress(g[a:b], None if b_res is None else b_res[a:b], w.delta, w.dist, w.stages,
+                sidco.sidco_compress(g[a:b], None if br is None else br[a:b], w.delta, w.dist, w.stages,
                                      b_idx[o_offs[t]:o_offs[t + 1]], b_val[o_offs[t]:o_offs[t + 1]], b_cnt[t:t + 1],
                                      b_eta[t:t + 1], stream=stream)
 
@@ -351,7 +379,7 @@ def main():
         "config": {
             "workload": f"{w.name}: d={d} {'fp32' if not typed else args.grad_dtype + ' gradient, fp32 residual'}, delta={w.delta}, dist={['exp', 'gamma-gpd', 'gpd'][w.dist]}, "
                         f"stages={w.stages}, delta1={w.delta1}, error_feedback={'on' if ec else 'off'}",
-            "gradient_buffers_in_rotation": nbuf, "khat_over_k": round(float(np.mean(khat)) / (w.delta * d), 4),
+            "gradient_buffers_in_rotation": nbuf, "residual_buffers_in_rotation": nres, "khat_over_k": round(float(np.mean(khat)) / (w.delta * d), 4),
         },
         "roofline": roofline, "path": path, "cpu_baseline": cpu_baseline, "topk_comparator": topk,
         "dgc_comparator": dgc, "per_tensor": per_tensor,

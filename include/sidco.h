@@ -296,7 +296,10 @@ int sidco_dgc_result(void *stream, int64_t *host_out);
  * Corollaries 1.2 and 1.3).  This is the kernel that dominates a call; it is
  * exported so that it can be timed and checked on its own.  On return of the
  * stream, residual holds acc = grad + residual.  The sums stay in the
- * workspace until the next call on the device.
+ * workspace until the next call on the device.  Right after a sidco_compress
+ * call of the same d and dist that took the fused first stage (see
+ * sidco_set_fusion) the kernel runs in that same variant, so that it can be
+ * timed as it runs inside a call; the sums are the same.
  */
 int sidco_fit(void *stream, const float *grad, float *residual, int64_t d, int dist);
 /* The same on a gradient of element type grad_dtype (SIDCO_GRAD_*), as in sidco_compress_typed. */

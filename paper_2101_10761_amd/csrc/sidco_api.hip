@@ -1116,6 +1116,25 @@ int sidco_fit_typed(void* stream, const void* grad, int grad_dtype, float* resid
     p.M = 1;
     p.acc_reset = 1;
     p.part_out = h->part[0];
+    // After a sidco_compress call of the same length and law that took the fused first stage, run the kernel
+    // in that same variant (it writes its lists into the workspace; the next call starts over anyway), so
+    // that the kernel can be timed as it runs inside a call.
+    DeviceCtx& c = *cp;
+    if (g_fusion && c.fused_primed && c.sig_d == d && c.sig_dist == dist && c.sig_M >= 2 && c.sig_theta > 0.0 &&
+        !fit_uses_flat(d, p.vec_ok != 0)) {
+        const size_t seg = seg_bytes(d);
+        p.M = c.sig_M;
+        for (int m = 0; m < c.sig_M; ++m) p.L[m] = log(1.0 / c.sig_ratios[m]);
+        p.use_hint = 1;
+        p.fused = 1;
+        p.theta = (float)c.sig_theta;
+        p.theta_min = hint_floor(1.0, p.L[0], p.L[1]);
+        p.band_out = (float*)((char*)c.ws + head_bytes());
+        p.band_cnt = h->cnt[0];
+        p.cand_out = (int2*)((char*)c.ws + head_bytes() + seg);
+        p.cand_cnt = h->cnt[1];
+        p.raw_out = h->part[1];
+    }
     launch_fit(p, (double*)((char*)cp->ws + head_bytes() + seg_bytes(d)), (hipStream_t)stream);
     cp->fit_nblocks = p.nblocks;
     cp->fit_d = d;

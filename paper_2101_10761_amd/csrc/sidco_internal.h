@@ -264,7 +264,7 @@ void launch_scatter_add(float* dense, int64_t d, const int32_t* idx, const float
                         int64_t capacity, float scale, uint32_t* bad, hipStream_t s);
 // k_fit's shape for large vectors (see k_fit_flat): one float4 per thread, 256-thread blocks
 constexpr int kFlatBlock = 256;
-constexpr int64_t kFlatMinD = 100000000;
+constexpr int64_t kFlatMinD = 12000000;
 inline bool fit_uses_flat(int64_t d, bool vec_ok) { return vec_ok && d >= kFlatMinD; }
 inline uint32_t fit_flat_blocks(int64_t d) { return (uint32_t)((d / 4 + kFlatBlock - 1) / kFlatBlock); }
 void launch_fit(const Params& p, double* scratch, hipStream_t s);
