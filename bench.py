@@ -36,13 +36,13 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def make_workload(name: str):
+def make_workload(name: str, d: int = 0):
     from paper_2101_10761_amd import workloads
     table = {
         "cfg1": workloads.config1, "cfg2": workloads.config2, "cfg3": workloads.config3,
         "cfg4": workloads.config4, "cfg5": workloads.config5,
     }
-    return table[name]()
+    return table[name](d) if d > 0 else table[name]()
 
 
 def algorithmic_bytes(d, ec, n_stage, khat, fit_bpe=None):
@@ -61,6 +61,7 @@ def main():
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--d", type=int, default=0, help="length of the vector, if not the workload's own (size sweeps)")
     ap.add_argument("--profile-steps", type=int, default=50, help="steps timed kernel by kernel with HIP events")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -69,8 +70,9 @@ def main():
     ap.add_argument("--residual-buffers", type=int, default=0,
                     help="carried residuals in rotation (0 = as many as gradient buffers; 1 = a single residual "
                          "that stays cache-resident between steps)")
-    ap.add_argument("--no-fusion", action="store_true",
-                    help="switch the fused first stage of repeated same-shape calls off (sidco_set_fusion)")
+    ap.add_argument("--fusion", action="store_true",
+                    help="switch the fused first stage of repeated same-shape calls on (sidco_set_fusion; it only "
+                         "pays with cache-resident operands, e.g. together with --residual-buffers 1)")
     ap.add_argument("--grad-dtype", choices=["f32", "f16", "bf16"], default="f32",
                     help="element type of the gradient buffer (the residual and all arithmetic stay fp32/fp64); "
                          "16-bit gradients use the default stage schedule (delta_1 = 0.25) and skip the comparators")
@@ -84,7 +86,7 @@ def main():
     import paper_2101_10761_amd as sidco
 
     sidco.load()  # fails loudly when the HIP library has not been built
-    sidco.sidco_set_fusion(not args.no_fusion)
+    sidco.sidco_set_fusion(args.fusion)
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         sys.exit(3)
@@ -92,7 +94,7 @@ def main():
     torch.cuda.set_device(dev)
 
     t0 = time.time()
-    w = make_workload(args.workload)
+    w = make_workload(args.workload, args.d)
     d = w.d
     log(f"workload {w.name}: d={d} delta={w.delta} dist={w.dist} stages={w.stages} delta1={w.delta1} "
         f"(generated in {time.time() - t0:.1f}s)")

@@ -347,14 +347,19 @@ int sidco_set_workspace(void *device_ptr, size_t bytes);
 int sidco_set_speculation(double theta);
 
 /*
- * Fused first stage (default on).  A call that repeats the previous call's
- * shape on the device lets its first pass do the first stage's work as well:
- * the statistics of the exceedances of eta_1 come from moments above, and the
- * entries inside, a narrow band around the previous call's eta_1, and the
- * candidate lists for stage 2 from the previous call's thresholds.  When this
- * call's eta_1 falls inside the band no second pass over the vector is needed
- * (SIDCO_ST_FUSED); otherwise the first stage reads the vector as usual
- * (SIDCO_ST_FALLBACK).  The result is the same either way.  0 switches it off.
+ * Fused first stage (default off; 1 switches it on).  A call that repeats the
+ * previous call's shape on the device lets its first pass do the first stage's
+ * work as well: the statistics of the exceedances of eta_1 come from moments
+ * above, and the entries inside, a narrow band around the previous call's
+ * eta_1, and the candidate lists for stage 2 from the previous call's
+ * thresholds.  When this call's eta_1 falls inside the band no second pass over
+ * the vector is needed (SIDCO_ST_FUSED); otherwise the first stage reads the
+ * vector as usual (SIDCO_ST_FALLBACK).  The result is the same either way.
+ * It pays when the vector and the residual stay cache-resident between calls
+ * (short vectors, back-to-back calls: -7 % at 25 M elements); with operands
+ * that come from HBM every call the longer first pass costs what the saved
+ * pass gains, so it is off unless asked for.  Vectors of 12 M elements and more,
+ * whose first pass runs as a flat grid without per-wave lists, never take it.
  */
 int sidco_set_fusion(int enable);
 

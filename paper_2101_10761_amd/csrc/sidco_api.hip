@@ -73,7 +73,7 @@ std::mutex g_mu;
 DeviceCtx g_ctx[kMaxDevices];
 bool g_profiling = false;
 double g_speculation = kSpeculation;
-bool g_fusion = true;
+bool g_fusion = false;
 thread_local char g_hip_msg[256] = "";
 
 int hip_fail(hipError_t e, const char* what)

@@ -23,7 +23,7 @@ def _fusion_on():
     sidco.sidco_set_fusion(True)
     sidco.sidco_set_speculation(0.5)
     yield
-    sidco.sidco_set_fusion(True)
+    sidco.sidco_set_fusion(False)             # the library's default
 
 
 def _reset_shape():
