@@ -67,6 +67,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-topk", action="store_true", help="skip the exact Top-k comparator leg")
     ap.add_argument("--no-dgc", action="store_true", help="skip the DGC comparator leg")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the plain-kernel streaming ceiling leg")
     ap.add_argument("--residual-buffers", type=int, default=0,
                     help="carried residuals in rotation (0 = as many as gradient buffers; 1 = a single residual "
                          "that stays cache-resident between steps)")
@@ -231,6 +232,29 @@ def main():
         "kernels_us": {k: round(kern_us[k], 2) for k in order},
     }
 
+    # What this machine streams with nothing of ours in the way: torch's own in-place add (two reads and one
+    # write per element, the traffic of k_fit) and device copy (one read, one write) over the same rotating
+    # buffers.  The first pass cannot be faster than the first of these.
+    ceiling = None
+    if ec and not typed and not args.no_ceiling:
+        scratch = fresh_residuals()
+        ceiling = {}
+        for name, bpe, fn in (("add_inplace_2r1w", 12, lambda i: scratch[i % nres].add_(grads[i % nbuf])),
+                              ("copy_1r1w", 8, lambda i: scratch[i % nres].copy_(grads[i % nbuf]))):
+            for i in range(8):
+                fn(i)
+            torch.cuda.synchronize()
+            ev_a.record(stream)
+            for i in range(48):
+                fn(8 + i)
+            ev_b.record(stream)
+            ev_b.synchronize()
+            us = ev_a.elapsed_time(ev_b) / 48 * 1e3
+            ceiling[name] = {"us": round(us, 2), "GBps": round(bpe * d / (us * 1e-6) / 1e9, 1),
+                             "frac_of_peak": round(bpe * d / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)}
+        del scratch
+        log(f"streaming ceiling (torch kernels, same buffers): {ceiling}")
+
     # Comparator: exact Top-k (radix select) with k = ceil(delta d) on the same gradients, same buffer rotation,
     # own carried residual (the paper's micro-benchmarks normalise every compressor by Top-k's time)
     topk = None
@@ -383,7 +407,8 @@ def main():
                         f"stages={w.stages}, delta1={w.delta1}, error_feedback={'on' if ec else 'off'}",
             "gradient_buffers_in_rotation": nbuf, "residual_buffers_in_rotation": nres, "khat_over_k": round(float(np.mean(khat)) / (w.delta * d), 4),
         },
-        "roofline": roofline, "path": path, "cpu_baseline": cpu_baseline, "topk_comparator": topk,
+        "roofline": roofline, "path": path, "streaming_ceiling": ceiling, "cpu_baseline": cpu_baseline,
+        "topk_comparator": topk,
         "dgc_comparator": dgc, "per_tensor": per_tensor,
         "paper_context": "the paper prints no absolute compression rate in text (its figures are the only source); it "
                          "states that on a V100 (PyTorch 1.1, CUDA 10.2) every threshold estimator is far faster than "
