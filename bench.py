@@ -220,7 +220,8 @@ def main():
         except Exception:
             traffic = None
     roofline = {
-        "kernel": "k_fit (fused first stage variant)" if fused_steps else "k_fit", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "kernel": ("k_fit (fused first stage variant)" if fused_steps else
+                   "k_fit (first pass; from 12 M elements k_fit_flat + k_fit_reduce)"), "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
         "bytes_per_elem": fit_bpe, "elems_per_launch": d, "avg_launch_us": round(fit_us, 2),
     }
