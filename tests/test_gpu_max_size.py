@@ -1,0 +1,123 @@
+"""The largest vector the boundary accepts, d = 2^31 - 1 (a ragged length: d mod 4 = 3, d mod 256 = 255).
+
+The C oracle would need minutes and tens of GB of host memory here, so this case is checked through
+properties that hold at any size, evaluated with plain torch operations on the device: the accumulated vector
+is the fp32 sum, every threshold matches the closed form on fp64 moments of that vector, the selected set is
+exactly {|acc| > eta_M}, the values are acc's, and the residual is acc with zeros at the selected positions."""
+import math
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+D_MAX = 2 ** 31 - 1
+CHUNK = 1 << 27
+
+
+def _chunks(n):
+    for a in range(0, n, CHUNK):
+        yield a, min(n, a + CHUNK)
+
+
+def _make(torch, dev, seed, scale):
+    """Laplace-like values, generated chunk by chunk on the device."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    out = torch.empty(D_MAX, dtype=torch.float32, device=dev)
+    for a, b in _chunks(D_MAX):
+        u = torch.empty(b - a, dtype=torch.float32, device=dev).uniform_(-0.5, 0.5, generator=gen)
+        sign = torch.sign(u)
+        out[a:b] = -scale * sign * torch.log1p(-2.0 * u.abs()).clamp_(min=-80.0)
+    return out
+
+
+def _moments_above(torch, acc, eta):
+    """n, sum(|x| - eta), sum((|x| - eta)^2) over |x| > eta in fp64, chunk by chunk (eta = None: over everything)."""
+    n, s1, s2 = 0, 0.0, 0.0
+    for a, b in _chunks(acc.numel()):
+        m = acc[a:b].abs()
+        if eta is not None:
+            m = m[m > eta]
+            y = m.double() - float(eta)
+        else:
+            y = m.double()
+        n += y.numel()
+        s1 += float(y.sum())
+        s2 += float((y * y).sum())
+    return n, s1, s2
+
+
+def test_exponential_two_stages_with_error_feedback_at_the_maximum_length():
+    import torch
+    import paper_2101_10761_amd as sidco
+
+    dev = torch.device("cuda:0")
+    g = _make(torch, dev, 1, 1e-3)
+    r = _make(torch, dev, 2, 2e-4)
+    acc = torch.empty_like(g)
+    for a, b in _chunks(D_MAX):
+        acc[a:b] = g[a:b] + r[a:b]
+    delta, stages = 0.0005, 2
+    ratios = sidco.sidco_stage_ratios(delta, stages)
+    cap = sidco.sidco_out_capacity(D_MAX, delta)
+    out_idx = torch.full((cap + 64,), -7, dtype=torch.int32, device=dev)
+    out_val = torch.full((cap + 64,), 7.0, dtype=torch.float32, device=dev)
+    out_count = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    out_eta = torch.full((1,), -1.0, dtype=torch.float32, device=dev)
+    print("compress at d = 2^31 - 1", flush=True)
+    sidco.sidco_compress(g, r, delta, sidco.DIST_EXP, stages, out_idx[:cap], out_val[:cap], out_count, out_eta)
+    diag = sidco.sidco_read_diag()
+    torch.cuda.synchronize()
+    assert diag.status & ~(sidco.ST_FALLBACK | sidco.ST_FUSED) == 0
+    k = int(out_count.item())
+    eta = float(out_eta.item())
+
+    # thresholds: eq. (6) on the mean of |acc|, then Corollary 2 on the exceedances of the GPU's own eta_1
+    n1, s1, _ = _moments_above(torch, acc, None)
+    assert n1 == D_MAX == diag.n[0]
+    eta1_ref = (s1 / n1) * math.log(1.0 / ratios[0])
+    assert abs(diag.eta[0] - eta1_ref) <= 1e-5 * eta1_ref
+    n2, y1, _ = _moments_above(torch, acc, diag.eta[0])
+    assert n2 == diag.n[1]
+    eta2_ref = diag.eta[0] + (y1 / n2) * math.log(1.0 / ratios[1])
+    assert abs(diag.eta[1] - eta2_ref) <= 1e-5 * eta2_ref
+    assert eta == diag.eta[1]
+
+    # selection: exactly the entries above eta_M, with acc's values, nothing written past the count
+    want = torch.cat([torch.nonzero(acc[a:b].abs() > eta).flatten() + a for a, b in _chunks(D_MAX)])
+    assert want.numel() == k == diag.selected and 0 < k <= cap
+    got, order = torch.sort(out_idx[:k].long())
+    assert torch.equal(got, want)
+    assert torch.equal(out_val[:k][order], acc[want])
+    assert torch.all(out_idx[k:] == -7) and torch.all(out_val[k:] == 7.0)
+    assert int(want[-1]) > 2 ** 31 - 1 - 10_000_000      # entries from the very end of the vector are among them
+    # residual: acc with zeros at the selected positions
+    acc[want] = 0.0
+    for a, b in _chunks(D_MAX):
+        assert torch.equal(r[a:b], acc[a:b])
+
+
+def test_exact_topk_at_the_maximum_length():
+    import torch
+    import paper_2101_10761_amd as sidco
+
+    dev = torch.device("cuda:0")
+    g = _make(torch, dev, 3, 1e-3)
+    k = 1_000_003
+    out_idx = torch.full((k + 64,), -7, dtype=torch.int32, device=dev)
+    out_val = torch.full((k + 64,), 7.0, dtype=torch.float32, device=dev)
+    out_count = torch.full((1,), -1, dtype=torch.int32, device=dev)
+    out_kth = torch.full((1,), -1.0, dtype=torch.float32, device=dev)
+    print("top-k at d = 2^31 - 1", flush=True)
+    sidco.sidco_topk(g, None, k, out_idx[:k], out_val[:k], out_count, out_kth)
+    torch.cuda.synchronize()
+    kth = float(out_kth.item())
+    assert int(out_count.item()) == k
+    n_gt = sum(int((g[a:b].abs() > kth).sum()) for a, b in _chunks(D_MAX))
+    n_ge = sum(int((g[a:b].abs() >= kth).sum()) for a, b in _chunks(D_MAX))
+    assert n_gt < k <= n_ge                              # kth is the k-th largest magnitude
+    idx = out_idx[:k].long()
+    assert torch.unique(idx).numel() == k and int(idx.min()) >= 0 and int(idx.max()) < D_MAX
+    assert torch.equal(out_val[:k], g[idx])
+    assert int((out_val[:k].abs() > kth).sum()) == n_gt and torch.all(out_val[:k].abs() >= kth)
+    assert torch.all(out_idx[k:] == -7)
