@@ -4,6 +4,11 @@
 //
 //   k_fit        acc = g + residual, stored back to residual; per-block fp64 partial sums of
 //                |acc|, acc^2, log2|acc| (whichever the chosen law needs)       [reads 8 B, writes 4 B / element]
+//                Two launch shapes: every wave walks its own contiguous range (short vectors), or
+//                k_fit_flat, one float4 per thread in address order, followed by k_fit_reduce, which
+//                folds the per-block sums into the 512 slots the next kernel expects (long vectors,
+//                whose operands come from HBM: that shape streams 15 % faster there).
+//                The gradient may be fp16 / bf16; it is widened as it is read.
 //   k_compact<m> m = 1..M.  Prologue: every block reduces the previous kernel's partial sums in a
 //                fixed order and evaluates the closed-form threshold eta_m in fp64 (identical bits
 //                in every block).  Body: exceedances {|x| > eta_m} of the source (the dense acc
@@ -589,8 +594,11 @@ __device__ __forceinline__ void fit_body(const Params& p, Blk b)
 // ---------------------------------------------------------------------------------------------
 // k_fit_flat + k_fit_reduce: the same pass for large vectors.  One float4 per thread and a grid that
 // covers the vector in address order: the blocks in flight at any time touch one narrow window of each
-// buffer, which DRAM serves better than the 3 x 4096 separate streams of the per-wave ranges once
-// those ranges are long (measured inside a call at d = 138 M: 303 us against 354 us; no gain at 66 M, a loss at 25 M).
+// buffer, which DRAM serves better than the 3 x 4096 separate streams of the per-wave ranges when
+// the operands come from HBM (measured with a gradient and a residual that no cache holds: 52.9 us
+// against 62.5 us at d = 25.6 M, 129 us against 156 us at 66 M, i.e. what a plain in-place add reaches;
+// with a residual that is still in the memory-side cache from the previous call the per-wave shape is
+// the faster one up to 66 M, but no training loop leaves it there).
 // The price is one partial sum per 256-thread block - far too many for every block of the next
 // kernel to add up - so a second, small kernel folds them into the usual 512 slots, in a fixed order.
 // ---------------------------------------------------------------------------------------------
