@@ -147,3 +147,16 @@ def test_f32_code_is_the_plain_call(oracle):
     res = run_typed(torch.from_numpy(g32), None, 2, 0.01, 2)
     check_parity(oracle, g32, None, 2, sidco.sidco_stage_ratios(0.01, 2), res,
                  capacity=sidco.sidco_out_capacity(d, 0.01), label="f32 through the typed entry point")
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_long_vector_without_residual(oracle, kind):
+    """From 12 M elements the first pass runs as a flat grid; without a residual the widened vector lives in the
+    library's workspace."""
+    import paper_2101_10761_amd as sidco
+    d = 12_500_003
+    g32, _ = _grad(123, d)
+    g16, gw = narrow(g32, kind)
+    res = run_typed(g16, None, 2, 0.001, 3, grad_offset=4)
+    check_parity(oracle, gw, None, 2, sidco.sidco_stage_ratios(0.001, 3), res,
+                 capacity=sidco.sidco_out_capacity(d, 0.001), label=f"{kind} d {d} memoryless")
