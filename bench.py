@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--no-topk", action="store_true", help="skip the exact Top-k comparator leg")
     ap.add_argument("--no-dgc", action="store_true", help="skip the DGC comparator leg")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the plain-kernel streaming ceiling leg")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the steps replayed from HIP graphs (one per buffer pair)")
     ap.add_argument("--residual-buffers", type=int, default=0,
                     help="carried residuals in rotation (0 = as many as gradient buffers; 1 = a single residual "
                          "that stays cache-resident between steps)")
@@ -232,6 +234,40 @@ def main():
         "frac": round(path_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "kernels_us": {k: round(kern_us[k], 2) for k in order},
     }
+
+    # The same steps replayed from HIP graphs (one graph per buffer pair, captured through torch): what a
+    # launch-bound loop gains when the host only issues one graph launch per step.
+    graph_leg = None
+    if args.graph:
+        pairs = nbuf if nres == nbuf else 1
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        graphs = []
+        with torch.cuda.stream(side):
+            for i in range(max(pairs, nbuf)):
+                gph = torch.cuda.CUDAGraph()
+                gph.capture_begin()
+                if typed:
+                    sidco.sidco_compress_typed(grads[i % nbuf], residuals[i % nres], w.delta, w.dist, w.stages, out_idx,
+                                               out_val, out_count, out_eta, stream=side)
+                else:
+                    sidco.sidco_compress_ex(grads[i % nbuf], residuals[i % nres], w.dist, ratios, out_idx, out_val,
+                                            out_count, out_eta, stream=side)
+                gph.capture_end()
+                graphs.append(gph)
+        stream.wait_stream(side)
+        torch.cuda.synchronize()
+        for i in range(args.warmup):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for i in range(args.steps):
+            graphs[(args.warmup + i) % len(graphs)].replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - tg) * 1e3 / args.steps
+        graph_leg = {"ms_per_step": round(g_ms, 5), "value": round(d / (g_ms * 1e-3) / 1e9, 2), "unit": "G elem/s",
+                     "graphs": len(graphs), "eager_ms_per_step": round(ms_per_step, 5)}
+        log(f"graph replay: {g_ms * 1e3:.1f} us/step ({graph_leg['value']} G elem/s) against {ms_per_step * 1e3:.1f} us eager")
 
     # What this machine streams with nothing of ours in the way: torch's own in-place add (two reads and one
     # write per element, the traffic of k_fit) and device copy (one read, one write) over the same rotating
@@ -408,7 +444,8 @@ def main():
                         f"stages={w.stages}, delta1={w.delta1}, error_feedback={'on' if ec else 'off'}",
             "gradient_buffers_in_rotation": nbuf, "residual_buffers_in_rotation": nres, "khat_over_k": round(float(np.mean(khat)) / (w.delta * d), 4),
         },
-        "roofline": roofline, "path": path, "streaming_ceiling": ceiling, "cpu_baseline": cpu_baseline,
+        "roofline": roofline, "path": path, "streaming_ceiling": ceiling, "graph_replay": graph_leg,
+        "cpu_baseline": cpu_baseline,
         "topk_comparator": topk,
         "dgc_comparator": dgc, "per_tensor": per_tensor,
         "paper_context": "the paper prints no absolute compression rate in text (its figures are the only source); it "
