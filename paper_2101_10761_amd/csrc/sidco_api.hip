@@ -85,16 +85,17 @@ int hip_fail(hipError_t e, const char* what)
 bool aligned4(const void* p) { return ((uintptr_t)p & 3u) == 0; }
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
-int check_common(const float* grad, const float* residual, int64_t d, int dist, const int32_t* out_idx,
-                 const float* out_val, const int32_t* out_count, const float* out_eta)
+// `grad_align`: alignment the gradient's element type needs (4 for fp32, 2 for the 16-bit types)
+int check_common(const void* grad, const float* residual, int64_t d, int dist, const int32_t* out_idx,
+                 const float* out_val, const int32_t* out_count, const float* out_eta, uintptr_t grad_align = 4)
 {
     if (!grad || !out_idx || !out_val || !out_count || !out_eta) return SIDCO_ERR_NULL;
     if (d < 1 || d > (int64_t)INT32_MAX) return SIDCO_ERR_SIZE;
     if (dist != SIDCO_DIST_EXP && dist != SIDCO_DIST_GAMMA_GPD && dist != SIDCO_DIST_GPD) return SIDCO_ERR_DIST;
-    if (!aligned4(grad) || !aligned4(residual) || !aligned4(out_idx) || !aligned4(out_val) || !aligned4(out_count) ||
-        !aligned4(out_eta))
+    if (((uintptr_t)grad & (grad_align - 1)) != 0 || !aligned4(residual) || !aligned4(out_idx) || !aligned4(out_val) ||
+        !aligned4(out_count) || !aligned4(out_eta))
         return SIDCO_ERR_ALIGN;
-    if (residual && (const void*)residual == (const void*)grad) return SIDCO_ERR_ARG;
+    if (residual && (const void*)residual == grad) return SIDCO_ERR_ARG;
     return SIDCO_OK;
 }
 
@@ -460,11 +461,8 @@ int sidco_compress_typed(void* stream, const void* grad, int grad_dtype, float* 
         return sidco_compress(stream, (const float*)grad, residual, d, delta, dist, stages, out_idx, out_val, out_count,
                               out_eta);
     if (grad_dtype != SIDCO_GRAD_F16 && grad_dtype != SIDCO_GRAD_BF16) return SIDCO_ERR_ARG;
-    // the common checks want a 4-byte aligned gradient: hand them a stand-in and check the 2-byte alignment here
-    int rc = check_common(grad ? (const float*)out_val : nullptr, residual, d, dist, out_idx, out_val, out_count, out_eta);
+    int rc = check_common(grad, residual, d, dist, out_idx, out_val, out_count, out_eta, 2);
     if (rc != SIDCO_OK) return rc;
-    if (((uintptr_t)grad & 1u) != 0) return SIDCO_ERR_ALIGN;
-    if (residual && (const void*)residual == grad) return SIDCO_ERR_ARG;
     if (!(delta > 0.0 && delta < 1.0)) return SIDCO_ERR_DELTA;
     if (stages < 1 || stages > SIDCO_MAX_STAGES) return SIDCO_ERR_STAGES;
     double ratios[SIDCO_MAX_STAGES];
