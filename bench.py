@@ -73,9 +73,6 @@ def main():
     ap.add_argument("--residual-buffers", type=int, default=0,
                     help="carried residuals in rotation (0 = as many as gradient buffers; 1 = a single residual "
                          "that stays cache-resident between steps)")
-    ap.add_argument("--fusion", action="store_true",
-                    help="switch the fused first stage of repeated same-shape calls on (sidco_set_fusion; it only "
-                         "pays with cache-resident operands, e.g. together with --residual-buffers 1)")
     ap.add_argument("--grad-dtype", choices=["f32", "f16", "bf16"], default="f32",
                     help="element type of the gradient buffer (the residual and all arithmetic stay fp32/fp64); "
                          "16-bit gradients use the default stage schedule (delta_1 = 0.25) and skip the comparators")
@@ -89,7 +86,6 @@ def main():
     import paper_2101_10761_amd as sidco
 
     sidco.load()  # fails loudly when the HIP library has not been built
-    sidco.sidco_set_fusion(args.fusion)
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         sys.exit(3)
@@ -185,11 +181,9 @@ def main():
 
     # Dominant kernel on its own: batches of back-to-back k_fit launches (sidco_fit) between two HIP
     # events on the same stream, so that the events' own dispatch latency (several microseconds, which
-    # the in-sequence figures above include) is spread over the batch.  After steps that took the fused
-    # first stage, sidco_fit runs that same variant of the kernel.  Every launch of a batch gets its own
+    # the in-sequence figures above include) is spread over the batch.  Every launch of a batch gets its own
     # copy of the carried residual (restored, untimed, before each batch), so that each one sees the
     # values of a real step rather than a residual that has already absorbed the gradient several times.
-    fused_steps = bool(diag.status & sidco.ST_FUSED)
     batch, fit_ms = 20, []
     ev_a, ev_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     n_done = args.warmup + args.steps + args.profile_steps
@@ -211,7 +205,7 @@ def main():
     fit_bpe = gbytes + (8 if ec else (4 if typed else 0))   # read g [, read r], write acc unless acc is g itself
     fit_bytes = fit_bpe * d
     fit_us = float(np.mean(fit_ms)) * 1e3
-    log(f"k_fit alone{' (fused first stage)' if fused_steps else ''}: {fit_us:.1f} us per launch "
+    log(f"k_fit alone: {fit_us:.1f} us per launch "
         f"(HIP events around batches of {batch})")
     achieved = fit_bytes / (fit_us * 1e-6) / 1e9
     traffic = None
@@ -222,8 +216,7 @@ def main():
         except Exception:
             traffic = None
     roofline = {
-        "kernel": ("k_fit (fused first stage variant)" if fused_steps else
-                   "k_fit (first pass; from 12 M elements k_fit_flat + k_fit_reduce)"), "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "kernel": "k_fit (first pass; from 12 M elements k_fit_flat + k_fit_reduce)", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
         "bytes_per_elem": fit_bpe, "elems_per_launch": d, "avg_launch_us": round(fit_us, 2),
     }

@@ -73,11 +73,6 @@ extern "C" {
                                            dense vector again (see sidco_set_speculation); the result
                                            is the same either way                                     */
 
-#define SIDCO_ST_FUSED        (1u << 7) /* performance only: the first pass also did the first stage's
-                                           work (statistics above eta_1, candidate lists) from the
-                                           previous call's thresholds, so no second pass over the
-                                           vector was needed (see sidco_set_fusion)                   */
-
 /* Per-call diagnostics, filled on the device by the kernels of the last call. */
 typedef struct sidco_diag {
     float    eta[SIDCO_MAX_STAGES];      /* eta_m, fp32, m = 1..M (Lemma 2: absolute thresholds)      */
@@ -296,10 +291,7 @@ int sidco_dgc_result(void *stream, int64_t *host_out);
  * Corollaries 1.2 and 1.3).  This is the kernel that dominates a call; it is
  * exported so that it can be timed and checked on its own.  On return of the
  * stream, residual holds acc = grad + residual.  The sums stay in the
- * workspace until the next call on the device.  Right after a sidco_compress
- * call of the same d and dist that took the fused first stage (see
- * sidco_set_fusion) the kernel runs in that same variant, so that it can be
- * timed as it runs inside a call; the sums are the same.
+ * workspace until the next call on the device.
  */
 int sidco_fit(void *stream, const float *grad, float *residual, int64_t d, int dist);
 /* The same on a gradient of element type grad_dtype (SIDCO_GRAD_*), as in sidco_compress_typed. */
@@ -345,23 +337,6 @@ int sidco_set_workspace(void *device_ptr, size_t bytes);
  * to the calls that follow, on every device.
  */
 int sidco_set_speculation(double theta);
-
-/*
- * Fused first stage (default off; 1 switches it on).  A call that repeats the
- * previous call's shape on the device lets its first pass do the first stage's
- * work as well: the statistics of the exceedances of eta_1 come from moments
- * above, and the entries inside, a narrow band around the previous call's
- * eta_1, and the candidate lists for stage 2 from the previous call's
- * thresholds.  When this call's eta_1 falls inside the band no second pass over
- * the vector is needed (SIDCO_ST_FUSED); otherwise the first stage reads the
- * vector as usual (SIDCO_ST_FALLBACK).  The result is the same either way.
- * It pays when the vector and the residual stay cache-resident between calls
- * (short vectors, back-to-back calls: -7 % at 25 M elements); with operands
- * that come from HBM every call the longer first pass costs what the saved
- * pass gains, so it is off unless asked for.  Vectors of 12 M elements and more,
- * whose first pass runs as a flat grid without per-wave lists, never take it.
- */
-int sidco_set_fusion(int enable);
 
 /* Copy the diagnostics of the last call on the current device to host memory.
  * Synchronises `stream`.                                                      */

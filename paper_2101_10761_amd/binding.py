@@ -15,7 +15,6 @@ LIB_PATH = os.path.join(HERE, "libsidco.so")
 MAX_STAGES = 8
 DIST_EXP, DIST_GAMMA_GPD, DIST_GPD = 0, 1, 2
 ST_NONFINITE, ST_VAR_ZERO, ST_GAMMA_S, ST_GAMMA_CLAMP, ST_STOPPED, ST_OVERFLOW, ST_FALLBACK = 1, 2, 4, 8, 16, 32, 64
-ST_FUSED = 128
 
 EXPORTS = [
     "sidco_compress", "sidco_compress_typed", "sidco_workspace_bytes_typed", "sidco_compress_ex", "sidco_compress_batched", "sidco_batched_out_offsets",
@@ -23,7 +22,7 @@ EXPORTS = [
     "sidco_controller_destroy", "sidco_controller_stages", "sidco_controller_iteration",
     "sidco_controller_last_average", "sidco_controller_compress", "sidco_scatter_add", "sidco_scatter_check",
     "sidco_fit", "sidco_fit_typed", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
-    "sidco_workspace_bytes", "sidco_set_workspace", "sidco_set_speculation", "sidco_set_fusion", "sidco_read_diag", "sidco_set_profiling",
+    "sidco_workspace_bytes", "sidco_set_workspace", "sidco_set_speculation", "sidco_read_diag", "sidco_set_profiling",
     "sidco_get_profile", "sidco_strerror", "sidco_last_hip_error", "sidco_version", "sidco_shutdown",
 ]
 
@@ -136,8 +135,6 @@ def load() -> C.CDLL:
     lib.sidco_set_workspace.restype = C.c_int
     lib.sidco_set_speculation.argtypes = [C.c_double]
     lib.sidco_set_speculation.restype = C.c_int
-    lib.sidco_set_fusion.argtypes = [C.c_int]
-    lib.sidco_set_fusion.restype = C.c_int
     lib.sidco_read_diag.argtypes = [vp, C.POINTER(Diag)]
     lib.sidco_read_diag.restype = C.c_int
     lib.sidco_set_profiling.argtypes = [C.c_int]
@@ -448,11 +445,6 @@ def sidco_fit_result(stream=None) -> tuple[float, float, float, float]:
 def sidco_set_speculation(theta: float) -> None:
     """Position of a dense stage's candidate threshold (0 = lists of all exceedances); see include/sidco.h."""
     _check(load().sidco_set_speculation(float(theta)), "sidco_set_speculation")
-
-
-def sidco_set_fusion(enable: bool) -> None:
-    """Switches the fused first stage of repeated same-shape calls on or off; see include/sidco.h."""
-    _check(load().sidco_set_fusion(1 if enable else 0), "sidco_set_fusion")
 
 
 def sidco_read_diag(stream=None) -> Diag:

@@ -49,7 +49,6 @@ struct DeviceCtx {
     int prof_n = 0;            // kernels of the last profiled call
     const char* prof_name[kMaxKernels] = {};
     int64_t dgc_n_s = 0, dgc_k_s = 0;  // sizes of the last sidco_dgc call
-    bool fused_primed = false;         // the previous call of this shape ran with the fused first stage
     bool bad_cleared = false;  // the scatter kernels' bad-index flag has been initialised in this workspace
     int64_t last_cap = 0;      // output capacity of the last compress call
     // shape of the last compress call: a call that repeats it may use the device's record of where the
@@ -73,7 +72,6 @@ std::mutex g_mu;
 DeviceCtx g_ctx[kMaxDevices];
 bool g_profiling = false;
 double g_speculation = kSpeculation;
-bool g_fusion = false;
 thread_local char g_hip_msg[256] = "";
 
 int hip_fail(hipError_t e, const char* what)
@@ -244,27 +242,6 @@ int run(void* stream, const void* grad, float* residual, int64_t d, int dist, co
     c.sig_theta = theta;
     for (int m = 0; m < M; ++m) c.sig_ratios[m] = ratios[m];
     p.use_hint = same_shape ? 1 : 0;
-    // Fused first stage: k_fit also prepares what the first stage's kernel needs, from the previous call's
-    // thresholds.  Only for a call that repeats the previous call's shape and whose first stage writes
-    // candidate lists; not in the large-vector launch shape of k_fit, which has no per-wave lists.
-    bool fused = false;
-    if (g_fusion && same_shape && M >= 2 && theta > 0.0 && !fit_uses_flat(d, p.vec_ok != 0))
-        fused = exp(-(p.L[0] + theta * p.L[1])) <= kMaterializeBelow;
-    p.fused = fused ? 1 : 0;
-    p.fused_first = (fused && !c.fused_primed) ? 1 : 0;
-    c.fused_primed = fused;
-    if (fused) {
-        // the candidate threshold's rule needs the first stage's theta range before the first kernel
-        p.theta = (float)theta;
-        p.theta_min = hint_floor(1.0, p.L[0], p.L[1]);
-        // where the first stage's kernel (buffers: in = 0, out = 1) expects each piece
-        p.band_out = (float*)segbuf[0];
-        p.band_cnt = h->cnt[0];
-        p.cand_out = segbuf[1];
-        p.cand_cnt = h->cnt[1];
-        p.raw_out = h->part[1];
-    }
-
     const bool prof = g_profiling;
     if (prof) {
         rc = make_events(c);
@@ -1114,25 +1091,6 @@ int sidco_fit_typed(void* stream, const void* grad, int grad_dtype, float* resid
     p.M = 1;
     p.acc_reset = 1;
     p.part_out = h->part[0];
-    // After a sidco_compress call of the same length and law that took the fused first stage, run the kernel
-    // in that same variant (it writes its lists into the workspace; the next call starts over anyway), so
-    // that the kernel can be timed as it runs inside a call.
-    DeviceCtx& c = *cp;
-    if (g_fusion && c.fused_primed && c.sig_d == d && c.sig_dist == dist && c.sig_M >= 2 && c.sig_theta > 0.0 &&
-        !fit_uses_flat(d, p.vec_ok != 0)) {
-        const size_t seg = seg_bytes(d);
-        p.M = c.sig_M;
-        for (int m = 0; m < c.sig_M; ++m) p.L[m] = log(1.0 / c.sig_ratios[m]);
-        p.use_hint = 1;
-        p.fused = 1;
-        p.theta = (float)c.sig_theta;
-        p.theta_min = hint_floor(1.0, p.L[0], p.L[1]);
-        p.band_out = (float*)((char*)c.ws + head_bytes());
-        p.band_cnt = h->cnt[0];
-        p.cand_out = (int2*)((char*)c.ws + head_bytes() + seg);
-        p.cand_cnt = h->cnt[1];
-        p.raw_out = h->part[1];
-    }
     launch_fit(p, (double*)((char*)cp->ws + head_bytes() + seg_bytes(d)), (hipStream_t)stream);
     cp->fit_nblocks = p.nblocks;
     cp->fit_d = d;
@@ -1196,13 +1154,6 @@ int sidco_set_speculation(double theta)
     if (!(theta >= 0.0 && theta <= 1.0)) return SIDCO_ERR_ARG;
     std::lock_guard<std::mutex> lock(g_mu);
     g_speculation = theta;
-    return SIDCO_OK;
-}
-
-int sidco_set_fusion(int enable)
-{
-    std::lock_guard<std::mutex> lock(g_mu);
-    g_fusion = enable != 0;
     return SIDCO_OK;
 }
 

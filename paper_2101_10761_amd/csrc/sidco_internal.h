@@ -43,10 +43,6 @@ constexpr uint32_t kStGammaClamp = SIDCO_ST_GAMMA_CLAMP;
 constexpr uint32_t kStStopped = SIDCO_ST_STOPPED;
 constexpr uint32_t kStOverflow = SIDCO_ST_OVERFLOW;
 constexpr uint32_t kStFallback = SIDCO_ST_FALLBACK;
-constexpr uint32_t kStFused = SIDCO_ST_FUSED;
-// Fused first stage (see k_fit): half-width of the band around the previous call's eta_1, relative to
-// it - the first value, and the limits of what the device adapts it to from call to call.
-constexpr float kBandFirst = 0.02f, kBandMin = 0.003f, kBandMax = 0.08f;
 
 // A fitted law as the kernels use it (see Fit in the kernel source), with the location it sits on.
 struct FitRecord {
@@ -68,11 +64,6 @@ struct DevState {
     float theta_seen[SIDCO_MAX_STAGES + 1];
     // Adapt_Stages bookkeeping (Algorithm 1): pairs reported by the calls since the controller last
     // looked, not counting the call in flight; k_fit folds the previous call's count in (or starts over)
-    // Fused first stage: what k_fit of the call in flight prepared for the first stage's kernel.
-    uint32_t fused_on;        // 1: band lists, moments above the band and candidate lists are there
-    float band_lo, band_hi;   // the band: eta_1 of the previous call, less and plus band_rel of it
-    float fused_eta_w;        // the candidate lists hold every entry above this
-    float band_rel;           // survives from call to call: relative half-width of the band
     unsigned long long khat_sum;
     long long prev_cap;                           // output capacity of the previous call (clips its count)
     unsigned long long selected_ctr;              // pairs selected by the last stage (cleared by k_fit)
@@ -106,13 +97,6 @@ struct Params {
     float theta;            // > 0: the lists of this kernel are candidate lists (see stage_prologue); else 0
     float theta_min;        // lowest theta a hint may lead to: below it the lists would exceed kMaterializeBelow
     int use_hint;           // the previous call on the device had this call's shape: theta_seen applies
-    int fused;              // k_fit may do the first stage's work as well, from the previous call's thresholds
-    int fused_first;        // ... for the first time with this shape: the band starts at its default width
-    float* band_out;        // fused first stage, written by k_fit: per-wave lists of the magnitudes in the band,
-    uint32_t* band_cnt;     //   their lengths,
-    int2* cand_out;         //   per-wave candidate lists,
-    uint32_t* cand_cnt;     //   their lengths,
-    double* raw_out;        //   and per-block sum |x|, sum x^2 and count of the entries above the band
     int prev_cand;          // the producer of this kernel's source lists wrote candidate lists
     DevState* st;
     const double* part_in;  // [4][kMaxBlocks] partial sums written by the previous kernel

@@ -277,17 +277,6 @@ __device__ StageEta stage_prologue(const Params& p, Blk b, bool auto_src, double
     r.lists_ok = auto_src && (r.eta >= list_eta);  // false for a NaN threshold, which selects nothing anyway
     if (auto_src && !r.lists_ok) status |= kStFallback;
     if (b.id == 0 && t == 0) {
-        if (m == 1 && p.fused) {
-            // width of the next call's band: four times the relative change of eta_1 just seen, shrinking
-            // by at most 30 % per call, within [kBandMin, kBandMax]
-            const float old = p.st->diag.eta[0];
-            float rel = p.fused_first ? kBandFirst : p.st->band_rel;
-            if (!(rel >= kBandMin && rel <= kBandMax)) rel = kBandFirst;
-            const float change = fabsf(r.eta - old) / old;
-            float next = fmaxf(4.0f * change + kBandMin, 0.7f * rel);
-            if (!(next == next)) next = kBandFirst;
-            p.st->band_rel = fminf(fmaxf(next, kBandMin), kBandMax);
-        }
         p.st->diag.eta[m - 1] = r.eta;
         p.st->diag.n[m - 1] = (int64_t)n;
         p.st->diag.stats[m - 1][0] = stats[0];
@@ -338,81 +327,12 @@ __device__ __forceinline__ void fit_accum(float x, double& s1, double& s2, doubl
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Fused first stage.  The first stage's kernel exists only because eta_1 is not known before the
-// whole vector has been summed.  A call that repeats the previous call's shape (the next training
-// iteration) knows roughly where eta_1 will fall, so k_fit prepares, in the same pass,
-//   * per-wave lists of the magnitudes inside a narrow band [lo, hi] around the previous eta_1,
-//   * count, sum |x| and sum x^2 of the entries above the band (per block),
-//   * per-wave candidate lists for stage 2: the entries above a threshold predicted from the previous
-//     call's stage-1 fit and from where its eta_2 fell (the same rule as the candidate threshold of
-//     stage_prologue, evaluated on last call's fit).
-// If this call's eta_1 lands inside the band, the statistics of its exceedances are exact without a
-// second pass over the vector: sum (|x|-eta) and sum (|x|-eta)^2 over the entries above the band
-// follow from the three moments, the band's own entries are few and are summed directly by the first
-// stage's kernel, which then skips the dense vector (status SIDCO_ST_FUSED).  If eta_1 lands outside,
-// that kernel runs its normal dense pass and overwrites the candidate lists (SIDCO_ST_FALLBACK).
-// The band's width follows the observed change of eta_1 from call to call.
-// ---------------------------------------------------------------------------------------------
-struct FusedPlan {
-    bool on;
-    float lo, hi, eta_w;
-};
-
-// Same result in every thread of every block: it only reads what the previous call left.
-__device__ __forceinline__ FusedPlan fused_plan(const Params& p)
-{
-    FusedPlan f;
-    f.on = false;
-    f.lo = f.hi = f.eta_w = 0.0f;
-    const float eta_prev = p.st->diag.eta[0];
-    const float seen = p.st->theta_seen[1];
-    const FitRecord fit = p.st->cand_fit[1];
-    float rel = p.fused_first ? kBandFirst : p.st->band_rel;
-    if (!(rel >= kBandMin && rel <= kBandMax)) rel = kBandFirst;
-    if (!(eta_prev > 0.0f) || !(eta_prev < FLT_MAX) || !(seen == seen)) return f;
-    const float theta = fminf(fmaxf(seen - kHintMargin, p.theta_min), kHintMax);
-    const double Lw = p.L[0] + (double)theta * p.L[1];
-    Fit q;
-    q.gpd = fit.gpd != 0;
-    q.s = fit.s;
-    q.c = fit.c;
-    q.a = fit.a;
-    q.b = fit.b;
-    f.lo = eta_prev * (1.0f - rel);
-    f.hi = eta_prev * (1.0f + rel);
-    f.eta_w = fit.loc + fit_quantile_fast(q, Lw);
-    f.on = f.eta_w > f.hi && f.eta_w < FLT_MAX && f.lo > 0.0f;
-    return f;
-}
-
-// what a lane accumulates for the fused first stage
-struct FusedAcc {
-    uint32_t n_hi;   // entries above the band (wave-uniform)
-    double s1, s2;   // their sum |x| and sum x^2
-};
-
-template <int DIST>
-__device__ __forceinline__ void fused_one(bool valid, float x, int32_t idx, const FusedPlan& f, FusedAcc& acc,
-                                          ListWriterT<float>& bw, ListWriter& cw, int lane)
-{
-    const float a = __builtin_fabsf(x);  // NaN: every comparison below is false
-    const bool above = valid && a > f.hi;
-    acc.n_hi += (uint32_t)__popcll(__ballot(above));
-    const double da = above ? (double)a : 0.0;
-    acc.s1 += da;
-    if constexpr (DIST != kDistExp) acc.s2 = __builtin_fma(da, da, acc.s2);
-    list_push_entry(bw, valid && a > f.lo && !above, a, lane);
-    list_push(cw, valid && a > f.eta_w, idx, x, lane);
-}
-
 // U complete tiles starting at tile t, 4-element accesses.  EC: acc = g + residual, stored back.  A
 // 16-bit gradient is widened to fp32 first and acc is always stored (into the residual, or, without
 // one, into the workspace's own buffer), because every later kernel reads an fp32 vector.
-template <int DIST, bool EC, int GT, bool FUSED, int U>
+template <int DIST, bool EC, int GT, int U>
 __device__ __forceinline__ void fit_tiles(const void* __restrict__ g, f4* __restrict__ a4, uint32_t t, int lane,
-                                          double& s1, double& s2, double& sl, int& se, const FusedPlan& f,
-                                          FusedAcc& acc, ListWriterT<float>& bw, ListWriter& cw)
+                                          double& s1, double& s2, double& sl, int& se)
 {
     constexpr bool WRITE = EC || GT != kGradF32;
     f4 a[U], b[U];
@@ -432,15 +352,6 @@ __device__ __forceinline__ void fit_tiles(const void* __restrict__ g, f4* __rest
         fit_accum<DIST>(c.y, s1, s2, sl, se);
         fit_accum<DIST>(c.z, s1, s2, sl, se);
         fit_accum<DIST>(c.w, s1, s2, sl, se);
-        if constexpr (FUSED) {
-            const int32_t i0 = (int32_t)((t + u) * kTile + lane * 4);
-            fused_one<DIST>(true, c.x, i0 + 0, f, acc, bw, cw, lane);
-            fused_one<DIST>(true, c.y, i0 + 1, f, acc, bw, cw, lane);
-            fused_one<DIST>(true, c.z, i0 + 2, f, acc, bw, cw, lane);
-            fused_one<DIST>(true, c.w, i0 + 3, f, acc, bw, cw, lane);
-            list_flush(bw, lane);
-            list_flush(cw, lane);
-        }
     }
 }
 
@@ -471,11 +382,10 @@ __device__ __forceinline__ float fit_one(const Params& p, int64_t i, double& s1,
     return c;
 }
 
-// One wave's tiles.  FUSED: with the fused first stage's extra outputs.
-template <int DIST, bool EC, int GT, bool FUSED>
+// One wave's tiles.
+template <int DIST, bool EC, int GT>
 __device__ __forceinline__ void fit_wave(const Params& p, uint32_t w, int lane, double& s1, double& s2, double& sl,
-                                         int& se, const FusedPlan& f, FusedAcc& acc, ListWriterT<float>& bw,
-                                         ListWriter& cw)
+                                         int& se)
 {
     const uint32_t t0 = tile_begin(w, p.ntiles, p.nwaves), t1 = tile_begin(w + 1, p.ntiles, p.nwaves);
     const uint32_t tf = t1 < p.nfull ? t1 : p.nfull;  // tiles [t0,tf) are complete
@@ -484,28 +394,21 @@ __device__ __forceinline__ void fit_wave(const Params& p, uint32_t w, int lane, 
         f4* a4 = reinterpret_cast<f4*>(p.acc_w);
         // no second register buffer: with 16 waves per CU in flight it gained nothing (measured)
 #pragma unroll 1
-        for (; t + 4 <= tf; t += 4) fit_tiles<DIST, EC, GT, FUSED, 4>(p.grad, a4, t, lane, s1, s2, sl, se, f, acc, bw, cw);
+        for (; t + 4 <= tf; t += 4) fit_tiles<DIST, EC, GT, 4>(p.grad, a4, t, lane, s1, s2, sl, se);
 #pragma unroll 1
-        for (; t < tf; ++t) fit_tiles<DIST, EC, GT, FUSED, 1>(p.grad, a4, t, lane, s1, s2, sl, se, f, acc, bw, cw);
+        for (; t < tf; ++t) fit_tiles<DIST, EC, GT, 1>(p.grad, a4, t, lane, s1, s2, sl, se);
     }
     // unaligned buffers and the ragged last tile: guarded scalar accesses
     for (; t < t1; ++t) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int64_t i = (int64_t)t * kTile + lane * 4 + j;
-            const bool valid = i < p.d;
-            float c = 0.0f;
-            if (valid) c = fit_one<DIST, EC, GT>(p, i, s1, s2, sl, se);
-            if constexpr (FUSED) fused_one<DIST>(valid, c, (int32_t)i, f, acc, bw, cw, lane);
-        }
-        if constexpr (FUSED) {
-            list_flush(bw, lane);
-            list_flush(cw, lane);
+            if (i < p.d) fit_one<DIST, EC, GT>(p, i, s1, s2, sl, se);
         }
     }
 }
 
-template <int DIST, bool EC, int GT, bool FUSED>
+template <int DIST, bool EC, int GT>
 __device__ __forceinline__ void fit_body(const Params& p, Blk b)
 {
     __shared__ double sh[kWavesPerBlock][4];
@@ -513,47 +416,7 @@ __device__ __forceinline__ void fit_body(const Params& p, Blk b)
     const uint32_t w = b.id * kWavesPerBlock + wib;
     double s1 = 0.0, s2 = 0.0, sl = 0.0;
     int se = 0;
-    FusedPlan f;
-    f.on = false;
-    f.lo = f.hi = f.eta_w = 0.0f;
-    FusedAcc acc;
-    acc.n_hi = 0;
-    acc.s1 = acc.s2 = 0.0;
-    ListWriterT<float> bw;
-    ListWriter cw;
-    bw.list = nullptr;
-    bw.ring = nullptr;
-    cw.list = nullptr;
-    cw.ring = nullptr;
-    bw.run = bw.fill = cw.run = cw.fill = 0;
-    if constexpr (FUSED) {
-        __shared__ float band_ring[kWavesPerBlock][kRingSize];
-        __shared__ int2 cand_ring[kWavesPerBlock][kRingSize];
-        f = fused_plan(p);
-        if (b.id == 0 && threadIdx.x == 0) {
-            p.st->fused_on = f.on ? 1u : 0u;
-            p.st->band_lo = f.lo;
-            p.st->band_hi = f.hi;
-            p.st->fused_eta_w = f.eta_w;
-        }
-        bw.ring = band_ring[wib];
-        cw.ring = cand_ring[wib];
-    }
-    if (w < p.nwaves) {
-        if (FUSED && f.on) {  // block-uniform
-            const size_t off = (size_t)tile_begin(w, p.ntiles, p.nwaves) * kTile;
-            bw.list = p.band_out + off;
-            cw.list = p.cand_out + off;
-            fit_wave<DIST, EC, GT, true>(p, w, lane, s1, s2, sl, se, f, acc, bw, cw);
-            const uint32_t nb = list_finish(bw, lane), nc = list_finish(cw, lane);
-            if (lane == 0) {
-                p.band_cnt[w] = nb;
-                p.cand_cnt[w] = nc;
-            }
-        } else {
-            fit_wave<DIST, EC, GT, false>(p, w, lane, s1, s2, sl, se, f, acc, bw, cw);
-        }
-    }
+    if (w < p.nwaves) fit_wave<DIST, EC, GT>(p, w, lane, s1, s2, sl, se);
     double v[3] = {s1, s2, sl + (double)se};
     v[0] = wave_sum(v[0]);
     v[1] = wave_sum(v[1]);
@@ -569,24 +432,6 @@ __device__ __forceinline__ void fit_body(const Params& p, Blk b)
 #pragma unroll
         for (int i = 0; i < kWavesPerBlock; ++i) tot += sh[i][threadIdx.x];
         p.part_out[threadIdx.x * kMaxBlocks + b.id] = tot;
-    }
-    if constexpr (FUSED) {
-        if (f.on) {  // block-uniform
-            double r[3] = {wave_sum(acc.s1), wave_sum(acc.s2), (double)acc.n_hi};
-            __syncthreads();  // the sums above have been read
-            if (lane == 0) {
-                sh[wib][0] = r[0];
-                sh[wib][1] = r[1];
-                sh[wib][2] = r[2];
-            }
-            __syncthreads();
-            if (threadIdx.x < 3) {
-                double tot = 0.0;
-#pragma unroll
-                for (int i = 0; i < kWavesPerBlock; ++i) tot += sh[i][threadIdx.x];
-                p.raw_out[threadIdx.x * kMaxBlocks + b.id] = tot;
-            }
-        }
     }
     if (b.id == 0 && threadIdx.x == 0) fit_reset_state(p);
 }
@@ -838,60 +683,17 @@ __device__ __forceinline__ void compact_body(const Params& p, Blk b)
     const uint32_t t1 = active ? tile_begin(w + 1, p.ntiles, p.nwaves) : 0;
     const uint32_t tf = t1 < p.nfull ? t1 : p.nfull;  // tiles [t0,tf) are complete
 
-    // Fused first stage (see k_fit): what that kernel prepared, if it did
-    const bool fused = STATS && WRITE && p.fused && p.stage == 1 && p.st->fused_on != 0;  // the same in every block
-    float band_lo = 0.0f, band_hi = 0.0f, fused_eta_w = 0.0f;
-    double raw[3] = {0.0, 0.0, 0.0};
-    uint32_t n_band = 0;
-    float band0 = 0.0f;
-    const float* __restrict__ band = reinterpret_cast<const float*>(p.seg_in) + (size_t)t0 * kTile;
-    if (fused) {
-        band_lo = p.st->band_lo;
-        band_hi = p.st->band_hi;
-        fused_eta_w = p.st->fused_eta_w;
-        if (threadIdx.x == 0) {  // this block's moments above the band (the slot is overwritten at the end)
-            raw[0] = p.part_out[0 * kMaxBlocks + b.id];
-            raw[1] = p.part_out[1 * kMaxBlocks + b.id];
-            raw[2] = p.part_out[2 * kMaxBlocks + b.id];
-        }
-        if (active) {
-            n_band = p.cnt_in[w];
-            if ((uint32_t)lane < (t1 - t0) * kTile) band0 = band[lane];  // within the wave's segment; masked by n_band
-        }
-    }
-
     // The first loads of the body do not depend on the threshold: issue them before the prologue so
     // that their latency overlaps the reduction of the partial sums.
     f4 a0[U];
-    const bool pre_dense = !fused && active && p.vec_ok && t0 + U <= tf;
+    const bool pre_dense = active && p.vec_ok && t0 + U <= tf;
     if (pre_dense) load_tiles<U>(a0, reinterpret_cast<const f4*>(p.acc), dense_first_batch(p, t0, tf, U), lane);
 
     const StageEta se = stage_prologue(p, b, false, sh);
 
     uint32_t run = 0, ns = 0;
     double sy = 0.0, syy = 0.0;
-    // eta_1 inside the band: the band's entries and the moments above it give the exact statistics
-    const bool hit = fused && se.eta >= band_lo && se.eta <= band_hi;  // false for a NaN threshold
-    if (hit) {
-        const float eta = se.eta;
-        if (active) {
-            for (uint32_t c = 0; c < n_band; c += 64) {
-                const float a = c == 0 ? band0 : (c + lane < n_band ? band[c + lane] : 0.0f);
-                const bool sel = c + lane < n_band && a > eta;
-                ns += (uint32_t)__popcll(__ballot(sel));
-                const double y = sel ? (double)a - (double)eta : 0.0;
-                sy += y;
-                syy = __builtin_fma(y, y, syy);
-            }
-        }
-        if (threadIdx.x == 0) {
-            // sum (x - eta) and sum (x - eta)^2 over the entries above the band, from their moments
-            const double e = (double)eta;
-            sy += raw[0] - raw[2] * e;
-            syy += raw[1] - 2.0 * e * raw[0] + raw[2] * e * e;
-        }
-        if (wib == 0) ns += (uint32_t)__shfl((int)(uint32_t)raw[2], 0, 64);  // wave-uniform count
-    } else if (active) {
+    if (active) {
         ListWriter lw;
         lw.list = p.seg_out + (size_t)t0 * kTile;  // room for every element of the wave's tiles
         lw.ring = ring[WRITE ? wib : 0];
@@ -899,15 +701,6 @@ __device__ __forceinline__ void compact_body(const Params& p, Blk b)
         compact_dense<STATS, WRITE, U>(p, a0, pre_dense, t0, t1, tf, lane, se.eta, se.eta_w, lw, ns, sy, syy);
         if (WRITE) run = list_finish(lw, lane);
         if (lane == 0) p.cnt_out[w] = run;
-    }
-    if (STATS && WRITE && p.fused && p.stage == 1 && b.id == 0 && threadIdx.x == 0) {
-        // the same thread wrote these entries in the prologue
-        if (hit) {
-            p.st->list_eta[1] = fused_eta_w;
-            p.st->status_after[1] |= kStFused;
-        } else if (fused) {
-            p.st->status_after[1] |= kStFallback;
-        }
     }
     stage_epilogue<STATS>(p, b, lane, wib, STATS ? ns : run, sy, syy, sh, sh_cnt);
 }
@@ -1325,7 +1118,7 @@ __device__ __forceinline__ Params batch_params(const BatchArgs& a, bool final_gr
 {
     const uint32_t t = __builtin_amdgcn_readfirstlane((uint32_t)(final_grid ? a.tb->fmap[blockIdx.x] : a.tb->map[blockIdx.x]));
     const TensorDesc& ds = a.tb->desc[t];
-    Params p;
+    Params p = {};
     p.grad = a.grad + ds.offset;
     p.gt = kGradF32;
     p.residual = a.residual ? a.residual + ds.offset : nullptr;
@@ -1367,8 +1160,8 @@ __device__ __forceinline__ Params batch_params(const BatchArgs& a, bool final_gr
     return p;
 }
 
-template <int DIST, bool EC, int GT, bool FUSED>
-__global__ __launch_bounds__(kBlock, 4) void k_fit(Params p) { fit_body<DIST, EC, GT, FUSED>(p, whole_grid()); }
+template <int DIST, bool EC, int GT>
+__global__ __launch_bounds__(kBlock, 4) void k_fit(Params p) { fit_body<DIST, EC, GT>(p, whole_grid()); }
 template <bool STATS, bool WRITE>
 __global__ __launch_bounds__(kBlock, 4) void k_compact(Params p) { compact_body<STATS, WRITE>(p, whole_grid()); }
 __global__ __launch_bounds__(kBlock, 4) void k_lists(Params p) { lists_body(p, whole_grid()); }
@@ -1380,7 +1173,7 @@ __global__ __launch_bounds__(kBlock) void k_fit_batched(BatchArgs a)
 {
     Blk b;
     const Params p = batch_params(a, false, b);
-    fit_body<DIST, EC, kGradF32, false>(p, b);
+    fit_body<DIST, EC, kGradF32>(p, b);
 }
 template <bool STATS, bool WRITE>
 __global__ __launch_bounds__(kBlock, 4) void k_compact_batched(BatchArgs a)
@@ -1415,18 +1208,10 @@ template <bool EC, int GT>
 static void launch_fit_as(const Params& p, hipStream_t s)
 {
     const dim3 grid(p.nblocks), block(kBlock);
-    if (p.fused) {
-        switch (p.dist) {
-            case kDistExp: hipLaunchKernelGGL((k_fit<kDistExp, EC, GT, true>), grid, block, 0, s, p); break;
-            case kDistGamma: hipLaunchKernelGGL((k_fit<kDistGamma, EC, GT, true>), grid, block, 0, s, p); break;
-            default: hipLaunchKernelGGL((k_fit<kDistGpd, EC, GT, true>), grid, block, 0, s, p); break;
-        }
-        return;
-    }
     switch (p.dist) {
-        case kDistExp: hipLaunchKernelGGL((k_fit<kDistExp, EC, GT, false>), grid, block, 0, s, p); break;
-        case kDistGamma: hipLaunchKernelGGL((k_fit<kDistGamma, EC, GT, false>), grid, block, 0, s, p); break;
-        default: hipLaunchKernelGGL((k_fit<kDistGpd, EC, GT, false>), grid, block, 0, s, p); break;
+        case kDistExp: hipLaunchKernelGGL((k_fit<kDistExp, EC, GT>), grid, block, 0, s, p); break;
+        case kDistGamma: hipLaunchKernelGGL((k_fit<kDistGamma, EC, GT>), grid, block, 0, s, p); break;
+        default: hipLaunchKernelGGL((k_fit<kDistGpd, EC, GT>), grid, block, 0, s, p); break;
     }
 }
 
