@@ -175,136 +175,187 @@ struct StageEta {
 // always; if it lands at or above eta_w the candidate lists contain every entry it can select and
 // replace the dense vector, else that kernel falls back to the dense vector.  Either way the result is
 // the same: only the time depends on the guess.
-__device__ StageEta stage_prologue(const Params& p, Blk b, bool auto_src, double (*sh)[4])
+//
+// What a stage's prologue reads from memory: issued as early as possible, and BEFORE any bulk loads of
+// the kernel's body - the wave's memory counter retires in order, so a wait for these few values would
+// otherwise also wait for every load issued ahead of them.
+struct PrologueLoads {
+    double v[3];        // this thread's share of the producer's partial sums (and counts)
+    float eta_prev;     // eta_{m-1}
+    uint32_t status;    // status bits accumulated up to stage m-1
+    bool frozen;        // an empty exceedance set has stopped the refinement
+    float list_eta;     // the producer's lists hold every entry above this
+    float seen;         // where the next stage's threshold fell last time (hint), NaN if unknown
+    FitRecord prev_fit; // the producer's candidate fit (block 0, thread 0 only)
+};
+
+__device__ __forceinline__ PrologueLoads prologue_load(const Params& p, Blk b, bool auto_src)
 {
     const int m = p.stage;  // 1-based
     const uint32_t t = threadIdx.x;
     const bool have = t < p.nblocks;  // one thread per block of the kernel that produced the partial sums
+    PrologueLoads g;
+    g.seen = (p.theta > 0.0f && p.use_hint) ? p.st->theta_seen[m] : __builtin_nanf("");
+    g.prev_fit.gpd = 0;
+    g.prev_fit.loc = 0.0f;
+    g.prev_fit.s = g.prev_fit.c = g.prev_fit.a = g.prev_fit.b = 0.0;
+    if (auto_src && p.prev_cand && b.id == 0 && t == 0) g.prev_fit = p.st->cand_fit[m - 1];
+    g.list_eta = auto_src ? p.st->list_eta[m - 1] : 0.0f;
+    g.eta_prev = 0.0f;
+    g.status = 0;
+    g.frozen = false;
+    if (m == 1) {
+        g.v[0] = have ? p.part_in[0 * kMaxBlocks + t] : 0.0;
+        g.v[1] = (have && p.dist == kDistGpd) ? p.part_in[1 * kMaxBlocks + t] : 0.0;
+        g.v[2] = (have && p.dist == kDistGamma) ? p.part_in[2 * kMaxBlocks + t] : 0.0;
+    } else {
+        g.v[0] = have ? p.part_in[0 * kMaxBlocks + t] : 0.0;
+        g.v[1] = (have && p.dist != kDistExp) ? p.part_in[1 * kMaxBlocks + t] : 0.0;
+        g.v[2] = have ? (double)p.blk_in[t] : 0.0;  // counts < 2^31: exact in fp64
+        g.eta_prev = p.st->diag.eta[m - 2];
+        g.status = p.st->status_after[m - 1];
+        g.frozen = p.st->frozen_after[m - 1] != 0;
+    }
+    return g;
+}
+
+// Reduces the partial sums (fixed order) and evaluates eta for stage p.stage.  Returns the same values
+// in every thread of every block.  Block 0 records the stage in the diagnostics.
+__device__ StageEta prologue_finish(const Params& p, Blk b, bool auto_src, PrologueLoads& g, double (*sh)[4])
+{
+    const int m = p.stage;  // 1-based
+    const uint32_t t = threadIdx.x;
     const double L = stage_L(p, m - 1);
     // candidate threshold of this kernel's lists: log-ratio Lw > L, or none
     double Lw = 0.0;
     if (p.theta > 0.0f) {
         float theta = p.theta;
-        if (p.use_hint) {
-            const float seen = p.st->theta_seen[m];
-            if (seen == seen) theta = fminf(fmaxf(seen - kHintMargin, p.theta_min), kHintMax);
-        }
+        if (g.seen == g.seen) theta = fminf(fmaxf(g.seen - kHintMargin, p.theta_min), kHintMax);
         Lw = L + (double)theta * stage_L(p, m);
     }
-    // the producer's candidate fit, for the record of where this stage's threshold falls on its scale
-    FitRecord prev_fit;
-    prev_fit.gpd = 0;
-    prev_fit.loc = 0.0f;
-    prev_fit.s = prev_fit.c = prev_fit.a = prev_fit.b = 0.0;
-    if (auto_src && p.prev_cand && b.id == 0 && threadIdx.x == 0) prev_fit = p.st->cand_fit[m - 1];
+    const FitRecord prev_fit = g.prev_fit;
     Fit fit = fit_linear(0.0, 0.0);
     float loc = 0.0f;
-    uint32_t status = 0;
+    uint32_t status = g.status;
     double stats[3] = {0.0, 0.0, 0.0};
     StageEta r;
-    bool frozen = false;
+    bool frozen = g.frozen;
     unsigned long long n;
-    // the producer's list threshold, loaded together with the partial sums (one round trip)
-    const float list_eta = auto_src ? p.st->list_eta[m - 1] : 0.0f;
-    if (m == 1) {
-        double v[3];
-        v[0] = have ? p.part_in[0 * kMaxBlocks + t] : 0.0;
-        v[1] = (have && p.dist == kDistGpd) ? p.part_in[1 * kMaxBlocks + t] : 0.0;
-        v[2] = (have && p.dist == kDistGamma) ? p.part_in[2 * kMaxBlocks + t] : 0.0;
-        block_sum<3>(v, sh);
-        n = (unsigned long long)p.d;
-        const double d = (double)p.d;
-        const double mu = v[0] / d;
-        double var = 0.0, mulog = 0.0;
-        bool finite = isfinite(mu);
-        if (p.dist == kDistGpd) {
-            var = v[1] / d - mu * mu;
-            finite = finite && isfinite(var);
-        } else if (p.dist == kDistGamma) {
-            mulog = (v[2] / d) * 0.6931471805599453094;  // log2 -> natural log
-            finite = finite && isfinite(mulog);
-        }
-        stats[0] = mu;
-        stats[1] = var;
-        stats[2] = mulog;
-        if (!finite) {
-            status |= kStNonfinite;
-            r.eta = r.eta_w = __builtin_nanf("");
-        } else {
-            fit = stage1_fit(p.dist, mu, var, mulog, status);
-            double tq = fit_quantile(fit, L);
-            if (tq < 0.0) {  // only the gamma form can be negative: delta_1 * Gamma(alpha) > 1
-                status |= kStGammaClamp;
-                tq = 0.0;
+    block_sum<3>(g.v, sh);
+    r.eta = r.eta_w = 0.0f;
+    r.lists_ok = false;
+    // One wave per block evaluates the closed form - a few hundred dependent fp64 instructions, more for
+    // the gamma law - and the others wait: with every wave at it, four per SIMD take turns on the same
+    // arithmetic and the prologue lasts that much longer (measured).
+    if (t < 64) {
+        if (m == 1) {
+            n = (unsigned long long)p.d;
+            const double d = (double)p.d;
+            const double mu = g.v[0] / d;
+            double var = 0.0, mulog = 0.0;
+            bool finite = isfinite(mu);
+            if (p.dist == kDistGpd) {
+                var = g.v[1] / d - mu * mu;
+                finite = finite && isfinite(var);
+            } else if (p.dist == kDistGamma) {
+                mulog = (g.v[2] / d) * 0.6931471805599453094;  // log2 -> natural log
+                finite = finite && isfinite(mulog);
             }
-            r.eta = r.eta_w = (float)tq;
-            if (Lw > L) {
-                const float c = fit_quantile_fast(fit, Lw);
-                if (c > r.eta) r.eta_w = c;
-            }
-        }
-    } else {
-        double v[3];
-        v[0] = have ? p.part_in[0 * kMaxBlocks + t] : 0.0;
-        v[1] = (have && p.dist != kDistExp) ? p.part_in[1 * kMaxBlocks + t] : 0.0;
-        v[2] = have ? (double)p.blk_in[t] : 0.0;  // counts < 2^31: exact in fp64
-        // the previous stage's record, loaded together with the partial sums (one round trip)
-        const float eta_prev = p.st->diag.eta[m - 2];
-        status = p.st->status_after[m - 1];
-        frozen = p.st->frozen_after[m - 1] != 0;
-        block_sum<3>(v, sh);
-        n = (unsigned long long)v[2];
-        r.eta = r.eta_w = eta_prev;
-        if (!frozen) {
-            if (n == 0) {  // nothing exceeds eta_prev: keep it for all later stages
-                frozen = true;
-                status |= kStStopped;
+            stats[0] = mu;
+            stats[1] = var;
+            stats[2] = mulog;
+            if (!finite) {
+                status |= kStNonfinite;
+                r.eta = r.eta_w = __builtin_nanf("");
             } else {
-                const double ybar = v[0] / (double)n;
-                const double yvar = p.dist == kDistExp ? 0.0 : v[1] / (double)n - ybar * ybar;
-                stats[0] = ybar;
-                stats[1] = yvar;
-                fit = pot_fit(p.dist, ybar, yvar, status);
-                loc = eta_prev;
-                r.eta = r.eta_w = (float)((double)eta_prev + fit_quantile(fit, L));
+                fit = stage1_fit(p.dist, mu, var, mulog, status);
+                double tq = fit_quantile(fit, L);
+                if (tq < 0.0) {  // only the gamma form can be negative: delta_1 * Gamma(alpha) > 1
+                    status |= kStGammaClamp;
+                    tq = 0.0;
+                }
+                r.eta = r.eta_w = (float)tq;
                 if (Lw > L) {
-                    const float c = eta_prev + fit_quantile_fast(fit, Lw);
+                    const float c = fit_quantile_fast(fit, Lw);
                     if (c > r.eta) r.eta_w = c;
                 }
             }
+        } else {
+            const float eta_prev = g.eta_prev;
+            n = (unsigned long long)g.v[2];
+            r.eta = r.eta_w = eta_prev;
+            if (!frozen) {
+                if (n == 0) {  // nothing exceeds eta_prev: keep it for all later stages
+                    frozen = true;
+                    status |= kStStopped;
+                } else {
+                    const double ybar = g.v[0] / (double)n;
+                    const double yvar = p.dist == kDistExp ? 0.0 : g.v[1] / (double)n - ybar * ybar;
+                    stats[0] = ybar;
+                    stats[1] = yvar;
+                    fit = pot_fit(p.dist, ybar, yvar, status);
+                    loc = eta_prev;
+                    r.eta = r.eta_w = (float)((double)eta_prev + fit_quantile(fit, L));
+                    if (Lw > L) {
+                        const float c = eta_prev + fit_quantile_fast(fit, Lw);
+                        if (c > r.eta) r.eta_w = c;
+                    }
+                }
+            }
+        }
+        r.lists_ok = auto_src && (r.eta >= g.list_eta);  // false for a NaN threshold, which selects nothing anyway
+        if (auto_src && !r.lists_ok) status |= kStFallback;
+        if (b.id == 0 && t == 0) {
+            p.st->diag.eta[m - 1] = r.eta;
+            p.st->diag.n[m - 1] = (int64_t)n;
+            p.st->diag.stats[m - 1][0] = stats[0];
+            p.st->diag.stats[m - 1][1] = stats[1];
+            p.st->diag.stats[m - 1][2] = stats[2];
+            p.st->status_after[m] = status;
+            p.st->frozen_after[m] = frozen ? 1u : 0u;
+            p.st->list_eta[m] = r.eta_w;
+            if (p.theta > 0.0f) {
+                FitRecord rec;
+                rec.gpd = fit.gpd ? 1 : 0;
+                rec.loc = loc;
+                rec.s = fit.s;
+                rec.c = fit.c;
+                rec.a = fit.a;
+                rec.b = fit.b;
+                p.st->cand_fit[m] = rec;
+            }
+            if (auto_src && p.prev_cand) {
+                // invert the producer's quantile function at this stage's threshold:
+                // eta = loc + Q(L_{m-1} + theta * L_m)  ->  theta
+                const double tq = (double)r.eta - (double)prev_fit.loc;
+                const double Lq = prev_fit.gpd ? log1p(tq * prev_fit.a / prev_fit.b) / prev_fit.a : (tq - prev_fit.c) / prev_fit.s;
+                const float seen = (float)((Lq - stage_L(p, m - 2)) / L);
+                p.st->theta_seen[m - 1] = (frozen || !(fabsf(seen) < 1.0e6f)) ? __builtin_nanf("") : seen;
+            }
         }
     }
-    r.lists_ok = auto_src && (r.eta >= list_eta);  // false for a NaN threshold, which selects nothing anyway
-    if (auto_src && !r.lists_ok) status |= kStFallback;
-    if (b.id == 0 && t == 0) {
-        p.st->diag.eta[m - 1] = r.eta;
-        p.st->diag.n[m - 1] = (int64_t)n;
-        p.st->diag.stats[m - 1][0] = stats[0];
-        p.st->diag.stats[m - 1][1] = stats[1];
-        p.st->diag.stats[m - 1][2] = stats[2];
-        p.st->status_after[m] = status;
-        p.st->frozen_after[m] = frozen ? 1u : 0u;
-        p.st->list_eta[m] = r.eta_w;
-        if (p.theta > 0.0f) {
-            FitRecord rec;
-            rec.gpd = fit.gpd ? 1 : 0;
-            rec.loc = loc;
-            rec.s = fit.s;
-            rec.c = fit.c;
-            rec.a = fit.a;
-            rec.b = fit.b;
-            p.st->cand_fit[m] = rec;
-        }
-        if (auto_src && p.prev_cand) {
-            // invert the producer's quantile function at this stage's threshold:
-            // eta = loc + Q(L_{m-1} + theta * L_m)  ->  theta
-            const double tq = (double)r.eta - (double)prev_fit.loc;
-            const double Lq = prev_fit.gpd ? log1p(tq * prev_fit.a / prev_fit.b) / prev_fit.a : (tq - prev_fit.c) / prev_fit.s;
-            const float seen = (float)((Lq - stage_L(p, m - 2)) / L);
-            p.st->theta_seen[m - 1] = (frozen || !(fabsf(seen) < 1.0e6f)) ? __builtin_nanf("") : seen;
-        }
+    __syncthreads();  // every thread has left block_sum: sh is free
+    if (t == 0) {
+        float* out = reinterpret_cast<float*>(&sh[0][0]);
+        out[0] = r.eta;
+        out[1] = r.eta_w;
+        out[2] = r.lists_ok ? 1.0f : 0.0f;
+    }
+    __syncthreads();
+    {
+        const float* in = reinterpret_cast<const float*>(&sh[0][0]);
+        r.eta = in[0];
+        r.eta_w = in[1];
+        r.lists_ok = in[2] != 0.0f;
     }
     return r;
+}
+
+// both halves back to back, for kernels whose body loads little before the threshold is known
+__device__ __forceinline__ StageEta stage_prologue(const Params& p, Blk b, bool auto_src, double (*sh)[4])
+{
+    PrologueLoads g = prologue_load(p, b, auto_src);
+    return prologue_finish(p, b, auto_src, g, sh);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -527,9 +578,10 @@ __device__ __forceinline__ void emit(bool valid, float x, int32_t idx, float eta
     const float a = __builtin_fabsf(x);
     if (WRITE) list_push(lw, valid && (a > eta_w), idx, x, lane);
     if (STATS) {
+        // y = |x| - eta_s over the selected entries, exactly, and 0 elsewhere (eta_s - eta_s)
         const bool sel = valid && (a > eta_s);
         ns += (uint32_t)__popcll(__ballot(sel));
-        const double y = sel ? (double)a - (double)eta_s : 0.0;
+        const double y = (double)(sel ? a : eta_s) - (double)eta_s;
         sy += y;
         syy = __builtin_fma(y, y, syy);
     }
@@ -683,13 +735,15 @@ __device__ __forceinline__ void compact_body(const Params& p, Blk b)
     const uint32_t t1 = active ? tile_begin(w + 1, p.ntiles, p.nwaves) : 0;
     const uint32_t tf = t1 < p.nfull ? t1 : p.nfull;  // tiles [t0,tf) are complete
 
-    // The first loads of the body do not depend on the threshold: issue them before the prologue so
-    // that their latency overlaps the reduction of the partial sums.
+    // Neither the prologue's own loads nor the first loads of the body depend on the threshold.  The
+    // prologue's go first (the memory counter retires in order: behind the tiles they would wait for
+    // them), then the first batch of tiles, whose latency overlaps the reduction of the partial sums.
+    PrologueLoads g = prologue_load(p, b, false);
     f4 a0[U];
     const bool pre_dense = active && p.vec_ok && t0 + U <= tf;
     if (pre_dense) load_tiles<U>(a0, reinterpret_cast<const f4*>(p.acc), dense_first_batch(p, t0, tf, U), lane);
 
-    const StageEta se = stage_prologue(p, b, false, sh);
+    const StageEta se = prologue_finish(p, b, false, g, sh);
 
     uint32_t run = 0, ns = 0;
     double sy = 0.0, syy = 0.0;
