@@ -234,6 +234,8 @@ def main():
     if args.graph:
         pairs = nbuf if nres == nbuf else 1
         side = torch.cuda.Stream()
+        sidco.sidco_reserve(sidco.sidco_workspace_bytes_typed(d, {"f32": 0, "f16": 1, "bf16": 2}[args.grad_dtype], ec),
+                            stream=side)   # the capturing stream's workspace: allocated outside the capture
         side.wait_stream(stream)
         graphs = []
         with torch.cuda.stream(side):

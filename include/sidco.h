@@ -17,18 +17,34 @@
  * "host" pointers are ordinary host memory.  No torch types cross this boundary.
  * Every enqueueing call is asynchronous on `stream` and returns after enqueue;
  * outputs are valid once the stream reaches that point.  The library never
- * synchronises with the host inside an enqueueing call and never spins on the
- * device.  Thresholds, the selected set, its values and the residual are
- * deterministic (same inputs -> same bits); the order of the output pairs is
- * fixed for a single-stage call and may vary between runs for M >= 2.
+ * spins on the device, and an enqueueing call synchronises with the host in
+ * one case only: when the stream's workspace has to grow (first use, or a
+ * longer vector than before), it is freed and allocated again, which waits for
+ * the device.  sidco_reserve moves that out of the enqueueing calls.
+ * (sidco_controller_compress also reads one counter back on every Q-th call;
+ * that is its contract.)
+ *
+ * Results are deterministic for a given history of calls on a workspace: the
+ * same inputs after the same previous calls give the same bits.  Across
+ * different histories the exceedance statistics of the stages after the first
+ * are summed in a different order (the candidate lists follow the previous
+ * call's thresholds, see sidco_set_speculation), so a threshold can differ in
+ * its last bit, far inside the 1e-5 the fitted values are specified to; given
+ * the threshold, the selected set, its values and the residual are exact.  The
+ * order of the output pairs is fixed for a single-stage call and may vary
+ * between runs for M >= 2.
  *
  * Return value: 0 on success, a negative SIDCO_ERR_* otherwise.  Argument
  * errors are detected on the host before any HIP call is made.  Conditions
  * that depend on the data (NaN/Inf input, degenerate fits, output overflow)
  * never cause out-of-bounds accesses; they are reported in sidco_diag.status.
  *
- * Calls that overlap in time on one device share the library's workspace on
- * that device and race; serialise them (one stream, or events).
+ * Workspaces.  The library keeps one workspace per (device, stream), so calls
+ * on different streams do not share state and may overlap; calls on one stream
+ * are ordered by the stream.  A caller-provided workspace (sidco_set_workspace)
+ * replaces them all on its device: calls that use it must not overlap.  The
+ * diagnostics calls that take a stream (sidco_read_diag, sidco_fit_result, ...)
+ * report the last call made on that stream.
  */
 #ifndef SIDCO_H
 #define SIDCO_H
@@ -101,7 +117,7 @@ typedef struct sidco_diag {
  *  delta      target ratio k/d, 0 < delta < 1 (Sec. 2.3)
  *  dist       SIDCO_DIST_*
  *  stages     M, 1..SIDCO_MAX_STAGES.  The ratios are delta_1 = 0.25 (the
- *             paper's setting, Sec. 4.1) and delta_m = (delta/delta_1)^(1/(M-1))
+ *             paper's setting, Sec. 4.1; see sidco_set_delta1) and delta_m = (delta/delta_1)^(1/(M-1))
  *             for m >= 2, so that their product is delta (Sec. 2.4); if
  *             delta_1 <= delta or M = 1 a single stage at delta is used.
  *  out_idx    device, int32, capacity sidco_out_capacity(d, delta)
@@ -109,8 +125,14 @@ typedef struct sidco_diag {
  *  out_count  device, 1 int32: number of pairs written (khat)
  *  out_eta    device, 1 float: eta_M
  * The pairs are not sorted by index.  Buffers are owned by the caller; the library owns only
- * its workspace, which it allocates on first use per device (hipMalloc) and
+ * its workspaces, which it allocates on first use per stream (hipMalloc) and
  * grows when d grows, unless sidco_set_workspace was called.
+ * This is the entry point with the signature the project brief names; where that
+ * brief's sketch proposed companions by other names, these are the ones built:
+ * explicit stage ratios are an argument of sidco_compress_ex rather than state
+ * set by a "set_stage_ratios" call (sidco_set_delta1 exists for callers that must
+ * stay on this signature), and "get_diag" is sidco_read_diag (sidco_get_diag is
+ * exported as another name of the same function).
  */
 int sidco_compress(void *stream, const float *grad, float *residual, int64_t d,
                    double delta, int dist, int stages,
@@ -165,8 +187,8 @@ size_t sidco_workspace_bytes_typed(int64_t d, int grad_dtype, int has_residual);
  *  out_offsets     host, n+1 int64 (sidco_batched_out_offsets fills the default:
  *                  sidco_out_capacity per tensor)
  *  out_counts, out_etas  device, n int32 / n floats
- * The first call with a given layout uploads a table and synchronises `stream`;
- * calls that repeat it are asynchronous like every other call.
+ * A call with a layout other than the previous call's uploads a table of a few
+ * kilobytes in stream order; nothing waits for the device.
  */
 int sidco_compress_batched(void *stream, const float *grad, float *residual, const int64_t *offsets,
                            int n, double delta, int dist, int stages,
@@ -174,7 +196,7 @@ int sidco_compress_batched(void *stream, const float *grad, float *residual, con
                            int32_t *out_counts, float *out_etas);
 int sidco_batched_out_offsets(const int64_t *offsets, int n, double delta, int64_t *out_offsets);
 size_t sidco_workspace_bytes_batched(const int64_t *offsets, int n);
-/* Diagnostics of tensor t of the last batched call on the current device. Synchronises `stream`. */
+/* Diagnostics of tensor t of the last batched call on `stream`.  Synchronises `stream`. */
 int sidco_read_diag_batched(void *stream, int t, sidco_diag *host_out);
 
 /*
@@ -198,8 +220,11 @@ int sidco_adapt_stages(int stages, double khat_avg, double k, double eps_high, d
  * average (the pseudo-code drops the count of the adapting iteration yet divides
  * by Q; Sec. 3 describes an average over the past Q steps).  The paper's
  * settings are delta_1 = 0.25, eps_high = eps_low = 0.2, Q = 5 (Sec. 4.1).
- * Other calls of this library on the same device between two calls of a
- * controller disturb its count.
+ * A controller belongs to one stream.  Its running count lives in that
+ * stream's workspace: if any other call of this library uses the same
+ * workspace inside a window of Q calls, the window's count is not this
+ * vector's alone; the controller then leaves the number of stages as it is
+ * and counts the window in sidco_controller_disturbed.
  */
 typedef struct sidco_controller sidco_controller;
 int sidco_controller_create(sidco_controller **out, double delta, int dist, int stages,
@@ -209,6 +234,8 @@ int sidco_controller_stages(const sidco_controller *c);             /* current M
 int64_t sidco_controller_iteration(const sidco_controller *c);      /* calls made so far       */
 double sidco_controller_last_average(const sidco_controller *c);    /* khat average at the last
                                                                        adaptation, -1 before it */
+int64_t sidco_controller_disturbed(const sidco_controller *c);      /* windows skipped because another
+                                                                       caller used the workspace   */
 int sidco_controller_compress(sidco_controller *c, void *stream, const float *grad, float *residual,
                               int64_t d, int32_t *out_idx, float *out_val, int32_t *out_count,
                               float *out_eta);
@@ -277,7 +304,7 @@ int sidco_topk(void *stream, const float *grad, float *residual, int64_t d, int6
  * smallest one stay may differ between runs); otherwise all of them stay.
  * sidco_dgc_sizes fills sizes[0..2] = n_s, k_s, k (host only).
  * sidco_dgc_result fills host_out[0..3] = n_s, k_s, first-pass count and
- * entries written of the last sidco_dgc on the current device; it synchronises `stream`.
+ * entries written of the last sidco_dgc on `stream`; it synchronises `stream`.
  */
 int sidco_dgc(void *stream, const float *grad, float *residual, int64_t d, double delta,
               double sample_ratio, uint64_t seed,
@@ -297,7 +324,7 @@ int sidco_fit(void *stream, const float *grad, float *residual, int64_t d, int d
 /* The same on a gradient of element type grad_dtype (SIDCO_GRAD_*), as in sidco_compress_typed. */
 int sidco_fit_typed(void *stream, const void *grad, int grad_dtype, float *residual, int64_t d, int dist);
 
-/* Sums of the last sidco_fit on the current device, reduced on the host in a
+/* Sums of the last sidco_fit on `stream`, reduced on the host in a
  * fixed order.  host_sums (host, 4 doubles) receives sum|acc|, sum acc^2
  * (GPD law only, else 0), sum log max(|acc|, 2^-126) (gamma law only, else 0)
  * and d.  Synchronises `stream`.                                              */
@@ -316,13 +343,39 @@ int sidco_stage_ratios(double delta, int stages, double delta1, double *ratios);
  * error code for invalid arguments.                                           */
 int64_t sidco_out_capacity(int64_t d, double delta);
 
-/* Host helper: bytes of device workspace a call with this d needs.            */
+/* delta_1 of the default stage schedule used by sidco_compress,
+ * sidco_compress_typed and sidco_compress_batched, for the calls that follow on
+ * every device: 0 < delta1 < 1, initially 0.25 (Sec. 4.1).
+ * Explicit ratios per call: sidco_compress_ex.                                */
+int sidco_set_delta1(double delta1);
+
+/* Host helper: bytes of device workspace a call with this d needs.  It depends
+ * on d alone (room for one list slot per element in two buffers, whatever
+ * delta and the number of stages are); the 16-bit and batched variants have
+ * their own helpers.                                                          */
 size_t sidco_workspace_bytes(int64_t d);
 
 /* Give the library a caller-owned device workspace (256-byte aligned) for the
  * current device instead of letting it allocate; NULL/0 returns to library
- * allocation.  The buffer must outlive every call that uses it.               */
+ * allocation.  The buffer must outlive every call that uses it; it serves the
+ * calls of every stream, which therefore must not overlap.                    */
 int sidco_set_workspace(void *device_ptr, size_t bytes);
+
+/* Make sure that the library's own workspace of `stream` on the current device
+ * has at least `bytes` (see the sidco_workspace_bytes helpers), so that the
+ * enqueueing calls that follow on that stream neither allocate nor wait for
+ * the device.  This call itself may do both.  sidco_release frees the
+ * workspace of `stream` (it waits for work that still uses it).              */
+int sidco_reserve(void *stream, size_t bytes);
+int sidco_release(void *stream);
+
+/* Status bits without a host round trip: the sparsifier calls that follow on
+ * `stream` (single-vector calls; not the batched one) also OR the call's
+ * SIDCO_ST_* bits, SIDCO_ST_OVERFLOW included, into *device_word (device, one
+ * uint32, cleared at the start of each call), so that a consumer on the device,
+ * or a copy the caller already makes, sees them next to out_count.  NULL
+ * switches it off.                                                            */
+int sidco_set_status_word(void *stream, uint32_t *device_word);
 
 /*
  * Tuning knob, no effect on results.  A stage m < M that reads the dense vector
@@ -338,9 +391,10 @@ int sidco_set_workspace(void *device_ptr, size_t bytes);
  */
 int sidco_set_speculation(double theta);
 
-/* Copy the diagnostics of the last call on the current device to host memory.
- * Synchronises `stream`.                                                      */
+/* Copy the diagnostics of the last call on `stream` (current device) to host
+ * memory.  Synchronises `stream`.  sidco_get_diag is the same function.       */
 int sidco_read_diag(void *stream, sidco_diag *host_out);
+int sidco_get_diag(void *stream, sidco_diag *host_out);
 
 /* Per-kernel timing of the calls that follow (HIP events recorded on the
  * call's stream around every kernel).  sidco_get_profile synchronises on the

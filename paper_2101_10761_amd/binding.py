@@ -22,7 +22,9 @@ EXPORTS = [
     "sidco_controller_destroy", "sidco_controller_stages", "sidco_controller_iteration",
     "sidco_controller_last_average", "sidco_controller_compress", "sidco_scatter_add", "sidco_scatter_check",
     "sidco_fit", "sidco_fit_typed", "sidco_fit_result", "sidco_stage_ratios", "sidco_out_capacity",
-    "sidco_workspace_bytes", "sidco_set_workspace", "sidco_set_speculation", "sidco_read_diag", "sidco_set_profiling",
+    "sidco_workspace_bytes", "sidco_set_workspace", "sidco_reserve", "sidco_release", "sidco_set_status_word",
+    "sidco_set_delta1", "sidco_get_diag", "sidco_controller_disturbed",
+    "sidco_set_speculation", "sidco_read_diag", "sidco_set_profiling",
     "sidco_get_profile", "sidco_strerror", "sidco_last_hip_error", "sidco_version", "sidco_shutdown",
 ]
 
@@ -133,6 +135,18 @@ def load() -> C.CDLL:
     lib.sidco_workspace_bytes.restype = C.c_size_t
     lib.sidco_set_workspace.argtypes = [vp, C.c_size_t]
     lib.sidco_set_workspace.restype = C.c_int
+    lib.sidco_reserve.argtypes = [vp, C.c_size_t]
+    lib.sidco_reserve.restype = C.c_int
+    lib.sidco_release.argtypes = [vp]
+    lib.sidco_release.restype = C.c_int
+    lib.sidco_set_status_word.argtypes = [vp, vp]
+    lib.sidco_set_status_word.restype = C.c_int
+    lib.sidco_set_delta1.argtypes = [C.c_double]
+    lib.sidco_set_delta1.restype = C.c_int
+    lib.sidco_get_diag.argtypes = [vp, C.POINTER(Diag)]
+    lib.sidco_get_diag.restype = C.c_int
+    lib.sidco_controller_disturbed.argtypes = [C.c_void_p]
+    lib.sidco_controller_disturbed.restype = C.c_int64
     lib.sidco_set_speculation.argtypes = [C.c_double]
     lib.sidco_set_speculation.restype = C.c_int
     lib.sidco_read_diag.argtypes = [vp, C.POINTER(Diag)]
@@ -196,6 +210,10 @@ def sidco_workspace_bytes(d: int) -> int:
     return int(load().sidco_workspace_bytes(d))
 
 
+def sidco_workspace_bytes_typed(d: int, grad_dtype: int, has_residual: bool) -> int:
+    return int(load().sidco_workspace_bytes_typed(d, grad_dtype, 1 if has_residual else 0))
+
+
 def sidco_set_workspace(buf) -> None:
     """buf: a CUDA uint8 tensor the caller keeps alive, or None to return to library allocation."""
     if buf is None:
@@ -203,6 +221,25 @@ def sidco_set_workspace(buf) -> None:
     else:
         _check(load().sidco_set_workspace(C.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size()),
                "sidco_set_workspace")
+
+
+def sidco_reserve(nbytes: int, stream=None) -> None:
+    """Grows the library's own workspace of `stream` to at least nbytes (see sidco_workspace_bytes)."""
+    _check(load().sidco_reserve(_stream_handle(stream), int(nbytes)), "sidco_reserve")
+
+
+def sidco_release(stream=None) -> None:
+    _check(load().sidco_release(_stream_handle(stream)), "sidco_release")
+
+
+def sidco_set_status_word(word, stream=None) -> None:
+    """word: a CUDA uint32/int32 tensor of one element that receives the status bits of every call on
+    `stream`, or None to switch that off."""
+    _check(load().sidco_set_status_word(_stream_handle(stream), _ptr(word)), "sidco_set_status_word")
+
+
+def sidco_set_delta1(delta1: float) -> None:
+    _check(load().sidco_set_delta1(float(delta1)), "sidco_set_delta1")
 
 
 def sidco_compress(grad, residual, delta: float, dist: int, stages: int, out_idx, out_val, out_count, out_eta,
@@ -386,6 +423,11 @@ class Controller:
     def last_average(self) -> float:
         return load().sidco_controller_last_average(self._h)
 
+    @property
+    def disturbed(self) -> int:
+        """Windows whose count another caller of the same workspace broke (the stages were left as they were)."""
+        return int(load().sidco_controller_disturbed(self._h))
+
     def compress(self, grad, residual, out_idx, out_val, out_count, out_eta, stream=None) -> None:
         import torch
         d = grad.numel()
@@ -450,6 +492,13 @@ def sidco_set_speculation(theta: float) -> None:
 def sidco_read_diag(stream=None) -> Diag:
     diag = Diag()
     _check(load().sidco_read_diag(_stream_handle(stream), C.byref(diag)), "sidco_read_diag")
+    return diag
+
+
+def sidco_get_diag(stream=None) -> Diag:
+    """The same call under its other exported name."""
+    diag = Diag()
+    _check(load().sidco_get_diag(_stream_handle(stream), C.byref(diag)), "sidco_get_diag")
     return diag
 
 

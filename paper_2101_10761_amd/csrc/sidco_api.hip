@@ -2,6 +2,7 @@
 // Declarations and their contracts are in include/sidco.h.
 #include <hip/hip_runtime.h>
 #include <math.h>
+#include <stddef.h>
 #include <stdint.h>
 #include <string.h>
 
@@ -40,7 +41,10 @@ size_t seg_bytes(int64_t d)
     return ntiles * kTile * sizeof(int2);  // one slot per element: no list can overflow
 }
 
-struct DeviceCtx {
+// One workspace and the host's record of the calls made with it.  Library-owned workspaces are per
+// (device, stream): calls on different streams of a device use different ones and may overlap.
+struct WsCtx {
+    void* key = nullptr;       // stream that a library-owned workspace serves
     void* ws = nullptr;        // workspace in use
     size_t ws_bytes = 0;
     bool ws_owned = false;
@@ -51,33 +55,60 @@ struct DeviceCtx {
     int64_t dgc_n_s = 0, dgc_k_s = 0;  // sizes of the last sidco_dgc call
     bool bad_cleared = false;  // the scatter kernels' bad-index flag has been initialised in this workspace
     int64_t last_cap = 0;      // output capacity of the last compress call
+    uint32_t* status_out = nullptr;  // device word that receives the status bits of every call (sidco_set_status_word)
     // shape of the last compress call: a call that repeats it may use the device's record of where the
     // thresholds fell (DevState::theta_seen)
     int64_t sig_d = 0;
     int sig_dist = -1, sig_M = 0;
     double sig_ratios[SIDCO_MAX_STAGES] = {};
     double sig_theta = -1.0;
-    // batched calls: host image of the table the device holds (descriptors and block maps), the
-    // shared arguments it was used with, and the output capacities for the diagnostics
-    std::vector<unsigned char> batch_image;
+    // batched calls: host images of the tables uploaded so far (descriptors and block maps; kept alive
+    // because their upload is asynchronous), which of them the device holds, the shared arguments it was
+    // used with, and the output capacities for the diagnostics
+    std::vector<std::vector<unsigned char>*> batch_images;
+    int batch_cur = -1;
     double batch_delta = -1.0, batch_theta = -1.0;
     int batch_dist = -1, batch_M = 0, batch_n = 0;
     std::vector<int64_t> batch_cap;
     uint32_t fit_nblocks = 0;  // grid, length and law of the last sidco_fit call
     int64_t fit_d = 0;
     int fit_dist = 0;
+
+    // the workspace memory has changed: nothing is known about its contents
+    void forget()
+    {
+        sig_d = 0;
+        bad_cleared = false;
+        dgc_n_s = 0;
+        batch_cur = -1;
+        fit_nblocks = 0;
+    }
+};
+
+struct DeviceCtx {
+    WsCtx shared;                 // the caller's workspace (sidco_set_workspace): serves every stream when set
+    std::vector<WsCtx*> streams;  // library-owned workspaces, one per stream seen
+    WsCtx* last_prof = nullptr;   // workspace of the last profiled call
 };
 
 std::mutex g_mu;
 DeviceCtx g_ctx[kMaxDevices];
 bool g_profiling = false;
 double g_speculation = kSpeculation;
+double g_delta1 = 0.25;               // delta_1 of the default stage schedule (Sec. 4.1)
+unsigned long long g_next_owner = 1;  // ids of the stage controllers
 thread_local char g_hip_msg[256] = "";
 
 int hip_fail(hipError_t e, const char* what)
 {
     snprintf(g_hip_msg, sizeof(g_hip_msg), "%s: %s", what, hipGetErrorString(e));
     return SIDCO_ERR_HIP;
+}
+
+double default_delta1()
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    return g_delta1;
 }
 
 bool aligned4(const void* p) { return ((uintptr_t)p & 3u) == 0; }
@@ -98,7 +129,7 @@ int check_common(const void* grad, const float* residual, int64_t d, int dist, c
 }
 
 // Makes sure the current device has a workspace of at least `need` bytes.
-int ensure_workspace(DeviceCtx& c, size_t need)
+int ensure_workspace(WsCtx& c, size_t need)
 {
     if (c.ws && c.ws_bytes >= need) return SIDCO_OK;
     if (c.ws && !c.ws_owned) return SIDCO_ERR_WORKSPACE;  // caller-provided and too small
@@ -114,10 +145,7 @@ int ensure_workspace(DeviceCtx& c, size_t need)
     c.ws = p;
     c.ws_bytes = need;
     c.ws_owned = true;
-    c.sig_d = 0;  // a fresh workspace holds no record of an earlier call
-    c.bad_cleared = false;
-    c.dgc_n_s = 0;
-    c.batch_image.clear();
+    c.forget();  // a fresh workspace holds no record of an earlier call
     return SIDCO_OK;
 }
 
@@ -142,7 +170,7 @@ void fill_common(Params& p, WorkspaceHead* h, const void* grad, float* residual,
     p.st = &h->st;
 }
 
-int current_ctx(DeviceCtx** c)
+int current_device(DeviceCtx** c)
 {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -150,6 +178,42 @@ int current_ctx(DeviceCtx** c)
     if (dev < 0 || dev >= kMaxDevices) return SIDCO_ERR_ARG;
     *c = &g_ctx[dev];
     return SIDCO_OK;
+}
+
+// The workspace that serves `stream` on the current device: the caller's if one is set, else the
+// library's own for that stream (created empty on first use if `create`).  Caller holds g_mu.
+int pick_ws(void* stream, bool create, WsCtx** out, DeviceCtx** dev_out = nullptr)
+{
+    DeviceCtx* d = nullptr;
+    int rc = current_device(&d);
+    if (rc != SIDCO_OK) return rc;
+    if (dev_out) *dev_out = d;
+    if (d->shared.ws) {
+        *out = &d->shared;
+        return SIDCO_OK;
+    }
+    for (WsCtx* w : d->streams) {
+        if (w->key == stream) {
+            *out = w;
+            return SIDCO_OK;
+        }
+    }
+    if (!create) return SIDCO_ERR_WORKSPACE;
+    WsCtx* w = new (std::nothrow) WsCtx;
+    if (!w) return SIDCO_ERR_ARG;
+    w->key = stream;
+    d->streams.push_back(w);
+    *out = w;
+    return SIDCO_OK;
+}
+
+void free_ws(WsCtx& c)
+{
+    if (c.ws && c.ws_owned) (void)hipFree(c.ws);
+    if (c.ev_made)
+        for (int i = 0; i <= kMaxKernels; ++i) (void)hipEventDestroy(c.ev[i]);
+    for (auto* img : c.batch_images) delete img;
+    c = WsCtx();
 }
 
 // Grid of the last stage's kernel when it reads survivor lists.  The host only knows the expected
@@ -190,7 +254,7 @@ void fill_diag(const DevState& st, int64_t cap, sidco_diag* host_out)
 }
 
 // HIP events of the per-kernel profile, created on first use
-int make_events(DeviceCtx& c)
+int make_events(WsCtx& c)
 {
     if (c.ev_made) return SIDCO_OK;
     for (int i = 0; i <= kMaxKernels; ++i) {
@@ -203,15 +267,17 @@ int make_events(DeviceCtx& c)
 
 size_t acc_bytes(int64_t d) { return seg_bytes(d) / 2; }  // one float per list slot
 
+// `owner`: id of the stage controller that makes the call, 0 for every other caller.
 int run(void* stream, const void* grad, float* residual, int64_t d, int dist, const double* ratios, int M,
         int32_t* out_idx, float* out_val, int64_t out_cap, int32_t* out_count, float* out_eta, bool acc_reset = true,
-        int gt = kGradF32)
+        int gt = kGradF32, unsigned long long owner = 0)
 {
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx* cp = nullptr;
-    int rc = current_ctx(&cp);
+    WsCtx* cp = nullptr;
+    DeviceCtx* dev = nullptr;
+    int rc = pick_ws(stream, true, &cp, &dev);
     if (rc != SIDCO_OK) return rc;
-    DeviceCtx& c = *cp;
+    WsCtx& c = *cp;
     const size_t seg = seg_bytes(d);
     const bool own_acc = gt != kGradF32 && !residual;  // the widened vector needs a home
     rc = ensure_workspace(c, head_bytes() + 2 * seg + (own_acc ? acc_bytes(d) : 0));
@@ -232,6 +298,8 @@ int run(void* stream, const void* grad, float* residual, int64_t d, int dist, co
     p.out_eta = out_eta;
     p.out_cap = out_cap;
     p.acc_reset = acc_reset ? 1 : 0;
+    p.owner = owner;
+    p.status_out = c.status_out;
     c.last_cap = out_cap;
     const double theta = g_speculation;
     bool same_shape = c.sig_d == d && c.sig_dist == dist && c.sig_M == M && c.sig_theta == theta;
@@ -246,6 +314,7 @@ int run(void* stream, const void* grad, float* residual, int64_t d, int dist, co
     if (prof) {
         rc = make_events(c);
         if (rc != SIDCO_OK) return rc;
+        dev->last_prof = &c;
     }
     int k = 0;
     auto mark = [&](const char* name) {
@@ -383,23 +452,43 @@ int sidco_set_workspace(void* device_ptr, size_t bytes)
 {
     if (device_ptr && ((uintptr_t)device_ptr % kAlign) != 0) return SIDCO_ERR_WORKSPACE;
     if (device_ptr && bytes < head_bytes()) return SIDCO_ERR_WORKSPACE;
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
-    if (dev < 0 || dev >= kMaxDevices) return SIDCO_ERR_ARG;
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx& c = g_ctx[dev];
-    if (c.ws && c.ws_owned) {
-        e = hipFree(c.ws);
-        if (e != hipSuccess) return hip_fail(e, "hipFree(workspace)");
-    }
+    DeviceCtx* d = nullptr;
+    int rc = current_device(&d);
+    if (rc != SIDCO_OK) return rc;
+    WsCtx& c = d->shared;
+    if (d->last_prof == &c) d->last_prof = nullptr;
+    free_ws(c);  // events and table images of the previous shared workspace; its memory is the caller's
     c.ws = device_ptr;
     c.ws_bytes = device_ptr ? bytes : 0;
     c.ws_owned = false;
-    c.sig_d = 0;  // a fresh workspace holds no record of an earlier call
-    c.bad_cleared = false;
-    c.dgc_n_s = 0;
-    c.batch_image.clear();
+    return SIDCO_OK;
+}
+
+int sidco_reserve(void* stream, size_t bytes)
+{
+    if (bytes < head_bytes()) bytes = head_bytes();
+    std::lock_guard<std::mutex> lock(g_mu);
+    WsCtx* c = nullptr;
+    int rc = pick_ws(stream, true, &c);
+    if (rc != SIDCO_OK) return rc;
+    return ensure_workspace(*c, bytes);
+}
+
+int sidco_release(void* stream)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceCtx* d = nullptr;
+    int rc = current_device(&d);
+    if (rc != SIDCO_OK) return rc;
+    for (size_t i = 0; i < d->streams.size(); ++i) {
+        if (d->streams[i]->key != stream) continue;
+        if (d->last_prof == d->streams[i]) d->last_prof = nullptr;
+        free_ws(*d->streams[i]);  // hipFree waits for work that still uses the memory
+        delete d->streams[i];
+        d->streams.erase(d->streams.begin() + (long)i);
+        break;
+    }
     return SIDCO_OK;
 }
 
@@ -425,7 +514,7 @@ int sidco_compress(void* stream, const float* grad, float* residual, int64_t d, 
     if (!(delta > 0.0 && delta < 1.0)) return SIDCO_ERR_DELTA;
     if (stages < 1 || stages > SIDCO_MAX_STAGES) return SIDCO_ERR_STAGES;
     double ratios[SIDCO_MAX_STAGES];
-    const int M = sidco_stage_ratios(delta, stages, 0.25, ratios);
+    const int M = sidco_stage_ratios(delta, stages, default_delta1(), ratios);
     if (M < 1) return M;
     return run(stream, grad, residual, d, dist, ratios, M, out_idx, out_val, sidco_out_capacity(d, delta), out_count,
                out_eta);
@@ -443,7 +532,7 @@ int sidco_compress_typed(void* stream, const void* grad, int grad_dtype, float* 
     if (!(delta > 0.0 && delta < 1.0)) return SIDCO_ERR_DELTA;
     if (stages < 1 || stages > SIDCO_MAX_STAGES) return SIDCO_ERR_STAGES;
     double ratios[SIDCO_MAX_STAGES];
-    const int M = sidco_stage_ratios(delta, stages, 0.25, ratios);
+    const int M = sidco_stage_ratios(delta, stages, default_delta1(), ratios);
     if (M < 1) return M;
     return run(stream, grad, residual, d, dist, ratios, M, out_idx, out_val, sidco_out_capacity(d, delta), out_count,
                out_eta, true, grad_dtype == SIDCO_GRAD_F16 ? kGradF16 : kGradBf16);
@@ -475,6 +564,8 @@ struct sidco_controller {
     int dist, stages, max_stages, Q;
     int64_t iteration;      // calls made so far
     double last_avg;        // khat average the last adaptation saw (-1 before the first)
+    unsigned long long id;  // stamps the device state of the controller's calls
+    int64_t disturbed;      // windows whose count another caller of the same workspace broke
 };
 
 int sidco_controller_create(sidco_controller** out, double delta, int dist, int stages, int max_stages, int Q,
@@ -499,6 +590,11 @@ int sidco_controller_create(sidco_controller** out, double delta, int dist, int 
     c->Q = Q;
     c->iteration = 0;
     c->last_avg = -1.0;
+    c->disturbed = 0;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        c->id = g_next_owner++;
+    }
     *out = c;
     return SIDCO_OK;
 }
@@ -510,6 +606,8 @@ int sidco_controller_stages(const sidco_controller* c) { return c ? c->stages : 
 int64_t sidco_controller_iteration(const sidco_controller* c) { return c ? c->iteration : (int64_t)SIDCO_ERR_NULL; }
 
 double sidco_controller_last_average(const sidco_controller* c) { return c ? c->last_avg : -1.0; }
+
+int64_t sidco_controller_disturbed(const sidco_controller* c) { return c ? c->disturbed : (int64_t)SIDCO_ERR_NULL; }
 
 int sidco_controller_compress(sidco_controller* c, void* stream, const float* grad, float* residual, int64_t d,
                               int32_t* out_idx, float* out_val, int32_t* out_count, float* out_eta)
@@ -523,25 +621,29 @@ int sidco_controller_compress(sidco_controller* c, void* stream, const float* gr
     // the count of reported pairs starts over on the first call after an adaptation
     const bool first_of_window = c->iteration % c->Q == 0;
     rc = run(stream, grad, residual, d, c->dist, ratios, M, out_idx, out_val, sidco_out_capacity(d, c->delta),
-             out_count, out_eta, first_of_window);
+             out_count, out_eta, first_of_window, kGradF32, c->id);
     if (rc != SIDCO_OK) return rc;
     c->iteration += 1;
     if (c->iteration % c->Q != 0) return SIDCO_OK;
     // every Q-th call: read the count back (the only host synchronisation of the controller) and adapt
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
     DevState st;
     int64_t cap;
     {
         std::lock_guard<std::mutex> lock(g_mu);
-        DeviceCtx& ctx = g_ctx[dev];
-        cap = ctx.last_cap;
-        e = hipMemcpyAsync(&st, &((WorkspaceHead*)ctx.ws)->st, sizeof(DevState), hipMemcpyDeviceToHost,
-                           (hipStream_t)stream);
+        WsCtx* w = nullptr;
+        rc = pick_ws(stream, false, &w);
+        if (rc != SIDCO_OK) return rc;
+        cap = w->last_cap;
+        hipError_t e = hipMemcpyAsync(&st, &((WorkspaceHead*)w->ws)->st, sizeof(DevState), hipMemcpyDeviceToHost,
+                                      (hipStream_t)stream);
         if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(controller)");
         e = hipStreamSynchronize((hipStream_t)stream);
         if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    }
+    if (st.disturbed || st.owner != c->id) {
+        // another caller used this workspace inside the window: its count is not this vector's, keep M
+        c->disturbed += 1;
+        return SIDCO_OK;
     }
     const unsigned long long last = st.selected_ctr < (unsigned long long)cap ? st.selected_ctr : (unsigned long long)cap;
     const double avg = (double)(st.khat_sum + last) / (double)c->Q;
@@ -558,8 +660,8 @@ int sidco_scatter_add(void* stream, float* dense, int64_t d, const int32_t* idx,
     if (d < 1 || d > (int64_t)INT32_MAX || capacity < 1 || capacity > (int64_t)INT32_MAX) return SIDCO_ERR_SIZE;
     if (!aligned4(dense) || !aligned4(idx) || !aligned4(val) || !aligned4(count)) return SIDCO_ERR_ALIGN;
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx* cp = nullptr;
-    int rc = current_ctx(&cp);
+    WsCtx* cp = nullptr;
+    int rc = pick_ws(stream, true, &cp);
     if (rc != SIDCO_OK) return rc;
     rc = ensure_workspace(*cp, cp->ws ? cp->ws_bytes : head_bytes());  // the head alone is enough here
     if (rc != SIDCO_OK) return rc;
@@ -577,8 +679,9 @@ int sidco_scatter_add(void* stream, float* dense, int64_t d, const int32_t* idx,
 int sidco_scatter_check(void* stream)
 {
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx* cp = nullptr;
-    int rc = current_ctx(&cp);
+    WsCtx* cp = nullptr;
+    int rc = pick_ws(stream, false, &cp);
+    if (rc == SIDCO_ERR_WORKSPACE) return 0;  // no scatter call has been made on this stream
     if (rc != SIDCO_OK) return rc;
     if (!cp->ws || !cp->bad_cleared) return 0;
     uint32_t bad = 0;
@@ -688,45 +791,56 @@ int sidco_compress_batched(void* stream, const float* grad, float* residual, con
     if (!(delta > 0.0 && delta < 1.0)) return SIDCO_ERR_DELTA;
     if (stages < 1 || stages > SIDCO_MAX_STAGES) return SIDCO_ERR_STAGES;
     double ratios[SIDCO_MAX_STAGES];
-    const int M = sidco_stage_ratios(delta, stages, 0.25, ratios);
+    const int M = sidco_stage_ratios(delta, stages, default_delta1(), ratios);
     if (M < 1) return M;
     BatchPlan pl;
     int rc = plan_batch(offsets, n, out_offsets, pl);
     if (rc != SIDCO_OK) return rc;
 
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx* cp = nullptr;
-    rc = current_ctx(&cp);
+    WsCtx* cp = nullptr;
+    rc = pick_ws(stream, true, &cp);
     if (rc != SIDCO_OK) return rc;
-    DeviceCtx& c = *cp;
+    WsCtx& c = *cp;
     rc = ensure_workspace(c, head_bytes() + 2 * pl.slots * sizeof(int2));
     if (rc != SIDCO_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     WorkspaceHead* h = (WorkspaceHead*)c.ws;
     const double theta = g_speculation;
 
-    // The table on the device: uploaded when it differs from the one already there (the first call with a
-    // layout; synchronous).  A call that repeats the previous one, shared arguments included, may use the
-    // vectors' threshold hints.
-    const size_t desc_bytes = (size_t)n * sizeof(TensorDesc), map_bytes = kMaxBlocks * sizeof(uint16_t);
-    std::vector<unsigned char> image(desc_bytes + 2 * map_bytes);
-    memcpy(image.data(), pl.desc.data(), desc_bytes);
-    memcpy(image.data() + desc_bytes, pl.map.data(), map_bytes);
-    memcpy(image.data() + desc_bytes + map_bytes, pl.fmap.data(), map_bytes);
-    const bool same_table = image == c.batch_image;
+    // The table on the device (descriptors and block maps, one contiguous piece of BatchTable) is uploaded
+    // when it differs from the one already there, asynchronously and in stream order, from a host image
+    // that the library keeps for good (the copy may still be reading it when this call returns, and a
+    // caller may have captured it into a graph).  A call that repeats the previous one, shared arguments
+    // included, may use the vectors' threshold hints.
+    constexpr size_t table_bytes = sizeof(BatchTable) - offsetof(BatchTable, desc);
+    std::vector<unsigned char> image(table_bytes, 0);
+    memcpy(image.data(), pl.desc.data(), (size_t)n * sizeof(TensorDesc));
+    memcpy(image.data() + (offsetof(BatchTable, map) - offsetof(BatchTable, desc)), pl.map.data(),
+           kMaxBlocks * sizeof(uint16_t));
+    memcpy(image.data() + (offsetof(BatchTable, fmap) - offsetof(BatchTable, desc)), pl.fmap.data(),
+           kMaxBlocks * sizeof(uint16_t));
+    const bool same_table = c.batch_cur >= 0 && image == *c.batch_images[(size_t)c.batch_cur];
     const bool same_shape = same_table && c.batch_delta == delta && c.batch_theta == theta && c.batch_dist == dist &&
                             c.batch_M == M;
     if (!same_table) {
-        hipError_t e = hipStreamSynchronize(s);  // an earlier call on the stream may still read the old table
-        if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
-        e = hipMemcpy(h->batch.desc, pl.desc.data(), desc_bytes, hipMemcpyHostToDevice);
-        if (e == hipSuccess) e = hipMemcpy(h->batch.map, pl.map.data(), map_bytes, hipMemcpyHostToDevice);
-        if (e == hipSuccess) e = hipMemcpy(h->batch.fmap, pl.fmap.data(), map_bytes, hipMemcpyHostToDevice);
-        if (e != hipSuccess) {
-            c.batch_image.clear();
-            return hip_fail(e, "hipMemcpy(batch table)");
+        int found = -1;
+        for (size_t i = 0; i < c.batch_images.size() && found < 0; ++i)
+            if (*c.batch_images[i] == image) found = (int)i;
+        if (found < 0) {
+            auto* keep = new (std::nothrow) std::vector<unsigned char>();
+            if (!keep) return SIDCO_ERR_ARG;
+            keep->swap(image);
+            c.batch_images.push_back(keep);
+            found = (int)c.batch_images.size() - 1;
         }
-        c.batch_image.swap(image);
+        hipError_t e = hipMemcpyAsync(h->batch.desc, c.batch_images[(size_t)found]->data(), table_bytes,
+                                      hipMemcpyHostToDevice, s);
+        if (e != hipSuccess) {
+            c.batch_cur = -1;
+            return hip_fail(e, "hipMemcpyAsync(batch table)");
+        }
+        c.batch_cur = found;
     }
     c.batch_delta = delta;
     c.batch_theta = theta;
@@ -813,11 +927,11 @@ int sidco_read_diag_batched(void* stream, int t, sidco_diag* host_out)
 {
     if (!host_out) return SIDCO_ERR_NULL;
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx* cp = nullptr;
-    int rc = current_ctx(&cp);
+    WsCtx* cp = nullptr;
+    int rc = pick_ws(stream, false, &cp);
     if (rc != SIDCO_OK) return rc;
-    DeviceCtx& c = *cp;
-    if (!c.ws || c.batch_image.empty()) return SIDCO_ERR_WORKSPACE;
+    WsCtx& c = *cp;
+    if (!c.ws || c.batch_cur < 0) return SIDCO_ERR_WORKSPACE;
     if (t < 0 || t >= c.batch_n) return SIDCO_ERR_ARG;
     hipStream_t s = (hipStream_t)stream;
     DevState st;
@@ -840,10 +954,11 @@ int sidco_topk(void* stream, const float* grad, float* residual, int64_t d, int6
         return SIDCO_ERR_ALIGN;
     if (residual && (const void*)residual == (const void*)grad) return SIDCO_ERR_ARG;
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx* cp = nullptr;
-    int rc = current_ctx(&cp);
+    WsCtx* cp = nullptr;
+    DeviceCtx* dev = nullptr;
+    int rc = pick_ws(stream, true, &cp, &dev);
     if (rc != SIDCO_OK) return rc;
-    DeviceCtx& c = *cp;
+    WsCtx& c = *cp;
     rc = ensure_workspace(c, head_bytes() + 2 * seg_bytes(d));
     if (rc != SIDCO_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
@@ -876,6 +991,7 @@ int sidco_topk(void* stream, const float* grad, float* residual, int64_t d, int6
     if (prof) {
         rc = make_events(c);
         if (rc != SIDCO_OK) return rc;
+        dev->last_prof = &c;
     }
     int kn = 0;
     auto mark = [&](const char* name) {
@@ -943,10 +1059,11 @@ int sidco_dgc(void* stream, const float* grad, float* residual, int64_t d, doubl
     int64_t n_s, k_s, k;
     if (!dgc_sizes(d, delta, sample_ratio, &n_s, &k_s, &k)) return SIDCO_ERR_DELTA;
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx* cp = nullptr;
-    rc = current_ctx(&cp);
+    WsCtx* cp = nullptr;
+    DeviceCtx* dev = nullptr;
+    rc = pick_ws(stream, true, &cp, &dev);
     if (rc != SIDCO_OK) return rc;
-    DeviceCtx& c = *cp;
+    WsCtx& c = *cp;
     rc = ensure_workspace(c, head_bytes() + 2 * seg_bytes(d));
     if (rc != SIDCO_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
@@ -1003,6 +1120,7 @@ int sidco_dgc(void* stream, const float* grad, float* residual, int64_t d, doubl
     if (prof) {
         rc = make_events(c);
         if (rc != SIDCO_OK) return rc;
+        dev->last_prof = &c;
     }
     int kn = 0;
     auto mark = [&](const char* name) {
@@ -1050,8 +1168,8 @@ int sidco_dgc_result(void* stream, int64_t* host_out)
 {
     if (!host_out) return SIDCO_ERR_NULL;
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx* cp = nullptr;
-    int rc = current_ctx(&cp);
+    WsCtx* cp = nullptr;
+    int rc = pick_ws(stream, false, &cp);
     if (rc != SIDCO_OK) return rc;
     if (!cp->ws || cp->dgc_n_s == 0) return SIDCO_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
@@ -1078,8 +1196,8 @@ int sidco_fit_typed(void* stream, const void* grad, int grad_dtype, float* resid
     if (((uintptr_t)grad & (f32 ? 3u : 1u)) != 0 || !aligned4(residual)) return SIDCO_ERR_ALIGN;
     if (residual && (const void*)residual == grad) return SIDCO_ERR_ARG;
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx* cp = nullptr;
-    int rc = current_ctx(&cp);
+    WsCtx* cp = nullptr;
+    int rc = pick_ws(stream, true, &cp);
     if (rc != SIDCO_OK) return rc;
     const bool own_acc = !f32 && !residual;
     rc = ensure_workspace(*cp, head_bytes() + 2 * seg_bytes(d) + (own_acc ? acc_bytes(d) : 0));
@@ -1109,8 +1227,8 @@ int sidco_fit_result(void* stream, double* host_sums)
 {
     if (!host_sums) return SIDCO_ERR_NULL;
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx* cp = nullptr;
-    int rc = current_ctx(&cp);
+    WsCtx* cp = nullptr;
+    int rc = pick_ws(stream, false, &cp);
     if (rc != SIDCO_OK) return rc;
     if (!cp->ws || cp->fit_nblocks == 0) return SIDCO_ERR_WORKSPACE;
     static thread_local double part[4 * kMaxBlocks];
@@ -1132,20 +1250,40 @@ int sidco_fit_result(void* stream, double* host_sums)
 int sidco_read_diag(void* stream, sidco_diag* host_out)
 {
     if (!host_out) return SIDCO_ERR_NULL;
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
-    if (dev < 0 || dev >= kMaxDevices) return SIDCO_ERR_ARG;
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx& c = g_ctx[dev];
+    WsCtx* cp = nullptr;
+    int rc = pick_ws(stream, false, &cp);
+    if (rc != SIDCO_OK) return rc;
+    WsCtx& c = *cp;
     if (!c.ws) return SIDCO_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     DevState st;
-    e = hipMemcpyAsync(&st, &((WorkspaceHead*)c.ws)->st, sizeof(DevState), hipMemcpyDeviceToHost, s);
+    hipError_t e = hipMemcpyAsync(&st, &((WorkspaceHead*)c.ws)->st, sizeof(DevState), hipMemcpyDeviceToHost, s);
     if (e != hipSuccess) return hip_fail(e, "hipMemcpyAsync(diag)");
     e = hipStreamSynchronize(s);
     if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
     fill_diag(st, c.last_cap, host_out);
+    return SIDCO_OK;
+}
+
+int sidco_get_diag(void* stream, sidco_diag* host_out) { return sidco_read_diag(stream, host_out); }
+
+int sidco_set_delta1(double delta1)
+{
+    if (!(delta1 > 0.0 && delta1 < 1.0)) return SIDCO_ERR_DELTA;
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_delta1 = delta1;
+    return SIDCO_OK;
+}
+
+int sidco_set_status_word(void* stream, uint32_t* device_word)
+{
+    if (!aligned4(device_word)) return SIDCO_ERR_ALIGN;
+    std::lock_guard<std::mutex> lock(g_mu);
+    WsCtx* c = nullptr;
+    int rc = pick_ws(stream, true, &c);
+    if (rc != SIDCO_OK) return rc;
+    c->status_out = device_word;
     return SIDCO_OK;
 }
 
@@ -1167,14 +1305,13 @@ int sidco_set_profiling(int enable)
 int sidco_get_profile(float* ms, const char** names, int cap)
 {
     if (!ms || cap < 1) return SIDCO_ERR_NULL;
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
-    if (dev < 0 || dev >= kMaxDevices) return SIDCO_ERR_ARG;
     std::lock_guard<std::mutex> lock(g_mu);
-    DeviceCtx& c = g_ctx[dev];
-    if (c.prof_n == 0) return 0;
-    e = hipEventSynchronize(c.ev[c.prof_n]);
+    DeviceCtx* d = nullptr;
+    int rc = current_device(&d);
+    if (rc != SIDCO_OK) return rc;
+    if (!d->last_prof || d->last_prof->prof_n == 0) return 0;
+    WsCtx& c = *d->last_prof;
+    hipError_t e = hipEventSynchronize(c.ev[c.prof_n]);
     if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
     for (int i = 0; i < c.prof_n && i < cap; ++i) {
         e = hipEventElapsedTime(&ms[i], c.ev[i], c.ev[i + 1]);
@@ -1211,13 +1348,16 @@ void sidco_shutdown(void)
     int cur = 0;
     const bool have_cur = hipGetDevice(&cur) == hipSuccess;
     for (int dev = 0; dev < kMaxDevices; ++dev) {
-        DeviceCtx& c = g_ctx[dev];
-        if (!c.ws && !c.ev_made) continue;
+        DeviceCtx& d = g_ctx[dev];
+        if (!d.shared.ws && !d.shared.ev_made && d.streams.empty()) continue;
         if (hipSetDevice(dev) != hipSuccess) continue;
-        if (c.ws && c.ws_owned) (void)hipFree(c.ws);
-        if (c.ev_made)
-            for (int i = 0; i <= kMaxKernels; ++i) (void)hipEventDestroy(c.ev[i]);
-        c = DeviceCtx();
+        free_ws(d.shared);
+        for (WsCtx* w : d.streams) {
+            free_ws(*w);
+            delete w;
+        }
+        d.streams.clear();
+        d.last_prof = nullptr;
     }
     if (have_cur) (void)hipSetDevice(cur);
 }

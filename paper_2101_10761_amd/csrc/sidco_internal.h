@@ -69,6 +69,10 @@ struct DevState {
     unsigned long long selected_ctr;              // pairs selected by the last stage (cleared by k_fit)
     uint32_t overflow;                            // 1 if selected_ctr exceeded the output capacity
     uint32_t bad_index;                           // sidco_scatter_add met an index outside [0, d) since the last check
+    // who made the last call with this state (id of a stage controller, 0 otherwise), and whether a call
+    // of someone else fell into the current window of the controller's count
+    unsigned long long owner;
+    uint32_t disturbed;
 };
 
 // Kernel arguments (passed by value).
@@ -90,6 +94,7 @@ struct Params {
     int vec_ok;             // all dense buffers aligned for 4-element accesses (16 bytes; 8 for a 16-bit gradient)
     int reverse;            // a dense stage kernel walks every wave's tiles from the last to the first
     int acc_reset;          // k_fit: start the controller's count of reported pairs over instead of adding to it
+    unsigned long long owner;  // id of the stage controller that makes the call, 0 otherwise
     int dist;
     int M;
     int stage;              // 1-based stage a k_compact launch works for
@@ -112,6 +117,7 @@ struct Params {
     int32_t* out_count;
     float* out_eta;
     int64_t out_cap;
+    uint32_t* status_out;   // NULL, or a device word that receives the call's status bits as well
 };
 
 // ---- exact Top-k comparator (sidco_topk.hip) ----

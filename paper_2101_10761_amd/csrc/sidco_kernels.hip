@@ -416,10 +416,15 @@ __device__ __forceinline__ void fit_reset_state(const Params& p)
     const unsigned long long prev_sel = p.st->selected_ctr;
     const unsigned long long prev_cap = (unsigned long long)p.st->prev_cap;
     p.st->khat_sum = p.acc_reset ? 0ull : p.st->khat_sum + (prev_sel < prev_cap ? prev_sel : prev_cap);
+    // a window of a controller's count is only its own if every call since its start was that controller's
+    if (p.acc_reset) p.st->disturbed = 0;
+    else if (p.st->owner != p.owner) p.st->disturbed = 1;
+    p.st->owner = p.owner;
     p.st->prev_cap = (long long)p.out_cap;
     p.st->selected_ctr = 0;
     p.st->overflow = 0;
     if (p.out_count) *p.out_count = 0;
+    if (p.status_out) *p.status_out = 0;
 }
 
 // one element through the guarded scalar path
@@ -1013,10 +1018,15 @@ __device__ __forceinline__ void final_body(const Params& p, Blk b)
         sh_base = base;
         const unsigned long long end = base + tot;
         atomicMax(p.out_count, (int32_t)(end < cap ? end : cap));
-        if (end > cap) p.st->overflow = 1u;  // every writer stores the same value
+        if (end > cap) {
+            p.st->overflow = 1u;  // every writer stores the same value
+            if (p.status_out) atomicOr(p.status_out, kStOverflow);
+        }
         if (b.id == 0) {
             *p.out_eta = eta;
-            p.st->diag.status = p.st->status_after[p.M];  // written by this thread in the prologue
+            const uint32_t status = p.st->status_after[p.M];  // written by this thread in the prologue
+            p.st->diag.status = status;
+            if (p.status_out && status) atomicOr(p.status_out, status);
         }
     }
     __syncthreads();
@@ -1101,7 +1111,9 @@ __device__ __forceinline__ void gather_body(const Params& p, Blk b)
         *p.out_eta = p.st->diag.eta[p.M - 1];
         p.st->selected_ctr = total;
         p.st->overflow = total > cap ? 1u : 0u;
-        p.st->diag.status = p.st->status_after[p.M];
+        const uint32_t status = p.st->status_after[p.M];
+        p.st->diag.status = status;
+        if (p.status_out) *p.status_out = status | (total > cap ? kStOverflow : 0u);
     }
     if (!active) return;
     // offset of this wave inside the block: counts of the block's earlier waves

@@ -31,58 +31,83 @@ class GpuResult:
     selected: int
 
 
-def run_gpu(g, r, dist, ratios, cap=None, *, grad_offset=0, res_offset=0, use_default_schedule=None):
-    """Runs one call on cuda:0.  grad_offset / res_offset (in elements) place the vectors at unaligned
+class GpuCall:
+    """One sparsifier call on cuda:0 in three steps - buffers, enqueue on a stream, results - so that a test
+    can have several calls in flight.  grad_offset / res_offset (in elements) place the vectors at unaligned
     addresses.  use_default_schedule=(delta, stages) calls sidco_compress instead of sidco_compress_ex."""
-    import torch
-    import paper_2101_10761_amd as sidco
 
-    dev = torch.device("cuda:0")
-    d = g.size
-    gbuf = torch.zeros(d + grad_offset + 8, dtype=torch.float32, device=dev)
-    gt = gbuf[grad_offset:grad_offset + d]
-    gt.copy_(torch.from_numpy(g))
-    rt = None
-    if r is not None:
-        rbuf = torch.zeros(d + res_offset + 8, dtype=torch.float32, device=dev)
-        rt = rbuf[res_offset:res_offset + d]
-        rt.copy_(torch.from_numpy(r))
-    if use_default_schedule is not None:
-        delta, stages = use_default_schedule
-        cap = sidco.sidco_out_capacity(d, delta)
-    elif cap is None:
-        cap = d
-    guard = 64
-    out_idx = torch.full((cap + guard,), -7, dtype=torch.int32, device=dev)
-    out_val = torch.full((cap + guard,), 7.0, dtype=torch.float32, device=dev)
-    out_count = torch.full((1,), -1, dtype=torch.int32, device=dev)
-    out_eta = torch.full((1,), -1.0, dtype=torch.float32, device=dev)
-    if use_default_schedule is not None:
-        sidco.sidco_compress(gt, rt, delta, dist, stages, out_idx[:cap], out_val[:cap], out_count, out_eta)
-    else:
-        sidco.sidco_compress_ex(gt, rt, dist, list(ratios), out_idx[:cap], out_val[:cap], out_count, out_eta)
-    diag = sidco.sidco_read_diag()
-    torch.cuda.synchronize()
-    k = int(out_count.item())
-    assert 0 <= k <= cap
-    # nothing may be written past the count / the capacity, and the gradient is read-only
-    assert torch.all(out_idx[cap:] == -7) and torch.all(out_val[cap:] == 7.0)
-    assert torch.all(out_idx[k:cap] == -7)
-    np.testing.assert_array_equal(gt.cpu().numpy().view(np.uint32), g.view(np.uint32))
-    if grad_offset:
-        assert torch.all(gbuf[:grad_offset] == 0)
-    assert torch.all(gbuf[grad_offset + d:] == 0)
-    if rt is not None:
-        assert torch.all(rbuf[res_offset + d:] == 0)
-        if res_offset:
-            assert torch.all(rbuf[:res_offset] == 0)
-    M = diag.stages
-    return GpuResult(
-        idx=out_idx[:k].cpu().numpy(), val=out_val[:k].cpu().numpy(), count=k, eta=float(out_eta.item()),
-        residual=None if rt is None else rt.cpu().numpy(),
-        etas=np.array(diag.eta[:M], dtype=np.float32), n=np.array(diag.n[:M], dtype=np.int64),
-        stats=np.array([[diag.stats[m][q] for q in range(3)] for m in range(M)]), status=diag.status,
-        selected=diag.selected)
+    def __init__(self, g, r, dist, ratios, cap=None, *, grad_offset=0, res_offset=0, use_default_schedule=None):
+        import torch
+        import paper_2101_10761_amd as sidco
+
+        dev = torch.device("cuda:0")
+        self.g, self.dist, self.ratios = g, dist, ratios
+        self.grad_offset, self.res_offset, self.default = grad_offset, res_offset, use_default_schedule
+        d = g.size
+        self.gbuf = torch.zeros(d + grad_offset + 8, dtype=torch.float32, device=dev)
+        self.gt = self.gbuf[grad_offset:grad_offset + d]
+        self.gt.copy_(torch.from_numpy(g))
+        self.rt = self.rbuf = None
+        if r is not None:
+            self.rbuf = torch.zeros(d + res_offset + 8, dtype=torch.float32, device=dev)
+            self.rt = self.rbuf[res_offset:res_offset + d]
+            self.rt.copy_(torch.from_numpy(r))
+        if use_default_schedule is not None:
+            cap = sidco.sidco_out_capacity(d, use_default_schedule[0])
+        elif cap is None:
+            cap = d
+        self.cap = cap
+        guard = 64
+        self.out_idx = torch.full((cap + guard,), -7, dtype=torch.int32, device=dev)
+        self.out_val = torch.full((cap + guard,), 7.0, dtype=torch.float32, device=dev)
+        self.out_count = torch.full((1,), -1, dtype=torch.int32, device=dev)
+        self.out_eta = torch.full((1,), -1.0, dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+
+    def launch(self, stream=None):
+        import paper_2101_10761_amd as sidco
+        cap = self.cap
+        if self.default is not None:
+            delta, stages = self.default
+            sidco.sidco_compress(self.gt, self.rt, delta, self.dist, stages, self.out_idx[:cap], self.out_val[:cap],
+                                 self.out_count, self.out_eta, stream=stream)
+        else:
+            sidco.sidco_compress_ex(self.gt, self.rt, self.dist, list(self.ratios), self.out_idx[:cap], self.out_val[:cap],
+                                    self.out_count, self.out_eta, stream=stream)
+        return self
+
+    def collect(self, stream=None):
+        import torch
+        import paper_2101_10761_amd as sidco
+        diag = sidco.sidco_read_diag(stream)
+        torch.cuda.synchronize()
+        cap, g, d = self.cap, self.g, self.g.size
+        k = int(self.out_count.item())
+        assert 0 <= k <= cap
+        # nothing may be written past the count / the capacity, and the gradient is read-only
+        assert torch.all(self.out_idx[cap:] == -7) and torch.all(self.out_val[cap:] == 7.0)
+        assert torch.all(self.out_idx[k:cap] == -7)
+        np.testing.assert_array_equal(self.gt.cpu().numpy().view(np.uint32), g.view(np.uint32))
+        if self.grad_offset:
+            assert torch.all(self.gbuf[:self.grad_offset] == 0)
+        assert torch.all(self.gbuf[self.grad_offset + d:] == 0)
+        if self.rt is not None:
+            assert torch.all(self.rbuf[self.res_offset + d:] == 0)
+            if self.res_offset:
+                assert torch.all(self.rbuf[:self.res_offset] == 0)
+        M = diag.stages
+        return GpuResult(
+            idx=self.out_idx[:k].cpu().numpy(), val=self.out_val[:k].cpu().numpy(), count=k,
+            eta=float(self.out_eta.item()), residual=None if self.rt is None else self.rt.cpu().numpy(),
+            etas=np.array(diag.eta[:M], dtype=np.float32), n=np.array(diag.n[:M], dtype=np.int64),
+            stats=np.array([[diag.stats[m][q] for q in range(3)] for m in range(M)]), status=diag.status,
+            selected=diag.selected)
+
+
+def run_gpu(g, r, dist, ratios, cap=None, *, grad_offset=0, res_offset=0, use_default_schedule=None):
+    """Runs one call on cuda:0 on the current stream and returns its results."""
+    return GpuCall(g, r, dist, ratios, cap, grad_offset=grad_offset, res_offset=res_offset,
+                   use_default_schedule=use_default_schedule).launch().collect()
 
 
 def _close(a, b, rtol=STATS_RTOL, atol=0.0):

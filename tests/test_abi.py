@@ -209,3 +209,8 @@ def test_typed_argument_errors(lib):
     assert w(1_000_000, 0, 0) == base and w(1_000_000, 1, 1) == base and w(1_000_000, 2, 1) == base
     assert w(1_000_000, 1, 0) == w(1_000_000, 2, 0) >= base + 4 * 1_000_000
     assert w(0, 1, 0) == 0 and w(1000, 7, 0) == 0
+
+
+def test_new_setters_reject_bad_arguments(lib):
+    assert lib.sidco_set_delta1(0.0) == -3 and lib.sidco_set_delta1(1.0) == -3 and lib.sidco_set_delta1(float("nan")) == -3
+    assert lib.sidco_controller_disturbed(None) == -1

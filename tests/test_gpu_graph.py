@@ -33,13 +33,11 @@ def test_captured_call_replays_correctly(oracle, d, dist, delta, stages):
     host_g = _vec(1, d)
     host_r = np.zeros(d, np.float32)
     g.copy_(torch.from_numpy(host_g))
-    # eager call first: the workspace gets allocated outside the capture
-    sidco.sidco_compress(g, r, delta, dist, stages, out_idx, out_val, out_count, out_eta)
-    torch.cuda.synchronize()
-    r.zero_()
-
     graph = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
+    # the capturing stream's workspace is allocated outside the capture
+    sidco.sidco_reserve(sidco.sidco_workspace_bytes(d), stream=side)
+    torch.cuda.synchronize()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
         graph.capture_begin()
@@ -54,7 +52,7 @@ def test_captured_call_replays_correctly(oracle, d, dist, delta, stages):
         out_idx.fill_(-7)
         graph.replay()
         torch.cuda.synchronize()
-        diag = sidco.sidco_read_diag()
+        diag = sidco.sidco_read_diag(stream=side)
         k = int(out_count.item())
         M = diag.stages
         res = GpuResult(idx=out_idx[:k].cpu().numpy(), val=out_val[:k].cpu().numpy(), count=k,
@@ -65,6 +63,7 @@ def test_captured_call_replays_correctly(oracle, d, dist, delta, stages):
         ref = check_parity(oracle, host_g, host_r, dist, ratios, res, capacity=cap, label=f"replay {it} d {d}")
         host_r = ref.residual
         assert torch.all(out_idx[k:] == -7)
-        # eager work of the library between replays must not disturb the graph's next replay
-        sidco.sidco_fit(g, None, dist)
+        # eager work of the library on the same workspace between replays must not disturb the next replay
+        sidco.sidco_fit(g, None, dist, stream=side)
         torch.cuda.synchronize()
+    sidco.sidco_release(stream=side)
