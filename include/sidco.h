@@ -20,9 +20,9 @@
  * spins on the device, and an enqueueing call synchronises with the host in
  * one case only: when the stream's workspace has to grow (first use, or a
  * longer vector than before), it is freed and allocated again, which waits for
- * the device.  sidco_reserve moves that out of the enqueueing calls.
- * (sidco_controller_compress also reads one counter back on every Q-th call;
- * that is its contract.)
+ * the device.  sidco_reserve moves that out of the enqueueing calls, and
+ * sidco_compress_static never allocates at all.  (sidco_controller_compress also
+ * reads one counter back on every Q-th call; that is its contract.)
  *
  * Results are deterministic for a given history of calls on a workspace: the
  * same inputs after the same previous calls give the same bits.  Across
@@ -137,6 +137,34 @@ typedef struct sidco_diag {
 int sidco_compress(void *stream, const float *grad, float *residual, int64_t d,
                    double delta, int dist, int stages,
                    int32_t *out_idx, float *out_val, int32_t *out_count, float *out_eta);
+
+/*
+ * sidco_compress for callers that cannot allocate device memory or must not
+ * trigger an allocation: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same results, same kernels;
+ * the workspace is a fixed array inside the library's device code (about 34 MB,
+ * resident in every GPU the library is loaded on until the process ends), so the
+ * call makes no hipMalloc / hipFree and nothing that allocates, on any call,
+ * the first included.  Limits: d <= sidco_static_max_elements() = 2,097,152
+ * (SIDCO_ERR_SIZE beyond it, with the limit in sidco_last_hip_error), fp32
+ * gradients, the default stage schedule, no per-kernel profiling.  All calls
+ * on a GPU share that GPU's one array, on whatever stream: calls that overlap
+ * in time race and must be serialised by the caller.  The array keeps what the
+ * previous call left; the first kernel of every call resets the per-call
+ * counters, and the lists are always written before they are read, so nothing
+ * carries over except the threshold hints of a repeated shape (performance only).
+ * sidco_read_diag does not cover these calls.
+ * sidco_static_init looks the array's address up on the current device (the HIP
+ * runtime maps the array into the device on that first access); the first
+ * sidco_compress_static on a device does the same if it has not been called, so
+ * a caller that captures or forbids allocation from the start calls it once
+ * per device beforehand.
+ */
+int sidco_compress_static(void *stream, const float *grad, float *residual, int64_t d,
+                          double delta, int dist, int stages,
+                          int32_t *out_idx, float *out_val, int32_t *out_count, float *out_eta);
+int64_t sidco_static_max_elements(void);
+int sidco_static_init(void);
 
 /*
  * Same computation with explicit stage ratios delta_1..delta_M (host array,
@@ -344,8 +372,8 @@ int sidco_stage_ratios(double delta, int stages, double delta1, double *ratios);
 int64_t sidco_out_capacity(int64_t d, double delta);
 
 /* delta_1 of the default stage schedule used by sidco_compress,
- * sidco_compress_typed and sidco_compress_batched, for the calls that follow on
- * every device: 0 < delta1 < 1, initially 0.25 (Sec. 4.1).
+ * sidco_compress_static, sidco_compress_typed and sidco_compress_batched, for the
+ * calls that follow on every device: 0 < delta1 < 1, initially 0.25 (Sec. 4.1).
  * Explicit ratios per call: sidco_compress_ex.                                */
 int sidco_set_delta1(double delta1);
 

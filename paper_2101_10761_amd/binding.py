@@ -17,7 +17,7 @@ DIST_EXP, DIST_GAMMA_GPD, DIST_GPD = 0, 1, 2
 ST_NONFINITE, ST_VAR_ZERO, ST_GAMMA_S, ST_GAMMA_CLAMP, ST_STOPPED, ST_OVERFLOW, ST_FALLBACK = 1, 2, 4, 8, 16, 32, 64
 
 EXPORTS = [
-    "sidco_compress", "sidco_compress_typed", "sidco_workspace_bytes_typed", "sidco_compress_ex", "sidco_compress_batched", "sidco_batched_out_offsets",
+    "sidco_compress", "sidco_compress_static", "sidco_static_max_elements", "sidco_static_init", "sidco_compress_typed", "sidco_workspace_bytes_typed", "sidco_compress_ex", "sidco_compress_batched", "sidco_batched_out_offsets",
     "sidco_workspace_bytes_batched", "sidco_read_diag_batched", "sidco_topk", "sidco_dgc", "sidco_dgc_sizes", "sidco_dgc_result", "sidco_adapt_stages", "sidco_controller_create",
     "sidco_controller_destroy", "sidco_controller_stages", "sidco_controller_iteration",
     "sidco_controller_last_average", "sidco_controller_compress", "sidco_scatter_add", "sidco_scatter_check",
@@ -47,8 +47,9 @@ class SidcoError(RuntimeError):
     def __init__(self, code: int, where: str):
         lib = load()
         msg = lib.sidco_strerror(code).decode()
-        if code == -7:
-            msg += " (" + lib.sidco_last_hip_error().decode() + ")"
+        detail = lib.sidco_last_hip_error().decode()
+        if code == -7 or (code == -2 and detail.startswith("sidco_compress_static")):
+            msg += " (" + detail + ")"
         super().__init__(f"{where}: error {code}: {msg}")
         self.code = code
 
@@ -76,6 +77,12 @@ def load() -> C.CDLL:
     vp, f32p, i32p, f64p = C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_double)
     lib.sidco_compress.argtypes = [vp, f32p, f32p, C.c_int64, C.c_double, C.c_int, C.c_int, i32p, f32p, i32p, f32p]
     lib.sidco_compress.restype = C.c_int
+    lib.sidco_compress_static.argtypes = [vp, f32p, f32p, C.c_int64, C.c_double, C.c_int, C.c_int, i32p, f32p, i32p, f32p]
+    lib.sidco_compress_static.restype = C.c_int
+    lib.sidco_static_init.argtypes = []
+    lib.sidco_static_init.restype = C.c_int
+    lib.sidco_static_max_elements.argtypes = []
+    lib.sidco_static_max_elements.restype = C.c_int64
     lib.sidco_compress_ex.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int, f64p, C.c_int, i32p, f32p, C.c_int64,
                                       i32p, f32p]
     lib.sidco_compress_ex.restype = C.c_int
@@ -257,6 +264,32 @@ def sidco_compress(grad, residual, delta: float, dist: int, stages: int, out_idx
     _check_tensor(out_eta, torch.float32, "out_eta", 1)
     _check(load().sidco_compress(_stream_handle(stream), _ptr(grad), _ptr(residual), d, delta, dist, stages,
                                  _ptr(out_idx), _ptr(out_val), _ptr(out_count), _ptr(out_eta)), "sidco_compress")
+
+
+def sidco_compress_static(grad, residual, delta: float, dist: int, stages: int, out_idx, out_val, out_count, out_eta,
+                          stream=None) -> None:
+    """sidco_compress in the library's static scratch: no device allocation; d <= sidco_static_max_elements()."""
+    import torch
+    d = grad.numel()
+    _check_tensor(grad, torch.float32, "grad")
+    if residual is not None:
+        _check_tensor(residual, torch.float32, "residual", d)
+    cap = sidco_out_capacity(d, delta)
+    _check_tensor(out_idx, torch.int32, "out_idx", cap)
+    _check_tensor(out_val, torch.float32, "out_val", cap)
+    _check_tensor(out_count, torch.int32, "out_count", 1)
+    _check_tensor(out_eta, torch.float32, "out_eta", 1)
+    _check(load().sidco_compress_static(_stream_handle(stream), _ptr(grad), _ptr(residual), d, delta, dist, stages,
+                                        _ptr(out_idx), _ptr(out_val), _ptr(out_count), _ptr(out_eta)),
+           "sidco_compress_static")
+
+
+def sidco_static_init() -> None:
+    _check(load().sidco_static_init(), "sidco_static_init")
+
+
+def sidco_static_max_elements() -> int:
+    return int(load().sidco_static_max_elements())
 
 
 GRAD_F32, GRAD_F16, GRAD_BF16 = 0, 1, 2

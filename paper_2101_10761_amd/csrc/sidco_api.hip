@@ -85,7 +85,18 @@ struct WsCtx {
     }
 };
 
+// Scratch of sidco_compress_static: the workspace of a call (device state, partial sums, list lengths and
+// the two survivor-list buffers) for vectors of up to kStaticMaxD elements, resident in every GPU the
+// library runs on from the moment its code is loaded until the process ends.  In host code this name is
+// only a handle for hipGetSymbolAddress: the device address is looked up once per device (static_ws)
+// and that pointer is what kernels and copies get.
+constexpr int64_t kStaticMaxD = 2097152;
+constexpr size_t kStaticBytes =
+    (sizeof(WorkspaceHead) + kAlign - 1) / kAlign * kAlign + 2 * (size_t)kStaticMaxD * sizeof(int2);
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticBytes];
+
 struct DeviceCtx {
+    WsCtx stat;                   // the static scratch of this device (sidco_compress_static)
     WsCtx shared;                 // the caller's workspace (sidco_set_workspace): serves every stream when set
     std::vector<WsCtx*> streams;  // library-owned workspaces, one per stream seen
     WsCtx* last_prof = nullptr;   // workspace of the last profiled call
@@ -207,6 +218,26 @@ int pick_ws(void* stream, bool create, WsCtx** out, DeviceCtx** dev_out = nullpt
     return SIDCO_OK;
 }
 
+// The static scratch of the current device as a workspace; its address is looked up on first use.
+// Caller holds g_mu.  No allocation of any kind.
+int static_ws(WsCtx** out)
+{
+    DeviceCtx* d = nullptr;
+    int rc = current_device(&d);
+    if (rc != SIDCO_OK) return rc;
+    if (!d->stat.ws) {
+        void* ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!ptr || ((uintptr_t)ptr % kAlign) != 0) return SIDCO_ERR_WORKSPACE;
+        d->stat.ws = ptr;
+        d->stat.ws_bytes = kStaticBytes;
+        d->stat.ws_owned = false;
+    }
+    *out = &d->stat;
+    return SIDCO_OK;
+}
+
 void free_ws(WsCtx& c)
 {
     if (c.ws && c.ws_owned) (void)hipFree(c.ws);
@@ -268,20 +299,29 @@ int make_events(WsCtx& c)
 size_t acc_bytes(int64_t d) { return seg_bytes(d) / 2; }  // one float per list slot
 
 // `owner`: id of the stage controller that makes the call, 0 for every other caller.
+// `use_static`: work in the device's static scratch and allocate nothing (sidco_compress_static).
 int run(void* stream, const void* grad, float* residual, int64_t d, int dist, const double* ratios, int M,
         int32_t* out_idx, float* out_val, int64_t out_cap, int32_t* out_count, float* out_eta, bool acc_reset = true,
-        int gt = kGradF32, unsigned long long owner = 0)
+        int gt = kGradF32, unsigned long long owner = 0, bool use_static = false)
 {
     std::lock_guard<std::mutex> lock(g_mu);
     WsCtx* cp = nullptr;
     DeviceCtx* dev = nullptr;
-    int rc = pick_ws(stream, true, &cp, &dev);
-    if (rc != SIDCO_OK) return rc;
-    WsCtx& c = *cp;
     const size_t seg = seg_bytes(d);
     const bool own_acc = gt != kGradF32 && !residual;  // the widened vector needs a home
-    rc = ensure_workspace(c, head_bytes() + 2 * seg + (own_acc ? acc_bytes(d) : 0));
-    if (rc != SIDCO_OK) return rc;
+    const size_t need = head_bytes() + 2 * seg + (own_acc ? acc_bytes(d) : 0);
+    int rc;
+    if (use_static) {
+        rc = static_ws(&cp);
+        if (rc != SIDCO_OK) return rc;
+        if (need > cp->ws_bytes) return SIDCO_ERR_SIZE;
+    } else {
+        rc = pick_ws(stream, true, &cp, &dev);
+        if (rc != SIDCO_OK) return rc;
+        rc = ensure_workspace(*cp, need);
+        if (rc != SIDCO_OK) return rc;
+    }
+    WsCtx& c = *cp;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
 
@@ -310,7 +350,7 @@ int run(void* stream, const void* grad, float* residual, int64_t d, int dist, co
     c.sig_theta = theta;
     for (int m = 0; m < M; ++m) c.sig_ratios[m] = ratios[m];
     p.use_hint = same_shape ? 1 : 0;
-    const bool prof = g_profiling;
+    const bool prof = g_profiling && !use_static;  // the events of a profile are created on first use
     if (prof) {
         rc = make_events(c);
         if (rc != SIDCO_OK) return rc;
@@ -518,6 +558,34 @@ int sidco_compress(void* stream, const float* grad, float* residual, int64_t d, 
     if (M < 1) return M;
     return run(stream, grad, residual, d, dist, ratios, M, out_idx, out_val, sidco_out_capacity(d, delta), out_count,
                out_eta);
+}
+
+int sidco_compress_static(void* stream, const float* grad, float* residual, int64_t d, double delta, int dist, int stages,
+                          int32_t* out_idx, float* out_val, int32_t* out_count, float* out_eta)
+{
+    int rc = check_common(grad, residual, d, dist, out_idx, out_val, out_count, out_eta);
+    if (rc != SIDCO_OK) return rc;
+    if (d > kStaticMaxD) {
+        snprintf(g_hip_msg, sizeof(g_hip_msg), "sidco_compress_static: d = %lld exceeds the static scratch (%lld elements)",
+                 (long long)d, (long long)kStaticMaxD);
+        return SIDCO_ERR_SIZE;
+    }
+    if (!(delta > 0.0 && delta < 1.0)) return SIDCO_ERR_DELTA;
+    if (stages < 1 || stages > SIDCO_MAX_STAGES) return SIDCO_ERR_STAGES;
+    double ratios[SIDCO_MAX_STAGES];
+    const int M = sidco_stage_ratios(delta, stages, default_delta1(), ratios);
+    if (M < 1) return M;
+    return run(stream, grad, residual, d, dist, ratios, M, out_idx, out_val, sidco_out_capacity(d, delta), out_count,
+               out_eta, true, kGradF32, 0, true);
+}
+
+int64_t sidco_static_max_elements(void) { return kStaticMaxD; }
+
+int sidco_static_init(void)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    WsCtx* c = nullptr;
+    return static_ws(&c);
 }
 
 int sidco_compress_typed(void* stream, const void* grad, int grad_dtype, float* residual, int64_t d, double delta,
@@ -1326,7 +1394,7 @@ const char* sidco_strerror(int code)
     switch (code) {
         case SIDCO_OK: return "ok";
         case SIDCO_ERR_NULL: return "a required pointer is NULL";
-        case SIDCO_ERR_SIZE: return "d or a capacity is out of range (1 .. 2^31-1)";
+        case SIDCO_ERR_SIZE: return "d or a capacity is out of range (1 .. 2^31-1, or the static scratch of sidco_compress_static)";
         case SIDCO_ERR_DELTA: return "a compression ratio is not in (0,1)";
         case SIDCO_ERR_STAGES: return "number of stages out of range (1 .. SIDCO_MAX_STAGES)";
         case SIDCO_ERR_DIST: return "unknown distribution";
@@ -1349,6 +1417,7 @@ void sidco_shutdown(void)
     const bool have_cur = hipGetDevice(&cur) == hipSuccess;
     for (int dev = 0; dev < kMaxDevices; ++dev) {
         DeviceCtx& d = g_ctx[dev];
+        d.stat = WsCtx();  // nothing to free: the scratch lives as long as the process
         if (!d.shared.ws && !d.shared.ev_made && d.streams.empty()) continue;
         if (hipSetDevice(dev) != hipSuccess) continue;
         free_ws(d.shared);
