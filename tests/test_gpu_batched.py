@@ -82,6 +82,14 @@ def test_config4_ragged_tensors(oracle, dist, stages, delta):
         check_batched(oracle, w.grad, res_in, offs, delta, dist, stages, out, f"cfg4 dist={dist} M={stages}")
 
 
+def test_config4_full_size_per_tensor(oracle):
+    """Config 4 as the benchmark runs its per-tensor mode: 66,000,000 elements, 50 tensors, one batched call."""
+    w = workloads.config4()
+    offs = [int(x) for x in w.tensor_offsets]
+    out = run_batched(w.grad, w.residual, offs, w.delta, w.dist, w.stages)
+    check_batched(oracle, w.grad, w.residual, offs, w.delta, w.dist, w.stages, out, "cfg4 full per tensor")
+
+
 def test_sizes_from_one_element_to_millions(oracle):
     rng = np.random.default_rng(8)
     sizes = [1, 2, 63, 64, 255, 256, 257, 1000, 4099, 1, 70_001, 300_000, 5, 2_000_003, 17]

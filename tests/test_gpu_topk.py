@@ -113,11 +113,23 @@ def test_threshold_operator_equals_topk_at_khat(oracle):
     np.testing.assert_array_equal(t[4].view(np.uint32), out.residual.view(np.uint32))
 
 
-@pytest.mark.parametrize("cfg,delta", [("cfg3", 0.001)])
+@pytest.mark.parametrize("cfg,delta", [("cfg3", 0.001), ("cfg5", 0.1)])
 def test_full_size(oracle, cfg, delta):
-    w = workloads.config3() if cfg == "cfg3" else workloads.config5(delta=delta)
-    k = int(np.ceil(delta * w.d))
-    check_topk(oracle, w.grad, w.residual, k, run_topk(w.grad, w.residual, k), label=f"{cfg} k={k}")
+    """The comparator at the benchmark configurations' own lengths; config 5 with a carried residual (the
+    second iteration's input: fresh gradient plus what the first iteration left)."""
+    if cfg == "cfg3":
+        w = workloads.config3()
+        g, r = w.grad, w.residual
+    else:
+        d = 138_357_544
+        g0 = workloads.config5_grad(0, d)
+        k0 = int(np.ceil(delta * d))
+        first = run_topk(g0, np.zeros(d, np.float32), k0)
+        r = first[4]                       # the residual after the first iteration's Top-k
+        del g0, first
+        g = workloads.config5_grad(1, d)
+    k = int(np.ceil(delta * g.size))
+    check_topk(oracle, g, r, k, run_topk(g, r, k), label=f"{cfg} delta={delta} k={k}")
 
 
 def test_profile_hooks_topk():
