@@ -13,6 +13,15 @@ the previous compression.  Each pair carries its own residual from one of its st
 (`--residual-buffers 1` keeps one residual for all steps: it then stays in the memory-side cache between
 steps and the first pass runs about a quarter faster - a figure that no training loop would see.)
 
+Config 5 (`--workload cfg5`, or `--fresh-gradients` with any workload) follows its own definition instead:
+ONE worker's consecutive iterations, a fresh i.i.d. gradient every step (a pool of distinct gradients drawn on
+the device, used in turn) added to ONE carried residual; `--delta` selects the ratio (0.1, 0.01, 0.001).
+
+Timing: the headline figure is the wall clock over exactly `--steps` calls between two device
+synchronisations.  Beside it, `--timed-calls` further calls are timed one by one with HIP events on the call's
+stream (median and minimum), and, with `--reset-residual`, once more with every pair's residual restored
+(untimed) before each call, so that every call sees the configuration's own first-iteration distribution.
+
 Prints ONE JSON line on stdout; everything else goes to stderr.
 """
 from __future__ import annotations
@@ -45,14 +54,108 @@ def make_workload(name: str, d: int = 0):
     return table[name](d) if d > 0 else table[name]()
 
 
-def algorithmic_bytes(d, ec, n_stage, khat, fit_bpe=None):
-    """Bytes the method itself must move: gradient (+ residual read and acc write), the second pass over
-    acc, every intermediate survivor list written once and read once (8 B pairs), output pairs and
-    residual zero-stores.  fit_bpe: bytes per element of the first pass when the gradient is not fp32."""
+def scope_formula_bytes(d, ec, n_stage, khat, fit_bpe=None):
+    """The scope table's byte count of a call: gradient (+ residual read and acc write), the second pass over
+    acc, every stage's exceedances written once and read once as 8-byte pairs, output pairs and residual
+    zero-stores.  fit_bpe: bytes per element of the first pass when the gradient is not fp32."""
     b = d * (fit_bpe if fit_bpe is not None else 4 * (3 if ec else 1)) + 4 * d
     b += sum(16 * int(n) for n in n_stage[1:])
     b += 12 * khat
     return b
+
+
+def moved_bytes_min(d, ec, n_stage, khat, fit_bpe=None):
+    """The least this design can move in a call: the first pass, ONE further pass over the accumulated vector
+    (whatever the number of stages: the dense stage only sums over the exceedances of eta_1 and writes
+    candidates for the stage after it), the lists behind the dense stage - candidates that must at least hold
+    the next stage's exceedances, then each later stage's exceedances, all written once and read once - and the
+    output.  The exceedances of eta_1 are never written, so they are not counted."""
+    b = d * (fit_bpe if fit_bpe is not None else 4 * (3 if ec else 1)) + 4 * d
+    M = len(n_stage)
+    if M >= 2:
+        after = [int(n) for n in n_stage[2:]] + [khat]      # what stages 2..M leave: n_3 .. n_M, khat
+        b += 16 * after[0]                                    # the dense stage's candidate lists
+        b += sum(16 * a for a in after[:-1])                  # exceedance lists written by the list stages
+    b += 12 * khat
+    return b
+
+
+def timing_summary(ms_list):
+    a = np.asarray(ms_list, dtype=np.float64) * 1e3
+    return {"calls": int(a.size), "median_us": round(float(np.median(a)), 2), "min_us": round(float(a.min()), 2),
+            "mean_us": round(float(a.mean()), 2), "max_us": round(float(a.max()), 2)}
+
+
+# ---- CPU baseline: the oracle as it stands, on one core and on all of them (one process per core, each on
+# its own slice of the vector: the data-parallel use the paper describes, every worker compressing its own
+# gradient).  Runs before anything touches the GPU: the worker processes are forked.
+_CPU_ARGS = None
+
+
+def _cpu_slice(bounds):
+    import oracle
+    w, oratios = _CPU_ARGS
+    a, b = bounds
+    rs = None if w.residual is None else np.ascontiguousarray(w.residual[a:b])
+    tc = time.perf_counter()
+    oracle.compress(np.ascontiguousarray(w.grad[a:b]), rs, ratios=oratios, dist=w.dist)
+    return time.perf_counter() - tc
+
+
+def cpu_baseline_legs(w, budget_s):
+    global _CPU_ARGS
+    import multiprocessing as mp
+    import oracle
+    oracle.build()
+    oratios = oracle.schedule(w.delta, w.stages, w.delta1)
+    d = w.d
+    cores_host = os.cpu_count() or 1
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = cores_host
+    workers = max(1, min(usable, 16))      # the share of a one-GPU box, whatever the host shows
+    _CPU_ARGS = (w, oratios)
+    # one core: the whole vector, median of at least 5 runs
+    t1 = []
+    t_used = 0.0
+    while len(t1) < 5 or (t_used < 0.4 * budget_s and len(t1) < 15):
+        t = _cpu_slice((0, d))
+        t1.append(t)
+        t_used += t
+    single = d / float(np.median(t1)) / 1e9
+    # all cores: `workers` processes, each on its own d / workers slice, timed until the last one is done
+    bounds = [(d * i // workers, d * (i + 1) // workers) for i in range(workers)]
+    tall = []
+    with mp.get_context("fork").Pool(workers) as pool:
+        pool.map(_cpu_slice, bounds)       # warm-up: page the slices in, load the library
+        t_used = 0.0
+        while len(tall) < 5 or (t_used < 0.4 * budget_s and len(tall) < 15):
+            tc = time.perf_counter()
+            pool.map(_cpu_slice, bounds)
+            tall.append(time.perf_counter() - tc)
+            t_used += tall[-1]
+    multi = d / float(np.median(tall)) / 1e9
+    _CPU_ARGS = None
+    return {
+        "value": round(single, 5), "unit": "G elem/s", "cores": 1, "kind": "oracle",
+        "sample": f"the workload's whole vector ({d} elements), first iteration's input, median of {len(t1)} runs "
+                  f"({float(np.median(t1)):.3f} s each), single thread, fp64 plain C",
+        "all_cores": {"value": round(multi, 5), "unit": "G elem/s", "cores": workers,
+                      "sample": f"{workers} processes, each compressing its own {d // workers}-element slice of the same "
+                                f"vector (one worker per core), median of {len(tall)} runs "
+                                f"({float(np.median(tall)):.3f} s until the last one finishes)"},
+        "cores_host": cores_host, "cores_usable": usable,
+    }
+
+
+def laplace_(out, scale, gen):
+    """Fills `out` (a CUDA tensor) with Laplace(0, scale) draws: inverse CDF of a uniform."""
+    import torch
+    out.uniform_(-0.5, 0.5, generator=gen)
+    sign = torch.sign(out)
+    out.abs_().mul_(-2.0).add_(1.0).clamp_(min=1e-30).log_().mul_(sign).mul_(-scale)
+    return out
 
 
 def main():
@@ -62,8 +165,14 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--d", type=int, default=0, help="length of the vector, if not the workload's own (size sweeps)")
+    ap.add_argument("--delta", type=float, default=0.0, help="target ratio, if not the workload's own (cfg5: 0.1, 0.01, 0.001)")
+    ap.add_argument("--fresh-gradients", action="store_true",
+                    help="a fresh i.i.d. gradient every step on ONE carried residual (always on for cfg5)")
+    ap.add_argument("--timed-calls", type=int, default=60, help="calls timed one by one with HIP events (median, min)")
+    ap.add_argument("--reset-residual", action="store_true",
+                    help="also time calls whose residual is restored, untimed, before each of them")
     ap.add_argument("--profile-steps", type=int, default=50, help="steps timed kernel by kernel with HIP events")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline leg")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the CPU-oracle baseline (both legs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-topk", action="store_true", help="skip the exact Top-k comparator leg")
     ap.add_argument("--no-dgc", action="store_true", help="skip the DGC comparator leg")
@@ -82,6 +191,22 @@ def main():
             "no sharding); --gpus must be 1")
         sys.exit(2)
 
+    t0 = time.time()
+    w = make_workload(args.workload, args.d)
+    if args.delta > 0.0:
+        w.delta = args.delta
+    d = w.d
+    fresh = args.fresh_gradients or args.workload == "cfg5"
+    log(f"workload {w.name}: d={d} delta={w.delta} dist={w.dist} stages={w.stages} delta1={w.delta1} "
+        f"(generated in {time.time() - t0:.1f}s){' fresh gradient every step, one carried residual' if fresh else ''}")
+
+    # the CPU legs fork worker processes: before anything touches the GPU
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        cpu_baseline = cpu_baseline_legs(w, args.cpu_seconds)
+        log(f"cpu oracle: {cpu_baseline['value']} G elem/s on 1 core; {cpu_baseline['all_cores']['value']} G elem/s on "
+            f"{cpu_baseline['all_cores']['cores']} cores (host has {cpu_baseline['cores_host']})")
+
     import torch
     import paper_2101_10761_amd as sidco
 
@@ -92,11 +217,6 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    t0 = time.time()
-    w = make_workload(args.workload, args.d)
-    d = w.d
-    log(f"workload {w.name}: d={d} delta={w.delta} dist={w.dist} stages={w.stages} delta1={w.delta1} "
-        f"(generated in {time.time() - t0:.1f}s)")
     ratios = sidco.sidco_stage_ratios(w.delta, w.stages, w.delta1)
     g0 = torch.from_numpy(w.grad).to(dev)
     typed = args.grad_dtype != "f32"
@@ -107,14 +227,30 @@ def main():
             sys.exit(2)
         g0 = g0.to(torch.float16 if args.grad_dtype == "f16" else torch.bfloat16)
         args.no_topk = args.no_dgc = True
-    nbuf = max(2, min(16, ROTATE_BYTES // (4 * d) + 1))
-    # The same gradient in several buffers: every step reads its gradient from another address range, and the
-    # carried residual reaches a steady state the way it does under a persistent gradient direction (an entry
-    # grows until it is selected and starts over), instead of turning Gaussian as it would under a stream of
-    # independent draws that are hardly ever selected.
-    grads = [g0] + [g0.clone() for _ in range(nbuf - 1)]
     ec = w.residual is not None
-    nres = nbuf if args.residual_buffers <= 0 else min(args.residual_buffers, nbuf)
+    if fresh:
+        # ONE worker's consecutive iterations: a pool of distinct i.i.d. gradients of the workload's law (config 5:
+        # Laplace(1e-3)), drawn on the device and used in turn, all added to ONE carried residual.  The pool is
+        # larger than the memory-side cache many times over, so every gradient comes from HBM; the residual is
+        # the one a training loop would carry.
+        pool_bytes = 48 << 30
+        nbuf = int(max(4, min(args.steps + args.warmup + args.timed_calls, pool_bytes // (gbytes * d), 128)))
+        gen = torch.Generator(device=dev)
+        grads = [g0]
+        scale = 1e-3
+        for i in range(1, nbuf):
+            gen.manual_seed(210110761 + 5 + 1000 * (i + 1))
+            gi = laplace_(torch.empty(d, dtype=torch.float32, device=dev), scale, gen)
+            grads.append(gi if not typed else gi.to(g0.dtype))
+        nres = 1
+    else:
+        nbuf = max(2, min(16, ROTATE_BYTES // (4 * d) + 1))
+        # The same gradient in several buffers: every step reads its gradient from another address range, and the
+        # carried residual reaches a steady state the way it does under a persistent gradient direction (an entry
+        # grows until it is selected and starts over), instead of turning Gaussian as it would under a stream of
+        # independent draws that are hardly ever selected.
+        grads = [g0] + [g0.clone() for _ in range(nbuf - 1)]
+        nres = nbuf if args.residual_buffers <= 0 else min(args.residual_buffers, nbuf)
 
     def fresh_residuals():
         if not ec:
@@ -126,16 +262,22 @@ def main():
     cap = max(sidco.sidco_out_capacity(d, w.delta), 1)
     out_idx = torch.empty(cap, dtype=torch.int32, device=dev)
     out_val = torch.empty(cap, dtype=torch.float32, device=dev)
-    out_count = torch.zeros(1, dtype=torch.int32, device=dev)
-    out_eta = torch.zeros(1, dtype=torch.float32, device=dev)
+    # every step reports its count and threshold into a slot of its own: the trajectory costs nothing
+    n_slots = args.warmup + args.steps + args.timed_calls * (2 if args.reset_residual else 1) + args.profile_steps + 8
+    counts = torch.zeros(n_slots, dtype=torch.int32, device=dev)
+    etas = torch.zeros(n_slots, dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
+    sidco.sidco_reserve(sidco.sidco_workspace_bytes_typed(d, {"f32": 0, "f16": 1, "bf16": 2}[args.grad_dtype], ec),
+                        stream=stream)
 
-    def step(i):
+    def step(i, slot=None):
+        slot = i if slot is None else slot
+        oc, oe = counts[slot:slot + 1], etas[slot:slot + 1]
         if typed:
             sidco.sidco_compress_typed(grads[i % nbuf], residuals[i % nres], w.delta, w.dist, w.stages, out_idx, out_val,
-                                       out_count, out_eta, stream=stream)
+                                       oc, oe, stream=stream)
         else:
-            sidco.sidco_compress_ex(grads[i % nbuf], residuals[i % nres], w.dist, ratios, out_idx, out_val, out_count, out_eta,
+            sidco.sidco_compress_ex(grads[i % nbuf], residuals[i % nres], w.dist, ratios, out_idx, out_val, oc, oe,
                                     stream=stream)
 
     for i in range(args.warmup):
@@ -148,7 +290,37 @@ def main():
     t_end = time.perf_counter()
     ms_per_step = (t_end - t_start) * 1e3 / args.steps
     value = d / (ms_per_step * 1e-3) / 1e9
-    log(f"timed {args.steps} steps: {ms_per_step * 1e3:.1f} us/step -> {value:.1f} G elem/s")
+    n_done = args.warmup + args.steps
+    traj = (counts[:n_done].cpu().numpy().astype(np.float64) / (w.delta * d))
+    log(f"timed {args.steps} steps: {ms_per_step * 1e3:.1f} us/step -> {value:.1f} G elem/s; khat/k over the timed "
+        f"steps: mean {traj[args.warmup:].mean():.4f}, first step {traj[0]:.4f}, last {traj[-1]:.4f}")
+
+    # the same calls one by one between two HIP events on the call's stream
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(max(args.timed_calls, 1))]
+    timing = {"wall_clock_loop": {"calls": args.steps, "mean_us": round(ms_per_step * 1e3, 2)}}
+    if args.timed_calls > 0:
+        for j in range(args.timed_calls):
+            ev[j][0].record(stream)
+            step(n_done + j)
+            ev[j][1].record(stream)
+        torch.cuda.synchronize()
+        timing["per_call_events"] = timing_summary([a.elapsed_time(b) for a, b in ev[:args.timed_calls]])
+        n_done += args.timed_calls
+        log(f"per-call HIP events: {timing['per_call_events']}")
+        if args.reset_residual and ec:
+            pristine = torch.from_numpy(w.residual).to(dev)
+            for j in range(args.timed_calls):
+                residuals[(n_done + j) % nres].copy_(pristine)      # untimed
+                ev[j][0].record(stream)
+                step(n_done + j)
+                ev[j][1].record(stream)
+            torch.cuda.synchronize()
+            timing["per_call_events_residual_reset"] = timing_summary([a.elapsed_time(b) for a, b in ev[:args.timed_calls]])
+            rr = counts[n_done:n_done + args.timed_calls].cpu().numpy().astype(np.float64) / (w.delta * d)
+            timing["per_call_events_residual_reset"]["khat_over_k_mean"] = round(float(rr.mean()), 4)
+            n_done += args.timed_calls
+            log(f"per-call HIP events, residual restored before each call: {timing['per_call_events_residual_reset']}")
+            del pristine
 
     # kernel-by-kernel timing with HIP events on the same stream
     sidco.sidco_set_profiling(True)
@@ -157,7 +329,7 @@ def main():
     n_stage = None
     khat = []
     for i in range(args.profile_steps):
-        step(args.warmup + args.steps + i)
+        step(n_done + i, slot=n_slots - 1)
         prof = sidco.sidco_get_profile()
         seen: dict[str, int] = {}
         for name, ms in prof:
@@ -171,8 +343,10 @@ def main():
         n_stage = [diag.n[m] for m in range(diag.stages)]
         khat.append(diag.count)
     sidco.sidco_set_profiling(False)
-    kern_us = {k: float(np.mean(v)) * 1e3 for k, v in per_kernel.items()}
-    log("per-kernel average (HIP events): " + ", ".join(f"{k} {kern_us[k]:.1f} us" for k in order))
+    n_done += args.profile_steps
+    kern_us = {k: float(np.median(v)) * 1e3 for k, v in per_kernel.items()}
+    log("per-kernel median (HIP events, each figure includes the events' own dispatch): " +
+        ", ".join(f"{k} {kern_us[k]:.1f} us" for k in order))
     if not khat:   # no profiled steps asked for: take the diagnostics of the last timed step
         diag = sidco.sidco_read_diag(stream)
         n_stage = [diag.n[m] for m in range(diag.stages)]
@@ -184,9 +358,8 @@ def main():
     # the in-sequence figures above include) is spread over the batch.  Every launch of a batch gets its own
     # copy of the carried residual (restored, untimed, before each batch), so that each one sees the
     # values of a real step rather than a residual that has already absorbed the gradient several times.
-    batch, fit_ms = 20, []
+    batch, fit_ms = (20 if d < 100_000_000 else 8), []
     ev_a, ev_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    n_done = args.warmup + args.steps + args.profile_steps
     residual = residuals[n_done % nres]          # the residual the next step would use
     scratch_res = [residual.clone() for _ in range(batch)] if ec else [None] * batch
     for rep in range(12):
@@ -208,23 +381,34 @@ def main():
     log(f"k_fit alone: {fit_us:.1f} us per launch "
         f"(HIP events around batches of {batch})")
     achieved = fit_bytes / (fit_us * 1e-6) / 1e9
-    traffic = None
+    traffic, counters = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not typed and args.d == 0:
         try:
-            traffic = None if typed else json.load(open(tpath)).get(args.workload, {}).get("k_fit")
+            counters = json.load(open(tpath)).get(args.workload)
+            traffic = (counters or {}).get("k_fit")
         except Exception:
-            traffic = None
+            traffic, counters = None, None
     roofline = {
         "kernel": "k_fit (first pass; from 12 M elements k_fit_flat + k_fit_reduce)", "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+        "traffic_source": None if traffic is None else "from profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE of an "
+                          "earlier run of this workload, scaled by a device copy of known size); not measured in this run",
         "bytes_per_elem": fit_bpe, "elems_per_launch": d, "avg_launch_us": round(fit_us, 2),
     }
-    path_bytes = algorithmic_bytes(d, ec, n_stage, int(np.mean(khat)), fit_bpe)
+    khat_mean = int(np.mean(khat))
+    moved = moved_bytes_min(d, ec, n_stage, khat_mean, fit_bpe)
+    formula = scope_formula_bytes(d, ec, n_stage, khat_mean, fit_bpe)
+    secs = ms_per_step * 1e-3
     path = {
-        "algorithmic_bytes": path_bytes, "bytes_per_elem": round(path_bytes / d, 2),
-        "achieved": round(path_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
-        "frac": round(path_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "bytes_moved_min": moved, "bytes_per_elem": round(moved / d, 2),
+        "achieved": round(moved / secs / 1e9, 1), "unit": "GB/s",
+        "frac": round(moved / secs / 1e9 / HBM_PEAK_GBPS, 4),
+        "note": "frac prices the step against the bytes this design must move (the exceedances of eta_1 are never "
+                "written as pairs); frac_scope_formula prices it against the scope table's formula, which charges them",
+        "scope_formula_bytes": formula, "frac_scope_formula": round(formula / secs / 1e9 / HBM_PEAK_GBPS, 4),
+        "counter_bytes": None if not counters else {k: v for k, v in counters.items()},
+        "counter_source": None if not counters else "profiles/hbm_traffic.json, not measured in this run",
         "kernels_us": {k: round(kern_us[k], 2) for k in order},
     }
 
@@ -232,22 +416,22 @@ def main():
     # launch-bound loop gains when the host only issues one graph launch per step.
     graph_leg = None
     if args.graph:
-        pairs = nbuf if nres == nbuf else 1
         side = torch.cuda.Stream()
         sidco.sidco_reserve(sidco.sidco_workspace_bytes_typed(d, {"f32": 0, "f16": 1, "bf16": 2}[args.grad_dtype], ec),
                             stream=side)   # the capturing stream's workspace: allocated outside the capture
         side.wait_stream(stream)
         graphs = []
         with torch.cuda.stream(side):
-            for i in range(max(pairs, nbuf)):
+            for i in range(min(nbuf, 16)):
                 gph = torch.cuda.CUDAGraph()
                 gph.capture_begin()
+                oc, oe = counts[n_slots - 2:n_slots - 1], etas[n_slots - 2:n_slots - 1]
                 if typed:
                     sidco.sidco_compress_typed(grads[i % nbuf], residuals[i % nres], w.delta, w.dist, w.stages, out_idx,
-                                               out_val, out_count, out_eta, stream=side)
+                                               out_val, oc, oe, stream=side)
                 else:
                     sidco.sidco_compress_ex(grads[i % nbuf], residuals[i % nres], w.dist, ratios, out_idx, out_val,
-                                            out_count, out_eta, stream=side)
+                                            oc, oe, stream=side)
                 gph.capture_end()
                 graphs.append(gph)
         stream.wait_stream(side)
@@ -310,7 +494,7 @@ def main():
             "kind": "exact Top-k, radix select on magnitude bits (own HIP kernels)", "k": k, "steps": n_topk,
             "ms_per_step": round(topk_ms, 5), "value": round(d / (topk_ms * 1e-3) / 1e9, 2), "unit": "G elem/s",
             "sidco_speedup_over_topk": round(topk_ms / ms_per_step, 3),
-            "kth_magnitude": float(t_kth.item()), "sidco_eta": float(out_eta.item()),
+            "kth_magnitude": float(t_kth.item()), "sidco_eta": float(etas[n_slots - 1].item()),
         }
         log(f"top-k comparator (k={k}): {topk_ms * 1e3:.1f} us/step -> {topk['value']} G elem/s; "
             f"SIDCo is {topk['sidco_speedup_over_topk']}x faster")
@@ -406,39 +590,26 @@ def main():
             f"({per_tensor['batched_value']} G elem/s), one call per tensor {times['one_call_per_tensor'] * 1e3:.1f} us/step, "
             f"whole vector {ms_per_step * 1e3:.1f} us/step")
 
-    cpu_baseline = None
-    if not args.no_cpu_baseline:
-        import oracle
-        oracle.build()
-        oratios = oracle.schedule(w.delta, w.stages, w.delta1)
-        # bounded sample: the first `ns` elements of the same vector, repeated until the time budget is used
-        ns = min(d, 26_000_000)
-        gs = np.ascontiguousarray(w.grad[:ns])
-        rs = None if w.residual is None else np.ascontiguousarray(w.residual[:ns])
-        reps, t_cpu = 0, 0.0
-        while t_cpu < args.cpu_seconds and reps < 50:
-            tc = time.perf_counter()
-            oracle.compress(gs, rs, ratios=oratios, dist=w.dist)
-            t_cpu += time.perf_counter() - tc
-            reps += 1
-        cpu_baseline = {
-            "value": round(ns * reps / t_cpu / 1e9, 5), "unit": "G elem/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {ns} of {d} elements of the same vector, {reps} repetitions, {t_cpu:.1f} s, "
-                      f"single thread, fp64 plain C",
-        }
-        log(f"cpu oracle: {cpu_baseline['value']} G elem/s on 1 core ({reps} reps, {t_cpu:.1f}s)")
-
     result = {
-        "metric": "G gradient elems/s compressed (d=25.6M fp32, delta=0.001)" if args.workload == "cfg3" and not typed
-                  else f"G gradient elems/s compressed ({args.workload}" + (f", {args.grad_dtype} gradient)" if typed else ")"),
+        "metric": "G gradient elems/s compressed (d=25.6M fp32, delta=0.001)" if args.workload == "cfg3" and not typed and args.delta == 0.0 and args.d == 0
+                  else f"G gradient elems/s compressed ({args.workload}, d={d}, delta={w.delta}" + (f", {args.grad_dtype} gradient)" if typed else ")"),
         "value": round(value, 2), "unit": "G elem/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {
             "workload": f"{w.name}: d={d} {'fp32' if not typed else args.grad_dtype + ' gradient, fp32 residual'}, delta={w.delta}, dist={['exp', 'gamma-gpd', 'gpd'][w.dist]}, "
                         f"stages={w.stages}, delta1={w.delta1}, error_feedback={'on' if ec else 'off'}",
-            "gradient_buffers_in_rotation": nbuf, "residual_buffers_in_rotation": nres, "khat_over_k": round(float(np.mean(khat)) / (w.delta * d), 4),
+            "gradients": ("pool of distinct i.i.d. gradients drawn on the device, used in turn" if fresh else
+                          "the workload's seeded gradient in several buffers, used in rotation"),
+            "gradient_buffers_in_rotation": nbuf, "residual_buffers_in_rotation": nres,
+            "khat_over_k": round(float(traj[args.warmup:].mean()), 4),
         },
+        "khat_over_k_trajectory": {"first_steps": [round(float(x), 4) for x in traj[:12]],
+                                   "timed_mean": round(float(traj[args.warmup:].mean()), 4),
+                                   "timed_min": round(float(traj[args.warmup:].min()), 4),
+                                   "timed_max": round(float(traj[args.warmup:].max()), 4),
+                                   "last": round(float(traj[-1]), 4)},
+        "timing": timing,
         "roofline": roofline, "path": path, "streaming_ceiling": ceiling, "graph_replay": graph_leg,
         "cpu_baseline": cpu_baseline,
         "topk_comparator": topk,
