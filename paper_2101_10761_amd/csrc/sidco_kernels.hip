@@ -594,7 +594,7 @@ __device__ __forceinline__ void emit(bool valid, float x, int32_t idx, float eta
 
 // U complete tiles of the dense vector, already loaded
 template <bool STATS, bool WRITE, int U>
-__device__ __forceinline__ void compact_loaded(const f4 (&a)[U], uint32_t t, int lane, float eta_s, float eta_w,
+__device__ __forceinline__ void compact_loaded(const f4* a, uint32_t t, int lane, float eta_s, float eta_w,
                                                ListWriter& lw, uint32_t& ns, double& sy, double& syy)
 {
 #pragma unroll
@@ -620,16 +620,22 @@ __device__ __forceinline__ void load_tiles(f4 (&a)[U], const f4* __restrict__ x4
 // first: the kernel before this one left the end of what it touched last in L2 (32 MB over the chip),
 // and the host alternates the direction from pass to pass so that each pass starts where the one
 // before it stopped (measured: 15.5 us instead of 18.3 us for 102 MB right after k_fit).
-// With `pre`, a0 already holds the first batch of U tiles (see dense_first_batch).
-// Plain load-then-process steps: with 16 waves per CU in flight, a second register buffer per wave
-// gained nothing for the statistics alone and lost 2-3 us once list entries are staged as well (measured).
-__device__ __forceinline__ uint32_t dense_first_batch(const Params& p, uint32_t t0, uint32_t tf, uint32_t U)
+// Batches of U tiles.  The caller has loaded the first PRE batches already, into a[0 .. PRE*U), while it
+// still waited for its threshold: a stage kernel's prologue is a cold round trip for the partial sums
+// plus a few hundred dependent fp64 instructions, 4-5 us in which the memory pipes would otherwise run
+// dry after the first batch.  PRE is a template parameter and the caller's loads are unconditional:
+// loads under a run-time condition come with copies that the compiler waits for on the spot.
+// After the prefetched batches, plain load-then-process steps: with 16 waves per CU in flight, a second
+// register buffer per wave gained nothing for the statistics alone and lost 2-3 us once list entries are
+// staged as well (measured).  One copy of the loop body: the next prefetched batch moves up into a[0 .. U)
+// by register copies (PRE - 1 times U moves per wave in all).
+__device__ __forceinline__ uint32_t dense_batch_tile(const Params& p, uint32_t t0, uint32_t tf, uint32_t U, uint32_t k)
 {
-    return p.reverse ? tf - U : t0;
+    return p.reverse ? tf - (k + 1) * U : t0 + k * U;
 }
 
-template <bool STATS, bool WRITE, int U>
-__device__ __forceinline__ void compact_dense(const Params& p, f4 (&a0)[U], bool pre, uint32_t t0, uint32_t t1,
+template <bool STATS, bool WRITE, int U, int PRE>
+__device__ __forceinline__ void compact_dense(const Params& p, f4 (&a)[(PRE > 0 ? PRE : 1) * U], uint32_t t0, uint32_t t1,
                                               uint32_t tf, int lane, float eta_s, float eta_w, ListWriter& lw,
                                               uint32_t& ns, double& sy, double& syy)
 {
@@ -639,15 +645,24 @@ __device__ __forceinline__ void compact_dense(const Params& p, f4 (&a0)[U], bool
         const uint32_t nb = (tf - t0) / U, rem = (tf - t0) - nb * U;
 #pragma unroll 1  // unrolled, the batches' loads pile up in registers and halve the occupancy
         for (uint32_t k = 0; k < nb; ++k) {
-            const uint32_t t = p.reverse ? tf - (k + 1) * U : t0 + k * U;
-            if (!(k == 0 && pre)) load_tiles<U>(a0, x4, t, lane);  // one copy of the loop body: a0 is the only buffer
-            compact_loaded<STATS, WRITE, U>(a0, t, lane, eta_s, eta_w, lw, ns, sy, syy);
+            const uint32_t t = dense_batch_tile(p, t0, tf, U, k);
+            if (k >= (uint32_t)PRE) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) a[u] = x4[(size_t)(t + u) * 64 + lane];
+            }
+            compact_loaded<STATS, WRITE, U>(a, t, lane, eta_s, eta_w, lw, ns, sy, syy);
+            if constexpr (PRE > 1) {
+                if (k + 1 < (uint32_t)PRE) {  // the next prefetched batch moves up
+#pragma unroll
+                    for (int u = 0; u < (PRE - 1) * U; ++u) a[u] = a[u + U];
+                }
+            }
         }
         const uint32_t tr = p.reverse ? t0 : t0 + nb * U;
         for (uint32_t t = tr; t < tr + rem; ++t) {
-            f4 a[1];
-            load_tiles<1>(a, x4, t, lane);
-            compact_loaded<STATS, WRITE, 1>(a, t, lane, eta_s, eta_w, lw, ns, sy, syy);
+            f4 one[1];
+            load_tiles<1>(one, x4, t, lane);
+            compact_loaded<STATS, WRITE, 1>(one, t, lane, eta_s, eta_w, lw, ns, sy, syy);
         }
         ts = tf;
     }
@@ -726,7 +741,9 @@ __device__ __forceinline__ void stage_epilogue(const Params& p, Blk b, int lane,
 // k_compact: a stage that reads the dense vector.  STATS: form the sums for the next stage's fit.
 // WRITE: append the entries above eta_w to this stage's lists (eta_w = eta_m, or a candidate threshold
 // above it); a stage whose candidates would still be a large fraction only counts and sums.
-template <bool STATS, bool WRITE>
+// PRE: batches of U tiles that every wave loads before the prologue; the host picks PRE > 0 only when the
+// vector is aligned for 4-element accesses and every wave owns at least PRE * U complete tiles.
+template <bool STATS, bool WRITE, int PRE>
 __device__ __forceinline__ void compact_body(const Params& p, Blk b)
 {
     __shared__ double sh[kWavesPerBlock][4];
@@ -742,11 +759,19 @@ __device__ __forceinline__ void compact_body(const Params& p, Blk b)
 
     // Neither the prologue's own loads nor the first loads of the body depend on the threshold.  The
     // prologue's go first (the memory counter retires in order: behind the tiles they would wait for
-    // them), then the first batch of tiles, whose latency overlaps the reduction of the partial sums.
+    // them), then the first batches of tiles, so that the stream runs while the partial sums are reduced
+    // and the closed form is evaluated.
     PrologueLoads g = prologue_load(p, b, false);
-    f4 a0[U];
-    const bool pre_dense = active && p.vec_ok && t0 + U <= tf;
-    if (pre_dense) load_tiles<U>(a0, reinterpret_cast<const f4*>(p.acc), dense_first_batch(p, t0, tf, U), lane);
+    f4 a0[(PRE > 0 ? PRE : 1) * U];
+    if constexpr (PRE > 0) {
+        const f4* __restrict__ x4 = reinterpret_cast<const f4*>(p.acc);
+#pragma unroll
+        for (int k = 0; k < PRE; ++k) {
+            const uint32_t t = dense_batch_tile(p, t0, tf, U, k);
+#pragma unroll
+            for (int u = 0; u < U; ++u) a0[k * U + u] = x4[(size_t)(t + u) * 64 + lane];
+        }
+    }
 
     const StageEta se = prologue_finish(p, b, false, g, sh);
 
@@ -757,7 +782,7 @@ __device__ __forceinline__ void compact_body(const Params& p, Blk b)
         lw.list = p.seg_out + (size_t)t0 * kTile;  // room for every element of the wave's tiles
         lw.ring = ring[WRITE ? wib : 0];
         lw.run = lw.fill = 0;
-        compact_dense<STATS, WRITE, U>(p, a0, pre_dense, t0, t1, tf, lane, se.eta, se.eta_w, lw, ns, sy, syy);
+        compact_dense<STATS, WRITE, U, PRE>(p, a0, t0, t1, tf, lane, se.eta, se.eta_w, lw, ns, sy, syy);
         if (WRITE) run = list_finish(lw, lane);
         if (lane == 0) p.cnt_out[w] = run;
     }
@@ -819,7 +844,7 @@ __device__ __forceinline__ void lists_body(const Params& p, Blk b)
                 // this stage's exceedances straight from the dense vector
                 f4 unused[U];
                 const uint32_t tf = t1 < p.nfull ? t1 : p.nfull;
-                compact_dense<true, true, U>(p, unused, false, t0, t1, tf, lane, eta, eta, lw, ns, sy, syy);
+                compact_dense<true, true, U, 0>(p, unused, t0, t1, tf, lane, eta, eta, lw, ns, sy, syy);
             } else {
                 const int4* __restrict__ src4 = reinterpret_cast<const int4*>(p.seg_in + (size_t)t0 * kTile);
                 const uint32_t cap2 = (t1 - t0) * (kTile / 2);
@@ -1228,8 +1253,8 @@ __device__ __forceinline__ Params batch_params(const BatchArgs& a, bool final_gr
 
 template <int DIST, bool EC, int GT>
 __global__ __launch_bounds__(kBlock, 4) void k_fit(Params p) { fit_body<DIST, EC, GT>(p, whole_grid()); }
-template <bool STATS, bool WRITE>
-__global__ __launch_bounds__(kBlock, 4) void k_compact(Params p) { compact_body<STATS, WRITE>(p, whole_grid()); }
+template <bool STATS, bool WRITE, int PRE>
+__global__ __launch_bounds__(kBlock, 4) void k_compact(Params p) { compact_body<STATS, WRITE, PRE>(p, whole_grid()); }
 __global__ __launch_bounds__(kBlock, 4) void k_lists(Params p) { lists_body(p, whole_grid()); }
 __global__ __launch_bounds__(kBlock) void k_final_lists(Params p) { final_body(p, whole_grid()); }
 __global__ __launch_bounds__(kBlock) void k_gather(Params p) { gather_body(p, whole_grid()); }
@@ -1246,7 +1271,7 @@ __global__ __launch_bounds__(kBlock, 4) void k_compact_batched(BatchArgs a)
 {
     Blk b;
     const Params p = batch_params(a, false, b);
-    compact_body<STATS, WRITE>(p, b);
+    compact_body<STATS, WRITE, 0>(p, b);
 }
 __global__ __launch_bounds__(kBlock, 4) void k_lists_batched(BatchArgs a)
 {
@@ -1326,12 +1351,23 @@ void launch_fit(const Params& p, double* scratch, hipStream_t s)
     }
 }
 
-void launch_compact(const Params& p, bool stats, bool write, hipStream_t s)
+template <int PRE>
+static void launch_compact_pre(const Params& p, bool stats, bool write, hipStream_t s)
 {
     const dim3 grid(p.nblocks), block(kBlock);
-    if (stats && write) hipLaunchKernelGGL((k_compact<true, true>), grid, block, 0, s, p);
-    else if (stats) hipLaunchKernelGGL((k_compact<true, false>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((k_compact<false, true>), grid, block, 0, s, p);
+    if (stats && write) hipLaunchKernelGGL((k_compact<true, true, PRE>), grid, block, 0, s, p);
+    else if (stats) hipLaunchKernelGGL((k_compact<true, false, PRE>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((k_compact<false, true, PRE>), grid, block, 0, s, p);
+}
+
+void launch_compact(const Params& p, bool stats, bool write, hipStream_t s)
+{
+    // prefetch before the prologue only where every wave has that many complete tiles to itself
+    const uint32_t per_wave = p.nwaves ? p.nfull / p.nwaves : 0;
+    if (p.vec_ok && p.nwaves == (uint32_t)kMaxWaves && per_wave >= (uint32_t)(kCompactPrefetch * 4))
+        launch_compact_pre<kCompactPrefetch>(p, stats, write, s);
+    else
+        launch_compact_pre<0>(p, stats, write, s);
 }
 
 void launch_lists(const Params& p, uint32_t grid_blocks, hipStream_t s)
