@@ -974,7 +974,8 @@ __device__ __forceinline__ void final_body(const Params& p, Blk b)
     __shared__ unsigned long long sh_base;
     constexpr int K = kFinalGroup;
     const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-    // source lists of this wave: first, first + 8, first + 16, ... below last
+    // source lists of this wave: first, first + 8, first + 16, first + 24 (below last): the launchers give a
+    // block at most kFinalGroup * 8 = 32 source lists, so one group of loads covers them all
     const uint32_t per_block = (p.nwaves + b.n - 1) / b.n;
     const uint32_t first = b.id * per_block + wib;
     const uint32_t last = min(p.nwaves, (b.id + 1) * per_block);
@@ -1006,26 +1007,6 @@ __device__ __forceinline__ void final_body(const Params& p, Blk b)
             const uint32_t i = c + lane;
             const int4 q = i < l0[k].cap2 ? l0[k].src4[i] : make_int4(0, 0, 0, 0);
             mine += final_count(q, i, n, eta);
-        }
-    }
-    for (uint32_t g = first + K * kWavesPerBlock; g < last; g += K * kWavesPerBlock) {
-        FinalList l[K];
-        int4 q[K];
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const uint32_t sw = g + k * kWavesPerBlock;
-            l[k] = final_list(p, sw, sw < last);
-            q[k] = (uint32_t)lane < l[k].cap2 ? l[k].src4[lane] : make_int4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const uint32_t n = __builtin_amdgcn_readfirstlane(l[k].n);
-            mine += final_count(q[k], lane, n, eta);
-            for (uint32_t c = 64; c < (n + 1) / 2; c += 64) {
-                const uint32_t i = c + lane;
-                const int4 qq = i < l[k].cap2 ? l[k].src4[i] : make_int4(0, 0, 0, 0);
-                mine += final_count(qq, i, n, eta);
-            }
         }
     }
     }
@@ -1070,26 +1051,6 @@ __device__ __forceinline__ void final_body(const Params& p, Blk b)
             const uint32_t i = c + lane;
             const int4 q = i < l0[k].cap2 ? l0[k].src4[i] : make_int4(0, 0, 0, 0);
             final_emit(p, q, i, n, eta, cap, pos);
-        }
-    }
-    for (uint32_t g = first + K * kWavesPerBlock; g < last; g += K * kWavesPerBlock) {
-        FinalList l[K];
-        int4 q[K];
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const uint32_t sw = g + k * kWavesPerBlock;
-            l[k] = final_list(p, sw, sw < last);
-            q[k] = (uint32_t)lane < l[k].cap2 ? l[k].src4[lane] : make_int4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-            const uint32_t n = __builtin_amdgcn_readfirstlane(l[k].n);
-            final_emit(p, q[k], lane, n, eta, cap, pos);
-            for (uint32_t c = 64; c < (n + 1) / 2; c += 64) {
-                const uint32_t i = c + lane;
-                const int4 qq = i < l[k].cap2 ? l[k].src4[i] : make_int4(0, 0, 0, 0);
-                final_emit(p, qq, i, n, eta, cap, pos);
-            }
         }
     }
 }
@@ -1377,6 +1338,9 @@ void launch_lists(const Params& p, uint32_t grid_blocks, hipStream_t s)
 
 void launch_final_lists(const Params& p, uint32_t grid_blocks, hipStream_t s)
 {
+    // a block reads at most kFinalGroup lists per wave (see final_body)
+    const uint32_t least = (p.nwaves + kFinalGroup * kWavesPerBlock - 1) / (kFinalGroup * kWavesPerBlock);
+    if (grid_blocks < least) grid_blocks = least;
     hipLaunchKernelGGL(k_final_lists, dim3(grid_blocks), dim3(kBlock), 0, s, p);
 }
 
