@@ -198,6 +198,28 @@ int sidco_compress_typed(void *stream, const void *grad, int grad_dtype, float *
                          int32_t *out_idx, float *out_val, int32_t *out_count, float *out_eta);
 size_t sidco_workspace_bytes_typed(int64_t d, int grad_dtype, int has_residual);
 
+/* The other calls on a gradient of element type grad_dtype (SIDCO_GRAD_*): the
+ * batched call, the stage controller, and the two comparators.  Everything but
+ * the gradient's element type is as in the call of the same name without
+ * "_typed"; the residual, all arithmetic and the outputs stay fp32 / fp64.
+ * Without a residual a 16-bit gradient's widened copy lives in the workspace
+ * (sidco_workspace_bytes_typed / sidco_workspace_bytes_batched_typed); the DGC
+ * comparator needs none.                                                      */
+int sidco_compress_batched_typed(void *stream, const void *grad, int grad_dtype, float *residual,
+                                 const int64_t *offsets, int n, double delta, int dist, int stages,
+                                 int32_t *out_idx, float *out_val, const int64_t *out_offsets,
+                                 int32_t *out_counts, float *out_etas);
+size_t sidco_workspace_bytes_batched_typed(const int64_t *offsets, int n, int grad_dtype, int has_residual);
+struct sidco_controller;
+int sidco_controller_compress_typed(struct sidco_controller *c, void *stream, const void *grad, int grad_dtype,
+                                    float *residual, int64_t d, int32_t *out_idx, float *out_val,
+                                    int32_t *out_count, float *out_eta);
+int sidco_topk_typed(void *stream, const void *grad, int grad_dtype, float *residual, int64_t d, int64_t k,
+                     int32_t *out_idx, float *out_val, int32_t *out_count, float *out_kth);
+int sidco_dgc_typed(void *stream, const void *grad, int grad_dtype, float *residual, int64_t d, double delta,
+                    double sample_ratio, uint64_t seed,
+                    int32_t *out_idx, float *out_val, int32_t *out_count, float *out_eta);
+
 /*
  * Several vectors in one launch sequence: the tensors of one flat gradient
  * buffer, each sparsified on its own exactly as sidco_compress would (the cost of

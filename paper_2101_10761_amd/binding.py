@@ -17,7 +17,9 @@ DIST_EXP, DIST_GAMMA_GPD, DIST_GPD = 0, 1, 2
 ST_NONFINITE, ST_VAR_ZERO, ST_GAMMA_S, ST_GAMMA_CLAMP, ST_STOPPED, ST_OVERFLOW, ST_FALLBACK = 1, 2, 4, 8, 16, 32, 64
 
 EXPORTS = [
-    "sidco_compress", "sidco_compress_static", "sidco_static_max_elements", "sidco_static_init", "sidco_compress_typed", "sidco_workspace_bytes_typed", "sidco_compress_ex", "sidco_compress_batched", "sidco_batched_out_offsets",
+    "sidco_compress", "sidco_compress_static", "sidco_static_max_elements", "sidco_static_init", "sidco_compress_typed", "sidco_workspace_bytes_typed",
+    "sidco_compress_batched_typed", "sidco_workspace_bytes_batched_typed", "sidco_controller_compress_typed", "sidco_topk_typed",
+    "sidco_dgc_typed", "sidco_compress_ex", "sidco_compress_batched", "sidco_batched_out_offsets",
     "sidco_workspace_bytes_batched", "sidco_read_diag_batched", "sidco_topk", "sidco_dgc", "sidco_dgc_sizes", "sidco_dgc_result", "sidco_adapt_stages", "sidco_controller_create",
     "sidco_controller_destroy", "sidco_controller_stages", "sidco_controller_iteration",
     "sidco_controller_last_average", "sidco_controller_compress", "sidco_scatter_add", "sidco_scatter_check",
@@ -93,9 +95,21 @@ def load() -> C.CDLL:
     lib.sidco_workspace_bytes_typed.restype = C.c_size_t
     lib.sidco_topk.argtypes = [vp, f32p, f32p, C.c_int64, C.c_int64, i32p, f32p, i32p, f32p]
     lib.sidco_topk.restype = C.c_int
+    lib.sidco_topk_typed.argtypes = [vp, vp, C.c_int, f32p, C.c_int64, C.c_int64, i32p, f32p, i32p, f32p]
+    lib.sidco_topk_typed.restype = C.c_int
     i64p = C.POINTER(C.c_int64)
     lib.sidco_dgc.argtypes = [vp, f32p, f32p, C.c_int64, C.c_double, C.c_double, C.c_uint64, i32p, f32p, i32p, f32p]
     lib.sidco_dgc.restype = C.c_int
+    lib.sidco_dgc_typed.argtypes = [vp, vp, C.c_int, f32p, C.c_int64, C.c_double, C.c_double, C.c_uint64, i32p, f32p, i32p,
+                                    f32p]
+    lib.sidco_dgc_typed.restype = C.c_int
+    lib.sidco_compress_batched_typed.argtypes = [vp, vp, C.c_int, f32p, i64p, C.c_int, C.c_double, C.c_int, C.c_int, i32p,
+                                                 f32p, i64p, i32p, f32p]
+    lib.sidco_compress_batched_typed.restype = C.c_int
+    lib.sidco_workspace_bytes_batched_typed.argtypes = [i64p, C.c_int, C.c_int, C.c_int]
+    lib.sidco_workspace_bytes_batched_typed.restype = C.c_size_t
+    lib.sidco_controller_compress_typed.argtypes = [C.c_void_p, vp, vp, C.c_int, f32p, C.c_int64, i32p, f32p, i32p, f32p]
+    lib.sidco_controller_compress_typed.restype = C.c_int
     lib.sidco_dgc_sizes.argtypes = [C.c_int64, C.c_double, C.c_double, i64p]
     lib.sidco_dgc_sizes.restype = C.c_int
     lib.sidco_dgc_result.argtypes = [vp, i64p]
@@ -412,6 +426,73 @@ def sidco_dgc(grad, residual, delta: float, sample_ratio: float, seed: int, out_
                             _ptr(out_idx), _ptr(out_val), _ptr(out_count), _ptr(out_eta)), "sidco_dgc")
 
 
+def _grad_code(grad):
+    """SIDCO_GRAD_* of a gradient tensor (float32, float16 or bfloat16)."""
+    import torch
+    codes = {torch.float32: GRAD_F32, torch.float16: GRAD_F16, torch.bfloat16: GRAD_BF16}
+    if not isinstance(grad, torch.Tensor) or grad.dtype not in codes:
+        raise TypeError("grad must be a CUDA tensor of dtype float32, float16 or bfloat16")
+    _check_tensor(grad, grad.dtype, "grad")
+    return codes[grad.dtype]
+
+
+def sidco_topk_typed(grad, residual, k: int, out_idx, out_val, out_count, out_kth, stream=None) -> None:
+    """sidco_topk on a gradient tensor of dtype float32, float16 or bfloat16 (the residual stays float32)."""
+    import torch
+    code = _grad_code(grad)
+    d = grad.numel()
+    if residual is not None:
+        _check_tensor(residual, torch.float32, "residual", d)
+    _check_tensor(out_idx, torch.int32, "out_idx", k)
+    _check_tensor(out_val, torch.float32, "out_val", k)
+    _check_tensor(out_count, torch.int32, "out_count", 1)
+    _check_tensor(out_kth, torch.float32, "out_kth", 1)
+    _check(load().sidco_topk_typed(_stream_handle(stream), _ptr(grad), code, _ptr(residual), d, k, _ptr(out_idx),
+                                   _ptr(out_val), _ptr(out_count), _ptr(out_kth)), "sidco_topk_typed")
+
+
+def sidco_dgc_typed(grad, residual, delta: float, sample_ratio: float, seed: int, out_idx, out_val, out_count, out_eta,
+                    stream=None) -> None:
+    """sidco_dgc on a gradient tensor of dtype float32, float16 or bfloat16 (the residual stays float32)."""
+    import torch
+    code = _grad_code(grad)
+    d = grad.numel()
+    if residual is not None:
+        _check_tensor(residual, torch.float32, "residual", d)
+    k = sidco_dgc_sizes(d, delta, sample_ratio)[2]
+    _check_tensor(out_idx, torch.int32, "out_idx", k)
+    _check_tensor(out_val, torch.float32, "out_val", k)
+    _check_tensor(out_count, torch.int32, "out_count", 1)
+    _check_tensor(out_eta, torch.float32, "out_eta", 1)
+    _check(load().sidco_dgc_typed(_stream_handle(stream), _ptr(grad), code, _ptr(residual), d, delta, sample_ratio, seed,
+                                  _ptr(out_idx), _ptr(out_val), _ptr(out_count), _ptr(out_eta)), "sidco_dgc_typed")
+
+
+def sidco_compress_batched_typed(grad, residual, offsets, delta: float, dist: int, stages: int, out_idx, out_val,
+                                 out_offsets, out_counts, out_etas, stream=None) -> None:
+    """sidco_compress_batched on a gradient buffer of dtype float32, float16 or bfloat16."""
+    import torch
+    code = _grad_code(grad)
+    n = len(offsets) - 1
+    if grad.numel() < offsets[-1]:
+        raise ValueError(f"grad has {grad.numel()} elements, needs {offsets[-1]}")
+    if residual is not None:
+        _check_tensor(residual, torch.float32, "residual", offsets[-1])
+    _check_tensor(out_idx, torch.int32, "out_idx", out_offsets[-1])
+    _check_tensor(out_val, torch.float32, "out_val", out_offsets[-1])
+    _check_tensor(out_counts, torch.int32, "out_counts", n)
+    _check_tensor(out_etas, torch.float32, "out_etas", n)
+    _check(load().sidco_compress_batched_typed(_stream_handle(stream), _ptr(grad), code, _ptr(residual),
+                                               _i64_array(offsets), n, delta, dist, stages, _ptr(out_idx), _ptr(out_val),
+                                               _i64_array(out_offsets), _ptr(out_counts), _ptr(out_etas)),
+           "sidco_compress_batched_typed")
+
+
+def sidco_workspace_bytes_batched_typed(offsets, grad_dtype: int, has_residual: bool) -> int:
+    return int(load().sidco_workspace_bytes_batched_typed(_i64_array(offsets), len(offsets) - 1, grad_dtype,
+                                                          1 if has_residual else 0))
+
+
 def sidco_dgc_result(stream=None):
     """(n_s, k_s, first-pass count, entries written) of the last sidco_dgc; synchronises the stream."""
     out = (C.c_int64 * 4)()
@@ -462,9 +543,11 @@ class Controller:
         return int(load().sidco_controller_disturbed(self._h))
 
     def compress(self, grad, residual, out_idx, out_val, out_count, out_eta, stream=None) -> None:
+        """One iteration; `grad` may be float32 (sidco_controller_compress) or float16 / bfloat16
+        (sidco_controller_compress_typed)."""
         import torch
         d = grad.numel()
-        _check_tensor(grad, torch.float32, "grad")
+        code = _grad_code(grad)
         if residual is not None:
             _check_tensor(residual, torch.float32, "residual", d)
         cap = sidco_out_capacity(d, self.delta)
@@ -472,9 +555,15 @@ class Controller:
         _check_tensor(out_val, torch.float32, "out_val", cap)
         _check_tensor(out_count, torch.int32, "out_count", 1)
         _check_tensor(out_eta, torch.float32, "out_eta", 1)
-        _check(load().sidco_controller_compress(self._h, _stream_handle(stream), _ptr(grad), _ptr(residual), d,
-                                                _ptr(out_idx), _ptr(out_val), _ptr(out_count), _ptr(out_eta)),
-               "sidco_controller_compress")
+        if code == GRAD_F32:
+            _check(load().sidco_controller_compress(self._h, _stream_handle(stream), _ptr(grad), _ptr(residual), d,
+                                                    _ptr(out_idx), _ptr(out_val), _ptr(out_count), _ptr(out_eta)),
+                   "sidco_controller_compress")
+        else:
+            _check(load().sidco_controller_compress_typed(self._h, _stream_handle(stream), _ptr(grad), code,
+                                                          _ptr(residual), d, _ptr(out_idx), _ptr(out_val),
+                                                          _ptr(out_count), _ptr(out_eta)),
+                   "sidco_controller_compress_typed")
 
 
 def sidco_scatter_add(dense, idx, val, count, scale: float = 1.0, stream=None) -> None:

@@ -122,6 +122,11 @@ double default_delta1()
     return g_delta1;
 }
 
+int grad_type(int grad_dtype)
+{
+    return grad_dtype == SIDCO_GRAD_F16 ? kGradF16 : (grad_dtype == SIDCO_GRAD_BF16 ? kGradBf16 : kGradF32);
+}
+
 bool aligned4(const void* p) { return ((uintptr_t)p & 3u) == 0; }
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
@@ -680,8 +685,18 @@ int64_t sidco_controller_disturbed(const sidco_controller* c) { return c ? c->di
 int sidco_controller_compress(sidco_controller* c, void* stream, const float* grad, float* residual, int64_t d,
                               int32_t* out_idx, float* out_val, int32_t* out_count, float* out_eta)
 {
+    return sidco_controller_compress_typed(c, stream, grad, SIDCO_GRAD_F32, residual, d, out_idx, out_val, out_count,
+                                           out_eta);
+}
+
+int sidco_controller_compress_typed(sidco_controller* c, void* stream, const void* grad, int grad_dtype, float* residual,
+                                    int64_t d, int32_t* out_idx, float* out_val, int32_t* out_count, float* out_eta)
+{
     if (!c) return SIDCO_ERR_NULL;
-    int rc = check_common(grad, residual, d, c->dist, out_idx, out_val, out_count, out_eta);
+    if (grad_dtype != SIDCO_GRAD_F32 && grad_dtype != SIDCO_GRAD_F16 && grad_dtype != SIDCO_GRAD_BF16)
+        return SIDCO_ERR_ARG;
+    const int gt = grad_type(grad_dtype);
+    int rc = check_common(grad, residual, d, c->dist, out_idx, out_val, out_count, out_eta, gt == kGradF32 ? 4 : 2);
     if (rc != SIDCO_OK) return rc;
     double ratios[SIDCO_MAX_STAGES];
     const int M = sidco_stage_ratios(c->delta, c->stages, c->delta1, ratios);
@@ -689,7 +704,7 @@ int sidco_controller_compress(sidco_controller* c, void* stream, const float* gr
     // the count of reported pairs starts over on the first call after an adaptation
     const bool first_of_window = c->iteration % c->Q == 0;
     rc = run(stream, grad, residual, d, c->dist, ratios, M, out_idx, out_val, sidco_out_capacity(d, c->delta),
-             out_count, out_eta, first_of_window, kGradF32, c->id);
+             out_count, out_eta, first_of_window, gt, c->id);
     if (rc != SIDCO_OK) return rc;
     c->iteration += 1;
     if (c->iteration % c->Q != 0) return SIDCO_OK;
@@ -850,10 +865,30 @@ int sidco_compress_batched(void* stream, const float* grad, float* residual, con
                            int dist, int stages, int32_t* out_idx, float* out_val, const int64_t* out_offsets,
                            int32_t* out_counts, float* out_etas)
 {
+    return sidco_compress_batched_typed(stream, grad, SIDCO_GRAD_F32, residual, offsets, n, delta, dist, stages, out_idx,
+                                        out_val, out_offsets, out_counts, out_etas);
+}
+
+size_t sidco_workspace_bytes_batched_typed(const int64_t* offsets, int n, int grad_dtype, int has_residual)
+{
+    const size_t base = sidco_workspace_bytes_batched(offsets, n);
+    if (base == 0) return 0;
+    if (grad_dtype != SIDCO_GRAD_F32 && grad_dtype != SIDCO_GRAD_F16 && grad_dtype != SIDCO_GRAD_BF16) return 0;
+    const bool own_acc = grad_dtype != SIDCO_GRAD_F32 && !has_residual;
+    return base + (own_acc ? (base - head_bytes()) / 4 : 0);  // one float per list slot of one buffer
+}
+
+int sidco_compress_batched_typed(void* stream, const void* grad, int grad_dtype, float* residual, const int64_t* offsets,
+                                 int n, double delta, int dist, int stages, int32_t* out_idx, float* out_val,
+                                 const int64_t* out_offsets, int32_t* out_counts, float* out_etas)
+{
     if (!grad || !offsets || !out_idx || !out_val || !out_offsets || !out_counts || !out_etas) return SIDCO_ERR_NULL;
+    if (grad_dtype != SIDCO_GRAD_F32 && grad_dtype != SIDCO_GRAD_F16 && grad_dtype != SIDCO_GRAD_BF16)
+        return SIDCO_ERR_ARG;
+    const int gt = grad_type(grad_dtype);
     if (dist != SIDCO_DIST_EXP && dist != SIDCO_DIST_GAMMA_GPD && dist != SIDCO_DIST_GPD) return SIDCO_ERR_DIST;
-    if (!aligned4(grad) || !aligned4(residual) || !aligned4(out_idx) || !aligned4(out_val) || !aligned4(out_counts) ||
-        !aligned4(out_etas))
+    if (((uintptr_t)grad & (gt == kGradF32 ? 3u : 1u)) != 0 || !aligned4(residual) || !aligned4(out_idx) ||
+        !aligned4(out_val) || !aligned4(out_counts) || !aligned4(out_etas))
         return SIDCO_ERR_ALIGN;
     if (residual && (const void*)residual == (const void*)grad) return SIDCO_ERR_ARG;
     if (!(delta > 0.0 && delta < 1.0)) return SIDCO_ERR_DELTA;
@@ -870,7 +905,8 @@ int sidco_compress_batched(void* stream, const float* grad, float* residual, con
     rc = pick_ws(stream, true, &cp);
     if (rc != SIDCO_OK) return rc;
     WsCtx& c = *cp;
-    rc = ensure_workspace(c, head_bytes() + 2 * pl.slots * sizeof(int2));
+    const bool own_acc = gt != kGradF32 && !residual;  // the widened vectors need a home
+    rc = ensure_workspace(c, head_bytes() + 2 * pl.slots * sizeof(int2) + (own_acc ? pl.slots * sizeof(float) : 0));
     if (rc != SIDCO_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     WorkspaceHead* h = (WorkspaceHead*)c.ws;
@@ -923,7 +959,9 @@ int sidco_compress_batched(void* stream, const float* grad, float* residual, con
     memset(&a, 0, sizeof(a));
     a.tb = &h->batch;
     a.grad = grad;
+    a.gt = gt;
     a.residual = residual;
+    a.acc_own = own_acc ? (float*)((char*)c.ws + head_bytes() + 2 * pl.slots * sizeof(int2)) : nullptr;
     a.out_idx = out_idx;
     a.out_val = out_val;
     a.out_counts = out_counts;
@@ -1014,11 +1052,20 @@ int sidco_read_diag_batched(void* stream, int t, sidco_diag* host_out)
 int sidco_topk(void* stream, const float* grad, float* residual, int64_t d, int64_t k, int32_t* out_idx, float* out_val,
                int32_t* out_count, float* out_kth)
 {
+    return sidco_topk_typed(stream, grad, SIDCO_GRAD_F32, residual, d, k, out_idx, out_val, out_count, out_kth);
+}
+
+int sidco_topk_typed(void* stream, const void* grad, int grad_dtype, float* residual, int64_t d, int64_t k,
+                     int32_t* out_idx, float* out_val, int32_t* out_count, float* out_kth)
+{
     if (!grad || !out_idx || !out_val || !out_count || !out_kth) return SIDCO_ERR_NULL;
+    if (grad_dtype != SIDCO_GRAD_F32 && grad_dtype != SIDCO_GRAD_F16 && grad_dtype != SIDCO_GRAD_BF16)
+        return SIDCO_ERR_ARG;
     if (d < 1 || d > (int64_t)INT32_MAX) return SIDCO_ERR_SIZE;
     if (k < 1 || k > d) return SIDCO_ERR_SIZE;
-    if (!aligned4(grad) || !aligned4(residual) || !aligned4(out_idx) || !aligned4(out_val) || !aligned4(out_count) ||
-        !aligned4(out_kth))
+    const int gt = grad_type(grad_dtype);
+    if (((uintptr_t)grad & (gt == kGradF32 ? 3u : 1u)) != 0 || !aligned4(residual) || !aligned4(out_idx) ||
+        !aligned4(out_val) || !aligned4(out_count) || !aligned4(out_kth))
         return SIDCO_ERR_ALIGN;
     if (residual && (const void*)residual == (const void*)grad) return SIDCO_ERR_ARG;
     std::lock_guard<std::mutex> lock(g_mu);
@@ -1027,17 +1074,21 @@ int sidco_topk(void* stream, const float* grad, float* residual, int64_t d, int6
     int rc = pick_ws(stream, true, &cp, &dev);
     if (rc != SIDCO_OK) return rc;
     WsCtx& c = *cp;
-    rc = ensure_workspace(c, head_bytes() + 2 * seg_bytes(d));
+    const bool own_acc = gt != kGradF32 && !residual;  // the widened vector needs a home
+    rc = ensure_workspace(c, head_bytes() + 2 * seg_bytes(d) + (own_acc ? acc_bytes(d) : 0));
     if (rc != SIDCO_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     WorkspaceHead* h = (WorkspaceHead*)c.ws;
 
     Params q;
-    fill_common(q, h, grad, residual, d, SIDCO_DIST_EXP);
+    fill_common(q, h, grad, residual, d, SIDCO_DIST_EXP, gt,
+                own_acc ? (float*)((char*)c.ws + head_bytes() + 2 * seg_bytes(d)) : nullptr);
     TopkParams p;
     memset(&p, 0, sizeof(p));
     p.grad = grad;
+    p.gt = gt;
     p.residual = residual;
+    p.acc_w = q.acc_w;
     p.acc = q.acc;
     p.d = d;
     p.k = k;
@@ -1122,7 +1173,18 @@ int sidco_dgc_sizes(int64_t d, double delta, double sample_ratio, int64_t* sizes
 int sidco_dgc(void* stream, const float* grad, float* residual, int64_t d, double delta, double sample_ratio,
               uint64_t seed, int32_t* out_idx, float* out_val, int32_t* out_count, float* out_eta)
 {
-    int rc = check_common(grad, residual, d, SIDCO_DIST_EXP, out_idx, out_val, out_count, out_eta);
+    return sidco_dgc_typed(stream, grad, SIDCO_GRAD_F32, residual, d, delta, sample_ratio, seed, out_idx, out_val,
+                           out_count, out_eta);
+}
+
+int sidco_dgc_typed(void* stream, const void* grad, int grad_dtype, float* residual, int64_t d, double delta,
+                    double sample_ratio, uint64_t seed, int32_t* out_idx, float* out_val, int32_t* out_count,
+                    float* out_eta)
+{
+    if (grad_dtype != SIDCO_GRAD_F32 && grad_dtype != SIDCO_GRAD_F16 && grad_dtype != SIDCO_GRAD_BF16)
+        return SIDCO_ERR_ARG;
+    const int gt = grad_type(grad_dtype);
+    int rc = check_common(grad, residual, d, SIDCO_DIST_EXP, out_idx, out_val, out_count, out_eta, gt == kGradF32 ? 4 : 2);
     if (rc != SIDCO_OK) return rc;
     int64_t n_s, k_s, k;
     if (!dgc_sizes(d, delta, sample_ratio, &n_s, &k_s, &k)) return SIDCO_ERR_DELTA;
@@ -1138,10 +1200,12 @@ int sidco_dgc(void* stream, const float* grad, float* residual, int64_t d, doubl
     WorkspaceHead* h = (WorkspaceHead*)c.ws;
 
     Params q;
-    fill_common(q, h, grad, residual, d, SIDCO_DIST_EXP);
+    fill_common(q, h, grad, residual, d, SIDCO_DIST_EXP, gt);  // no stored acc without a residual: the one dense
+                                                              // pass keeps what it selects in the lists
     DgcParams p;
     memset(&p, 0, sizeof(p));
     p.grad = grad;
+    p.gt = gt;
     p.residual = residual;
     p.d = d;
     p.k = k;
@@ -1165,8 +1229,10 @@ int sidco_dgc(void* stream, const float* grad, float* residual, int64_t d, doubl
     TopkParams t;
     memset(&t, 0, sizeof(t));
     t.grad = grad;
+    t.gt = gt;
     t.residual = residual;
-    t.acc = q.acc;
+    t.acc_w = residual;
+    t.acc = residual;  // unused: the second select works on the lists alone
     t.d = d;
     t.k = k;
     t.k_from_state = 1;

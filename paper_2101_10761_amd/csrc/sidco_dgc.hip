@@ -59,7 +59,7 @@ __global__ __launch_bounds__(kBlock) void k_dgc_zero(DgcParams p)
 
 constexpr int kDrawsPerThread = 4;  // independent random accesses a thread has in flight
 
-template <bool EC>
+template <bool EC, int GT>
 __global__ __launch_bounds__(kBlock) void k_dgc_sample(DgcParams p)
 {
     __shared__ uint32_t sh_hist[kTopkBins];
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kBlock) void k_dgc_sample(DgcParams p)
             const uint32_t j = j0 + q * stride;
             const uint64_t u = splitmix64_at(p.seed, j) >> 32;
             const int64_t i = (int64_t)((u * (uint64_t)p.d) >> 32);
-            x[q] = j < p.n_s ? p.grad[i] : 0.0f;
+            x[q] = j < p.n_s ? load_grad1<GT>(p.grad, i) : 0.0f;
             r[q] = (EC && j < p.n_s) ? p.residual[i] : 0.0f;
         }
 #pragma unroll
@@ -134,7 +134,7 @@ __device__ __forceinline__ void dgc_emit(bool valid, float x, int32_t idx, float
     if (keep) atomicAdd(&sh_hist[mag_key(x) >> 20], 1u);
 }
 
-template <bool EC>
+template <bool EC, int GT>
 __global__ __launch_bounds__(kBlock, 4) void k_dgc_dense(DgcParams p)
 {
     __shared__ uint32_t sh_hist[kTopkBins];
@@ -165,7 +165,6 @@ __global__ __launch_bounds__(kBlock, 4) void k_dgc_dense(DgcParams p)
         lw.run = lw.fill = 0;
         uint32_t t = t0;
         if (p.vec_ok) {
-            const f4* __restrict__ g4 = reinterpret_cast<const f4*>(p.grad);
             f4* __restrict__ r4 = reinterpret_cast<f4*>(p.residual);
             constexpr uint32_t U = 4;
 #pragma unroll 1
@@ -174,7 +173,7 @@ __global__ __launch_bounds__(kBlock, 4) void k_dgc_dense(DgcParams p)
 #pragma unroll
                 for (uint32_t u = 0; u < U; ++u) {
                     const size_t i = (size_t)(t + u) * 64 + lane;
-                    a[u] = EC ? __builtin_nontemporal_load(g4 + i) : g4[i];
+                    a[u] = load_grad4<GT, EC>(p.grad, i);
                     if (EC) b[u] = r4[i];
                 }
 #pragma unroll
@@ -194,7 +193,7 @@ __global__ __launch_bounds__(kBlock, 4) void k_dgc_dense(DgcParams p)
             }
             for (; t < tf; ++t) {
                 const size_t i = (size_t)t * 64 + lane;
-                f4 c = g4[i];
+                f4 c = load_grad4<GT, false>(p.grad, i);
                 if (EC) {
                     c = c + r4[i];
                     r4[i] = c;
@@ -215,7 +214,7 @@ __global__ __launch_bounds__(kBlock, 4) void k_dgc_dense(DgcParams p)
                 const bool valid = i < p.d;
                 float c = 0.0f;
                 if (valid) {
-                    c = p.grad[i];
+                    c = load_grad1<GT>(p.grad, i);
                     if (EC) {
                         c = c + p.residual[i];
                         p.residual[i] = c;
@@ -293,10 +292,20 @@ void launch_dgc_zero(const DgcParams& p, hipStream_t s)
     hipLaunchKernelGGL(k_dgc_zero, dim3((3 * kTopkBins + kBlock - 1) / kBlock), dim3(kBlock), 0, s, p);
 }
 
+template <int GT>
+static void launch_dgc_sample_type(const DgcParams& p, hipStream_t s)
+{
+    if (p.residual) hipLaunchKernelGGL((k_dgc_sample<true, GT>), dim3(sample_grid(p)), dim3(kBlock), 0, s, p);
+    else hipLaunchKernelGGL((k_dgc_sample<false, GT>), dim3(sample_grid(p)), dim3(kBlock), 0, s, p);
+}
+
 void launch_dgc_sample(const DgcParams& p, hipStream_t s)
 {
-    if (p.residual) hipLaunchKernelGGL(k_dgc_sample<true>, dim3(sample_grid(p)), dim3(kBlock), 0, s, p);
-    else hipLaunchKernelGGL(k_dgc_sample<false>, dim3(sample_grid(p)), dim3(kBlock), 0, s, p);
+    switch (p.gt) {
+        case kGradF16: launch_dgc_sample_type<kGradF16>(p, s); break;
+        case kGradBf16: launch_dgc_sample_type<kGradBf16>(p, s); break;
+        default: launch_dgc_sample_type<kGradF32>(p, s); break;
+    }
 }
 
 void launch_dgc_digit(const DgcParams& p, int digit, hipStream_t s)
@@ -308,10 +317,20 @@ void launch_dgc_digit(const DgcParams& p, int digit, hipStream_t s)
     else hipLaunchKernelGGL(k_dgc_digit<2>, dim3(g), dim3(kBlock), 0, s, p);
 }
 
+template <int GT>
+static void launch_dgc_dense_type(const DgcParams& p, hipStream_t s)
+{
+    if (p.residual) hipLaunchKernelGGL((k_dgc_dense<true, GT>), dim3(p.nblocks), dim3(kBlock), 0, s, p);
+    else hipLaunchKernelGGL((k_dgc_dense<false, GT>), dim3(p.nblocks), dim3(kBlock), 0, s, p);
+}
+
 void launch_dgc_dense(const DgcParams& p, hipStream_t s)
 {
-    if (p.residual) hipLaunchKernelGGL(k_dgc_dense<true>, dim3(p.nblocks), dim3(kBlock), 0, s, p);
-    else hipLaunchKernelGGL(k_dgc_dense<false>, dim3(p.nblocks), dim3(kBlock), 0, s, p);
+    switch (p.gt) {
+        case kGradF16: launch_dgc_dense_type<kGradF16>(p, s); break;
+        case kGradBf16: launch_dgc_dense_type<kGradBf16>(p, s); break;
+        default: launch_dgc_dense_type<kGradF32>(p, s); break;
+    }
 }
 
 void launch_dgc_lists(const DgcParams& p, uint32_t grid, hipStream_t s)

@@ -133,9 +133,12 @@ struct TopkState {
 };
 
 struct TopkParams {
-    const float* grad;
+    const void* grad;       // d elements of type `gt`
+    int gt;                 // kGrad*
     float* residual;        // NULL: memoryless
-    const float* acc;       // residual, else grad
+    float* acc_w;           // where the first kernel stores acc: residual; a workspace buffer for a 16-bit gradient
+                            // without residual; NULL when acc is the fp32 gradient itself
+    const float* acc;       // acc_w, else grad
     int64_t d;
     int64_t k;
     int k_from_state;       // the last kernel takes k from st->k_eff (may be 0) instead of `k`
@@ -168,7 +171,8 @@ struct DgcState {
 };
 
 struct DgcParams {
-    const float* grad;
+    const void* grad; // d elements of type `gt`
+    int gt;           // kGrad*
     float* residual;  // NULL: memoryless
     int64_t d;
     int64_t k;        // target number of entries
@@ -226,8 +230,10 @@ struct BatchTable {
 // Kernel arguments of a batched launch (by value): what all vectors share.
 struct BatchArgs {
     BatchTable* tb;
-    const float* grad;      // base pointers of the call
+    const void* grad;       // base pointers of the call; the gradient's elements are of type `gt`
+    int gt;                 // kGrad*
     float* residual;
+    float* acc_own;         // workspace copy of acc for a 16-bit gradient without residual, else NULL
     int32_t* out_idx;
     float* out_val;
     int32_t* out_counts;

@@ -1171,17 +1171,17 @@ __device__ __forceinline__ Params batch_params(const BatchArgs& a, bool final_gr
     const uint32_t t = __builtin_amdgcn_readfirstlane((uint32_t)(final_grid ? a.tb->fmap[blockIdx.x] : a.tb->map[blockIdx.x]));
     const TensorDesc& ds = a.tb->desc[t];
     Params p = {};
-    p.grad = a.grad + ds.offset;
-    p.gt = kGradF32;
+    p.grad = reinterpret_cast<const char*>(a.grad) + ds.offset * (a.gt == kGradF32 ? 4 : 2);
+    p.gt = a.gt;
     p.residual = a.residual ? a.residual + ds.offset : nullptr;
-    p.acc_w = p.residual;
-    p.acc = p.residual ? p.residual : a.grad + ds.offset;
+    p.acc_w = p.residual ? p.residual : (a.acc_own ? a.acc_own + ds.offset : nullptr);
+    p.acc = p.acc_w ? p.acc_w : reinterpret_cast<const float*>(p.grad);
     p.d = ds.d;
     p.ntiles = (uint32_t)((ds.d + kTile - 1) / kTile);
     p.nfull = (uint32_t)(ds.d / kTile);
     p.nwaves = ds.nblocks * kWavesPerBlock < p.ntiles ? ds.nblocks * kWavesPerBlock : p.ntiles;
     p.nblocks = ds.nblocks;
-    p.vec_ok = (((uintptr_t)p.grad | (uintptr_t)p.residual) & 15u) == 0;
+    p.vec_ok = ((uintptr_t)p.grad & (a.gt == kGradF32 ? 15u : 7u)) == 0 && ((uintptr_t)p.acc_w & 15u) == 0;
     p.reverse = a.reverse;
     p.acc_reset = 1;
     p.dist = a.dist;
@@ -1220,12 +1220,12 @@ __global__ __launch_bounds__(kBlock, 4) void k_lists(Params p) { lists_body(p, w
 __global__ __launch_bounds__(kBlock) void k_final_lists(Params p) { final_body(p, whole_grid()); }
 __global__ __launch_bounds__(kBlock) void k_gather(Params p) { gather_body(p, whole_grid()); }
 
-template <int DIST, bool EC>
+template <int DIST, bool EC, int GT>
 __global__ __launch_bounds__(kBlock) void k_fit_batched(BatchArgs a)
 {
     Blk b;
     const Params p = batch_params(a, false, b);
-    fit_body<DIST, EC, kGradF32>(p, b);
+    fit_body<DIST, EC, GT>(p, b);
 }
 template <bool STATS, bool WRITE>
 __global__ __launch_bounds__(kBlock, 4) void k_compact_batched(BatchArgs a)
@@ -1350,21 +1350,31 @@ void launch_gather(const Params& p, hipStream_t s)
 }
 
 // batched: `blocks` is the sum of the vectors' grids (the last stage's own, smaller sum for launch_final)
-template <bool EC>
-static void launch_fit_batched_ec(const BatchArgs& a, uint32_t blocks, hipStream_t s)
+template <bool EC, int GT>
+static void launch_fit_batched_as(const BatchArgs& a, uint32_t blocks, hipStream_t s)
 {
     const dim3 grid(blocks), block(kBlock);
     switch (a.dist) {
-        case kDistExp: hipLaunchKernelGGL((k_fit_batched<kDistExp, EC>), grid, block, 0, s, a); break;
-        case kDistGamma: hipLaunchKernelGGL((k_fit_batched<kDistGamma, EC>), grid, block, 0, s, a); break;
-        default: hipLaunchKernelGGL((k_fit_batched<kDistGpd, EC>), grid, block, 0, s, a); break;
+        case kDistExp: hipLaunchKernelGGL((k_fit_batched<kDistExp, EC, GT>), grid, block, 0, s, a); break;
+        case kDistGamma: hipLaunchKernelGGL((k_fit_batched<kDistGamma, EC, GT>), grid, block, 0, s, a); break;
+        default: hipLaunchKernelGGL((k_fit_batched<kDistGpd, EC, GT>), grid, block, 0, s, a); break;
     }
+}
+
+template <int GT>
+static void launch_fit_batched_type(const BatchArgs& a, bool ec, uint32_t blocks, hipStream_t s)
+{
+    if (ec) launch_fit_batched_as<true, GT>(a, blocks, s);
+    else launch_fit_batched_as<false, GT>(a, blocks, s);
 }
 
 void launch_fit_batched(const BatchArgs& a, bool ec, uint32_t blocks, hipStream_t s)
 {
-    if (ec) launch_fit_batched_ec<true>(a, blocks, s);
-    else launch_fit_batched_ec<false>(a, blocks, s);
+    switch (a.gt) {
+        case kGradF16: launch_fit_batched_type<kGradF16>(a, ec, blocks, s); break;
+        case kGradBf16: launch_fit_batched_type<kGradBf16>(a, ec, blocks, s); break;
+        default: launch_fit_batched_type<kGradF32>(a, ec, blocks, s); break;
+    }
 }
 
 void launch_compact_batched(const BatchArgs& a, bool stats, bool write, uint32_t blocks, hipStream_t s)

@@ -49,9 +49,11 @@ __global__ __launch_bounds__(kBlock) void k_topk_zero(TopkParams p)
 // ---------------------------------------------------------------------------------------------
 // k_topk_hist: error-compensation add + digit-0 histogram
 // ---------------------------------------------------------------------------------------------
-template <bool EC>
+template <bool EC, int GT>
 __global__ __launch_bounds__(kBlock) void k_topk_hist(TopkParams p)
 {
+    // a 16-bit gradient is widened as it is read, and acc is always stored then (every later kernel reads fp32)
+    constexpr bool WRITE = EC || GT != kGradF32;
     __shared__ uint32_t sh_hist[kTopkBins];
     for (int i = threadIdx.x; i < kTopkBins; i += kBlock) sh_hist[i] = 0;
     __syncthreads();
@@ -62,8 +64,7 @@ __global__ __launch_bounds__(kBlock) void k_topk_hist(TopkParams p)
         const uint32_t tf = t1 < p.nfull ? t1 : p.nfull;
         uint32_t t = t0;
         if (p.vec_ok) {
-            const f4* __restrict__ g4 = reinterpret_cast<const f4*>(p.grad);
-            f4* __restrict__ r4 = reinterpret_cast<f4*>(p.residual);
+            f4* __restrict__ r4 = reinterpret_cast<f4*>(p.acc_w);
             constexpr int U = 4;
             for (; t + U <= tf; t += U) {
                 f4 a[U], b[U];
@@ -71,16 +72,14 @@ __global__ __launch_bounds__(kBlock) void k_topk_hist(TopkParams p)
                 for (int u = 0; u < U; ++u) {
                     const size_t i = (size_t)(t + u) * 64 + lane;
                     // read once per call when acc is stored elsewhere: keep it out of the caches' way
-                    a[u] = EC ? __builtin_nontemporal_load(g4 + i) : g4[i];
+                    a[u] = load_grad4<GT, WRITE>(p.grad, i);
                     if (EC) b[u] = r4[i];
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     f4 c = a[u];
-                    if (EC) {
-                        c = a[u] + b[u];
-                        r4[(size_t)(t + u) * 64 + lane] = c;
-                    }
+                    if (EC) c = a[u] + b[u];
+                    if (WRITE) r4[(size_t)(t + u) * 64 + lane] = c;
                     atomicAdd(&sh_hist[mag_key(c.x) >> 20], 1u);
                     atomicAdd(&sh_hist[mag_key(c.y) >> 20], 1u);
                     atomicAdd(&sh_hist[mag_key(c.z) >> 20], 1u);
@@ -89,11 +88,9 @@ __global__ __launch_bounds__(kBlock) void k_topk_hist(TopkParams p)
             }
             for (; t < tf; ++t) {
                 const size_t i = (size_t)t * 64 + lane;
-                f4 c = g4[i];
-                if (EC) {
-                    c = c + r4[i];
-                    r4[i] = c;
-                }
+                f4 c = load_grad4<GT, false>(p.grad, i);
+                if (EC) c = c + r4[i];
+                if (WRITE) r4[i] = c;
                 atomicAdd(&sh_hist[mag_key(c.x) >> 20], 1u);
                 atomicAdd(&sh_hist[mag_key(c.y) >> 20], 1u);
                 atomicAdd(&sh_hist[mag_key(c.z) >> 20], 1u);
@@ -105,11 +102,9 @@ __global__ __launch_bounds__(kBlock) void k_topk_hist(TopkParams p)
             for (int j = 0; j < 4; ++j) {
                 const int64_t i = (int64_t)t * kTile + lane * 4 + j;
                 if (i < p.d) {
-                    float c = p.grad[i];
-                    if (EC) {
-                        c = c + p.residual[i];
-                        p.residual[i] = c;
-                    }
+                    float c = load_grad1<GT>(p.grad, i);
+                    if (EC) c = c + p.acc_w[i];
+                    if (WRITE) p.acc_w[i] = c;
                     atomicAdd(&sh_hist[mag_key(c) >> 20], 1u);
                 }
             }
@@ -333,10 +328,20 @@ void launch_topk_zero(const TopkParams& p, hipStream_t s)
     hipLaunchKernelGGL(k_topk_zero, dim3((3 * kTopkBins + kBlock - 1) / kBlock), dim3(kBlock), 0, s, p);
 }
 
+template <int GT>
+static void launch_topk_hist_type(const TopkParams& p, hipStream_t s)
+{
+    if (p.residual) hipLaunchKernelGGL((k_topk_hist<true, GT>), dim3(p.nblocks), dim3(kBlock), 0, s, p);
+    else hipLaunchKernelGGL((k_topk_hist<false, GT>), dim3(p.nblocks), dim3(kBlock), 0, s, p);
+}
+
 void launch_topk_hist(const TopkParams& p, hipStream_t s)
 {
-    if (p.residual) hipLaunchKernelGGL(k_topk_hist<true>, dim3(p.nblocks), dim3(kBlock), 0, s, p);
-    else hipLaunchKernelGGL(k_topk_hist<false>, dim3(p.nblocks), dim3(kBlock), 0, s, p);
+    switch (p.gt) {
+        case kGradF16: launch_topk_hist_type<kGradF16>(p, s); break;
+        case kGradBf16: launch_topk_hist_type<kGradBf16>(p, s); break;
+        default: launch_topk_hist_type<kGradF32>(p, s); break;
+    }
 }
 
 void launch_topk_compact(const TopkParams& p, hipStream_t s)

@@ -211,6 +211,42 @@ def test_typed_argument_errors(lib):
     assert w(0, 1, 0) == 0 and w(1000, 7, 0) == 0
 
 
+def test_typed_variants_of_the_other_calls_reject_bad_arguments(lib):
+    """Each *_typed variant refuses an unknown element type and a misaligned gradient before touching the GPU;
+    its other checks are the plain call's."""
+    ok, odd, half = C.c_void_p(256), C.c_void_p(257), C.c_void_p(258)
+    off = (C.c_int64 * 3)(0, 1000, 3000)
+    oo = (C.c_int64 * 3)(0, 100, 300)
+    tk, dg, bt = lib.sidco_topk_typed, lib.sidco_dgc_typed, lib.sidco_compress_batched_typed
+    for bad in (3, -1):
+        assert tk(None, ok, bad, None, 1000, 10, ok, ok, ok, ok) == -9
+        assert dg(None, ok, bad, None, 1000, 0.01, 0.01, 0, ok, ok, ok, ok) == -9
+        assert bt(None, ok, bad, None, off, 2, 0.01, 0, 2, ok, ok, oo, ok, ok) == -9
+    for code in (0, 1, 2):
+        assert tk(None, None, code, None, 1000, 10, ok, ok, ok, ok) == -1
+        assert tk(None, ok, code, None, 1000, 0, ok, ok, ok, ok) == -2
+        assert tk(None, ok, code, None, 1000, 1001, ok, ok, ok, ok) == -2
+        assert tk(None, odd, code, None, 1000, 10, ok, ok, ok, ok) == -8
+        assert tk(None, ok, code, ok, 1000, 10, ok, ok, ok, ok) == -9          # residual aliases the gradient
+        assert dg(None, None, code, None, 1000, 0.01, 0.01, 0, ok, ok, ok, ok) == -1
+        assert dg(None, odd, code, None, 1000, 0.01, 0.01, 0, ok, ok, ok, ok) == -8
+        assert dg(None, ok, code, None, 1000, 1.5, 0.01, 0, ok, ok, ok, ok) == -3
+        assert bt(None, None, code, None, off, 2, 0.01, 0, 2, ok, ok, oo, ok, ok) == -1
+        assert bt(None, odd, code, None, off, 2, 0.01, 0, 2, ok, ok, oo, ok, ok) == -8
+        assert bt(None, ok, code, None, off, 2, 0.01, 5, 2, ok, ok, oo, ok, ok) == -5
+        assert bt(None, ok, code, None, off, 513, 0.01, 0, 2, ok, ok, oo, ok, ok) == -2
+    # an address that is a multiple of 2 but not of 4 suits a 16-bit gradient only
+    assert tk(None, half, 0, None, 1000, 10, ok, ok, ok, ok) == -8
+    assert dg(None, half, 0, None, 1000, 0.01, 0.01, 0, ok, ok, ok, ok) == -8
+    assert bt(None, half, 0, None, off, 2, 0.01, 0, 2, ok, ok, oo, ok, ok) == -8
+    assert lib.sidco_controller_compress_typed(None, None, ok, 1, None, 1000, ok, ok, ok, ok) == -1
+    w = lib.sidco_workspace_bytes_batched_typed
+    base = lib.sidco_workspace_bytes_batched(off, 2)
+    assert w(off, 2, 0, 0) == base and w(off, 2, 1, 1) == base and w(off, 2, 2, 1) == base
+    assert w(off, 2, 1, 0) == w(off, 2, 2, 0) >= base + 4 * 3000
+    assert w(off, 2, 9, 0) == 0 and w(None, 2, 1, 0) == 0
+
+
 def test_new_setters_reject_bad_arguments(lib):
     assert lib.sidco_set_delta1(0.0) == -3 and lib.sidco_set_delta1(1.0) == -3 and lib.sidco_set_delta1(float("nan")) == -3
     assert lib.sidco_controller_disturbed(None) == -1

@@ -10,15 +10,19 @@ pytestmark = pytest.mark.gpu
 
 def run_batched(g, r, offsets, delta, dist, stages, *, base_offset=0, repeat=1):
     """One batched call (or `repeat` identical ones, each on a fresh copy of the residual); returns one GpuResult
-    per tensor of the last call."""
+    per tensor of the last call.  `g` is a float32 numpy vector (sidco_compress_batched) or a 16-bit torch CPU
+    tensor (sidco_compress_batched_typed)."""
     import torch
     import paper_2101_10761_amd as sidco
     dev = torch.device("cuda:0")
     n = len(offsets) - 1
-    d = g.size
-    gbuf = torch.zeros(d + base_offset + 8, dtype=torch.float32, device=dev)
+    typed = isinstance(g, torch.Tensor)
+    g_cpu = g if typed else torch.from_numpy(g)
+    d = g_cpu.numel()
+    call = sidco.sidco_compress_batched_typed if typed else sidco.sidco_compress_batched
+    gbuf = torch.zeros(d + base_offset + 8, dtype=g_cpu.dtype, device=dev)
     gt = gbuf[base_offset:base_offset + d]
-    gt.copy_(torch.from_numpy(g))
+    gt.copy_(g_cpu)
     rbuf = rt = None
     if r is not None:
         rbuf = torch.zeros(d + base_offset + 8, dtype=torch.float32, device=dev)
@@ -33,12 +37,11 @@ def run_batched(g, r, offsets, delta, dist, stages, *, base_offset=0, repeat=1):
         out_val = torch.full((total + guard,), 7.0, dtype=torch.float32, device=dev)
         out_counts = torch.full((n,), -1, dtype=torch.int32, device=dev)
         out_etas = torch.full((n,), -1.0, dtype=torch.float32, device=dev)
-        sidco.sidco_compress_batched(gt, rt, offsets, delta, dist, stages, out_idx[:total], out_val[:total], out_offsets,
-                                     out_counts, out_etas)
+        call(gt, rt, offsets, delta, dist, stages, out_idx[:total], out_val[:total], out_offsets, out_counts, out_etas)
     torch.cuda.synchronize()
     assert torch.all(out_idx[total:] == -7) and torch.all(out_val[total:] == 7.0)
-    np.testing.assert_array_equal(gt.cpu().numpy().view(np.uint32), g.view(np.uint32))
-    assert torch.all(gbuf[base_offset + d:] == 0) and torch.all(gbuf[:base_offset] == 0)
+    assert torch.equal(gt.cpu().view(torch.uint8), g_cpu.view(torch.uint8))      # the gradient is read-only
+    assert torch.all(gbuf[base_offset + d:].view(torch.uint8) == 0) and torch.all(gbuf[:base_offset].view(torch.uint8) == 0)
     if rbuf is not None:
         assert torch.all(rbuf[base_offset + d:] == 0) and torch.all(rbuf[:base_offset] == 0)
     counts = out_counts.cpu().numpy()

@@ -12,7 +12,7 @@ def _run_controller(grads, residual0, *, delta, dist, stages, max_stages, Q, eps
     import torch
     import paper_2101_10761_amd as sidco
     dev = torch.device("cuda:0")
-    d = grads[0].size
+    d = grads[0].numel() if isinstance(grads[0], torch.Tensor) else grads[0].size
     ctrl = sidco.Controller(delta, dist, stages=stages, max_stages=max_stages, Q=Q, eps_high=eps, eps_low=eps,
                             delta1=delta1)
     cap = sidco.sidco_out_capacity(d, delta)
@@ -25,7 +25,8 @@ def _run_controller(grads, residual0, *, delta, dist, stages, max_stages, Q, eps
     for i, g in enumerate(grads, start=1):
         M = ctrl.stages
         assert ctrl.iteration == i - 1
-        ctrl.compress(torch.from_numpy(g).to(dev), rt, out_idx, out_val, out_count, out_eta)
+        ctrl.compress((g if isinstance(g, torch.Tensor) else torch.from_numpy(g)).to(dev), rt, out_idx, out_val,
+                      out_count, out_eta)
         diag = sidco.sidco_read_diag()
         k = int(out_count.item())
         Md = diag.stages

@@ -9,15 +9,18 @@ pytestmark = pytest.mark.gpu
 
 
 def run_dgc(g, r, delta, rho, seed, *, grad_offset=0, res_offset=0):
+    """`g` is a float32 numpy vector (sidco_dgc) or a 16-bit torch CPU tensor (sidco_dgc_typed)."""
     import torch
     import paper_2101_10761_amd as sidco
 
     dev = torch.device("cuda:0")
-    d = g.size
+    typed = isinstance(g, torch.Tensor)
+    g_cpu = g if typed else torch.from_numpy(g)
+    d = g_cpu.numel()
     k = sidco.sidco_dgc_sizes(d, delta, rho)[2]
-    gbuf = torch.zeros(d + grad_offset + 8, dtype=torch.float32, device=dev)
+    gbuf = torch.zeros(d + grad_offset + 8, dtype=g_cpu.dtype, device=dev)
     gt = gbuf[grad_offset:grad_offset + d]
-    gt.copy_(torch.from_numpy(g))
+    gt.copy_(g_cpu)
     rt = None
     if r is not None:
         rbuf = torch.zeros(d + res_offset + 8, dtype=torch.float32, device=dev)
@@ -28,14 +31,15 @@ def run_dgc(g, r, delta, rho, seed, *, grad_offset=0, res_offset=0):
     out_val = torch.full((k + guard,), 7.0, dtype=torch.float32, device=dev)
     out_count = torch.full((1,), -1, dtype=torch.int32, device=dev)
     out_eta = torch.full((1,), -1.0, dtype=torch.float32, device=dev)
-    sidco.sidco_dgc(gt, rt, delta, rho, seed, out_idx[:k], out_val[:k], out_count, out_eta)
+    (sidco.sidco_dgc_typed if typed else sidco.sidco_dgc)(gt, rt, delta, rho, seed, out_idx[:k], out_val[:k], out_count,
+                                                          out_eta)
     torch.cuda.synchronize()
     n_s, k_s, first, written = sidco.sidco_dgc_result()
     count = int(out_count.item())
     assert written == count and 0 <= count <= k
     assert torch.all(out_idx[count:] == -7) and torch.all(out_val[count:] == 7.0)
-    np.testing.assert_array_equal(gt.cpu().numpy().view(np.uint32), g.view(np.uint32))
-    assert torch.all(gbuf[grad_offset + d:] == 0)
+    assert torch.equal(gt.cpu().view(torch.uint8), g_cpu.view(torch.uint8))      # the gradient is read-only
+    assert torch.all(gbuf[grad_offset + d:].view(torch.uint8) == 0) and torch.all(gbuf[:grad_offset].view(torch.uint8) == 0)
     if rt is not None:
         assert torch.all(rbuf[res_offset + d:] == 0)
     return dict(idx=out_idx[:count].cpu().numpy(), val=out_val[:count].cpu().numpy(), count=count,

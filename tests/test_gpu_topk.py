@@ -8,14 +8,17 @@ pytestmark = pytest.mark.gpu
 
 
 def run_topk(g, r, k, *, grad_offset=0, res_offset=0):
+    """`g` is a float32 numpy vector (sidco_topk) or a 16-bit torch CPU tensor (sidco_topk_typed)."""
     import torch
     import paper_2101_10761_amd as sidco
 
     dev = torch.device("cuda:0")
-    d = g.size
-    gbuf = torch.zeros(d + grad_offset + 8, dtype=torch.float32, device=dev)
+    typed = isinstance(g, torch.Tensor)
+    g_cpu = g if typed else torch.from_numpy(g)
+    d = g_cpu.numel()
+    gbuf = torch.zeros(d + grad_offset + 8, dtype=g_cpu.dtype, device=dev)
     gt = gbuf[grad_offset:grad_offset + d]
-    gt.copy_(torch.from_numpy(g))
+    gt.copy_(g_cpu)
     rt = None
     if r is not None:
         rbuf = torch.zeros(d + res_offset + 8, dtype=torch.float32, device=dev)
@@ -26,11 +29,11 @@ def run_topk(g, r, k, *, grad_offset=0, res_offset=0):
     out_val = torch.full((k + guard,), 7.0, dtype=torch.float32, device=dev)
     out_count = torch.full((1,), -1, dtype=torch.int32, device=dev)
     out_kth = torch.full((1,), -1.0, dtype=torch.float32, device=dev)
-    sidco.sidco_topk(gt, rt, k, out_idx[:k], out_val[:k], out_count, out_kth)
+    (sidco.sidco_topk_typed if typed else sidco.sidco_topk)(gt, rt, k, out_idx[:k], out_val[:k], out_count, out_kth)
     torch.cuda.synchronize()
     assert torch.all(out_idx[k:] == -7) and torch.all(out_val[k:] == 7.0)
-    np.testing.assert_array_equal(gt.cpu().numpy().view(np.uint32), g.view(np.uint32))
-    assert torch.all(gbuf[grad_offset + d:] == 0)
+    assert torch.equal(gt.cpu().view(torch.uint8), g_cpu.view(torch.uint8))      # the gradient is read-only
+    assert torch.all(gbuf[grad_offset + d:].view(torch.uint8) == 0) and torch.all(gbuf[:grad_offset].view(torch.uint8) == 0)
     if rt is not None:
         assert torch.all(rbuf[res_offset + d:] == 0)
     return (out_idx[:k].cpu().numpy(), out_val[:k].cpu().numpy(), int(out_count.item()), np.float32(out_kth.item()),

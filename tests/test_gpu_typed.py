@@ -160,3 +160,99 @@ def test_long_vector_without_residual(oracle, kind):
     res = run_typed(g16, None, 2, 0.001, 3, grad_offset=4)
     check_parity(oracle, gw, None, 2, sidco.sidco_stage_ratios(0.001, 3), res,
                  capacity=sidco.sidco_out_capacity(d, 0.001), label=f"{kind} d {d} memoryless")
+
+
+# ---- 16-bit gradients through the batched call, the controller and the two comparators -------------------------------
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("with_residual", [True, False])
+def test_batched_ragged_tensors(oracle, kind, with_residual):
+    """50 ragged tensors at odd offsets: a 16-bit tensor whose first element is not 8-byte aligned takes the
+    element-wise path, the others the vector path."""
+    from test_gpu_batched import run_batched, check_batched
+    from paper_2101_10761_amd import workloads
+    w = workloads.config4(d=6_600_000, ragged=True)
+    offs = [int(x) for x in w.tensor_offsets]
+    g16, gw = narrow(w.grad * np.float32(30.0), kind)      # scales over three decades, some fp16 subnormals remain
+    r = np.random.default_rng(4).laplace(0, 1e-4, size=w.d).astype(np.float32) if with_residual else None
+    for dist, stages, delta, base in [(1, 2, 1e-3, 0), (2, 3, 1e-2, 1)]:
+        out = run_batched(g16, r, offs, delta, dist, stages, base_offset=base)
+        check_batched(oracle, gw, r, offs, delta, dist, stages, out, f"{kind} batched dist={dist} M={stages}")
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_batched_small_tensors(oracle, kind):
+    from test_gpu_batched import run_batched, check_batched
+    rng = np.random.default_rng(8)
+    sizes = [1, 2, 63, 64, 255, 256, 257, 1000, 4099, 1, 70_001, 300_000, 5, 2_000_003, 17]
+    offs = [0] + [int(x) for x in np.cumsum(sizes)]
+    g16, gw = narrow(rng.laplace(0, 1e-2, size=offs[-1]).astype(np.float32), kind)
+    r = rng.laplace(0, 3e-3, size=offs[-1]).astype(np.float32)
+    for res_in in (r, None):
+        out = run_batched(g16, res_in, offs, 0.01, 0, 3, base_offset=3)
+        check_batched(oracle, gw, res_in, offs, 0.01, 0, 3, out, f"{kind} batched sizes ec={res_in is not None}")
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_controller_on_16_bit_gradients(oracle, kind):
+    """The controller's loop on 16-bit gradients equals the oracle's loop on the widened ones: same stage counts,
+    same selection, same residual at every iteration."""
+    from test_gpu_controller import _run_controller
+    import paper_2101_10761_amd as sidco
+    rng = np.random.default_rng(93)
+    d, delta, Q, W = 400_003, 0.001, 4, 4
+    pairs = [narrow((rng.standard_normal(d) * 1e-2).astype(np.float32), kind) for _ in range(W * Q)]
+    r0 = np.zeros(d, np.float32)
+    got = _run_controller([p[0] for p in pairs], r0, delta=delta, dist=0, stages=1, max_stages=6, Q=Q)
+    ref = oracle.adaptive_run([p[1] for p in pairs], r0, delta=delta, dist=0, stages=1, max_stages=6, Q=Q)
+    assert [m for m, _, _ in got] == [m for m, _ in ref]
+    assert len({m for m, _, _ in got}) > 1                 # the stage count did change on the way
+    r = r0
+    for i, ((M, out, _), (_, o)) in enumerate(zip(got, ref)):
+        check_parity(oracle, pairs[i][1], r, 0, oracle.schedule(delta, M, 0.25), out,
+                     capacity=sidco.sidco_out_capacity(d, delta), label=f"{kind} controller it={i + 1} M={M}")
+        assert out.count == o.count
+        r = out.residual
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("d", [1, 257, 70_001, 2_100_003])
+def test_topk_on_16_bit_gradients(oracle, kind, d):
+    """16-bit values tie often (few distinct magnitudes), so the k-th magnitude is usually shared."""
+    from test_gpu_topk import run_topk, check_topk
+    rng = np.random.default_rng(900 + d % 89)
+    g16, gw = narrow(rng.laplace(0, 1e-2, size=d).astype(np.float32), kind)
+    r = rng.laplace(0, 3e-3, size=d).astype(np.float32)
+    for k in sorted({1, max(1, d // 1000), max(1, d // 10), d}):
+        for res, go in ((r, 0), (None, 0), (r, 1), (None, 3)):
+            check_topk(oracle, gw, res, k, run_topk(g16, res, k, grad_offset=go, res_offset=go % 2),
+                       label=f"{kind} top-k d={d} k={k} ec={res is not None} offset={go}")
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+@pytest.mark.parametrize("with_residual", [False, True])
+def test_dgc_on_16_bit_gradients(oracle, kind, with_residual):
+    from test_gpu_dgc import run_dgc, check_dgc
+    rng = np.random.Generator(np.random.PCG64(511))
+    branches = set()
+    for seed, d in enumerate([1, 999, 250_003, 2_400_001]):
+        g16, gw = narrow(rng.laplace(0.0, 1e-2, d).astype(np.float32), kind)
+        r = rng.laplace(0.0, 3e-3, d).astype(np.float32) if with_residual else None
+        delta, rho = (0.001, 0.05) if seed % 2 else (0.01, 0.01)
+        out = run_dgc(g16, r, delta, rho, seed, grad_offset=seed % 2)
+        ref = check_dgc(oracle, gw, r, delta, rho, seed, out, f"{kind} dgc seed {seed} d {d}")
+        branches.add(ref.first_pass > out["k"])
+    assert branches                                           # at least one branch ran; both are checked when hit
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_comparators_at_headline_size(oracle, kind):
+    from test_gpu_topk import run_topk, check_topk
+    from test_gpu_dgc import run_dgc, check_dgc
+    from paper_2101_10761_amd import workloads
+    w = workloads.config3()
+    g16, gw = narrow(w.grad, kind)
+    k = max(1, int(w.d * w.delta))
+    check_topk(oracle, gw, w.residual, k, run_topk(g16, w.residual, k), label=f"{kind} cfg3 top-k")
+    out = run_dgc(g16, w.residual, w.delta, 0.01, 3)
+    check_dgc(oracle, gw, w.residual, w.delta, 0.01, 3, out, f"{kind} cfg3 dgc")
