@@ -255,11 +255,13 @@ void free_ws(WsCtx& c)
 // Grid of the last stage's kernel when it reads survivor lists.  The host only knows the expected
 // number of entries; a wrong guess costs time, never correctness.  Every block reserves its output
 // range with one same-address atomic, so few blocks for short lists (4 lists per wave, everything loaded
-// before the prologue) and more blocks for long ones.
+// before the prologue) and one list per wave for long ones (millions of pairs out: 1057 us against 1152 us per
+// call with 512 instead of 256 blocks at d = 138 M, delta = 0.1, where the kernel is bound by the scattered
+// stores that clear the residual; no difference at delta = 0.01 and below).
 uint32_t final_grid(const Params& p, double expect)
 {
     uint32_t grid = (p.nwaves + kFinalLists - 1) / kFinalLists;
-    if (expect > 4.0e6) grid = 256;
+    if (expect > 4.0e6) grid = p.nblocks;
     if (grid > p.nblocks) grid = p.nblocks;
     if (grid < 1) grid = 1;
     return grid;

@@ -625,17 +625,22 @@ __device__ __forceinline__ void load_tiles(f4 (&a)[U], const f4* __restrict__ x4
 // plus a few hundred dependent fp64 instructions, 4-5 us in which the memory pipes would otherwise run
 // dry after the first batch.  PRE is a template parameter and the caller's loads are unconditional:
 // loads under a run-time condition come with copies that the compiler waits for on the spot.
-// After the prefetched batches, plain load-then-process steps: with 16 waves per CU in flight, a second
-// register buffer per wave gained nothing for the statistics alone and lost 2-3 us once list entries are
-// staged as well (measured).  One copy of the loop body: the next prefetched batch moves up into a[0 .. U)
-// by register copies (PRE - 1 times U moves per wave in all).
+// After them the wave stays one batch ahead (kCompactPipeline): the request for batch k + PRE goes out
+// before batch k is processed, into the last register batch, and the batches move up by register copies
+// once batch k is done - one copy of the loop body (two inlined copies cost more in code size and
+// registers than they gained).  Measured against load-then-process steps with two prefetched batches:
+// 1-2 us less per dense stage at 14.7 M to 66 M elements, nothing at 138 M, where the stage is bound by
+// what the memory system still has to write back for the pass before it.
 __device__ __forceinline__ uint32_t dense_batch_tile(const Params& p, uint32_t t0, uint32_t tf, uint32_t U, uint32_t k)
 {
     return p.reverse ? tf - (k + 1) * U : t0 + k * U;
 }
 
+// register batches a wave holds: the PRE prefetched ones and, when pipelined, the one in flight behind them
+constexpr int dense_batches(int PRE) { return PRE > 0 ? PRE + (kCompactPipeline ? 1 : 0) : 1; }
+
 template <bool STATS, bool WRITE, int U, int PRE>
-__device__ __forceinline__ void compact_dense(const Params& p, f4 (&a)[(PRE > 0 ? PRE : 1) * U], uint32_t t0, uint32_t t1,
+__device__ __forceinline__ void compact_dense(const Params& p, f4 (&a)[dense_batches(PRE) * U], uint32_t t0, uint32_t t1,
                                               uint32_t tf, int lane, float eta_s, float eta_w, ListWriter& lw,
                                               uint32_t& ns, double& sy, double& syy)
 {
@@ -646,15 +651,29 @@ __device__ __forceinline__ void compact_dense(const Params& p, f4 (&a)[(PRE > 0 
 #pragma unroll 1  // unrolled, the batches' loads pile up in registers and halve the occupancy
         for (uint32_t k = 0; k < nb; ++k) {
             const uint32_t t = dense_batch_tile(p, t0, tf, U, k);
-            if (k >= (uint32_t)PRE) {
+            if constexpr (PRE > 0 && kCompactPipeline) {
+                // Batch k + PRE is requested before batch k is processed, so the wave keeps a batch in flight
+                // while it computes (per-wave time max(latency, arithmetic) instead of their sum).  The load is
+                // unconditional - the last batches are requested again, from L2, instead of a load under a
+                // condition - and lands in the last register batch; the batches move up once batch k is done.
+                const uint32_t kn = k + PRE < nb ? k + PRE : nb - 1;
+                const uint32_t tn = dense_batch_tile(p, t0, tf, U, kn);
 #pragma unroll
-                for (int u = 0; u < U; ++u) a[u] = x4[(size_t)(t + u) * 64 + lane];
-            }
-            compact_loaded<STATS, WRITE, U>(a, t, lane, eta_s, eta_w, lw, ns, sy, syy);
-            if constexpr (PRE > 1) {
-                if (k + 1 < (uint32_t)PRE) {  // the next prefetched batch moves up
+                for (int u = 0; u < U; ++u) a[PRE * U + u] = x4[(size_t)(tn + u) * 64 + lane];
+                compact_loaded<STATS, WRITE, U>(a, t, lane, eta_s, eta_w, lw, ns, sy, syy);
 #pragma unroll
-                    for (int u = 0; u < (PRE - 1) * U; ++u) a[u] = a[u + U];
+                for (int u = 0; u < PRE * U; ++u) a[u] = a[u + U];
+            } else {
+                if (k >= (uint32_t)PRE) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) a[u] = x4[(size_t)(t + u) * 64 + lane];
+                }
+                compact_loaded<STATS, WRITE, U>(a, t, lane, eta_s, eta_w, lw, ns, sy, syy);
+                if constexpr (PRE > 1) {
+                    if (k + 1 < (uint32_t)PRE) {  // the next prefetched batch moves up
+#pragma unroll
+                        for (int u = 0; u < (PRE - 1) * U; ++u) a[u] = a[u + U];
+                    }
                 }
             }
         }
@@ -762,7 +781,7 @@ __device__ __forceinline__ void compact_body(const Params& p, Blk b)
     // them), then the first batches of tiles, so that the stream runs while the partial sums are reduced
     // and the closed form is evaluated.
     PrologueLoads g = prologue_load(p, b, false);
-    f4 a0[(PRE > 0 ? PRE : 1) * U];
+    f4 a0[dense_batches(PRE) * U];
     if constexpr (PRE > 0) {
         const f4* __restrict__ x4 = reinterpret_cast<const f4*>(p.acc);
 #pragma unroll
