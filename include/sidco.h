@@ -127,12 +127,10 @@ typedef struct sidco_diag {
  * The pairs are not sorted by index.  Buffers are owned by the caller; the library owns only
  * its workspaces, which it allocates on first use per stream (hipMalloc) and
  * grows when d grows, unless sidco_set_workspace was called.
- * This is the entry point with the signature the project brief names; where that
- * brief's sketch proposed companions by other names, these are the ones built:
- * explicit stage ratios are an argument of sidco_compress_ex rather than state
- * set by a "set_stage_ratios" call (sidco_set_delta1 exists for callers that must
- * stay on this signature), and "get_diag" is sidco_read_diag (sidco_get_diag is
- * exported as another name of the same function).
+ * Explicit stage ratios are an argument of sidco_compress_ex rather than state
+ * set by a separate call (sidco_set_delta1 exists for callers that must stay on
+ * this signature); the diagnostics of a call are read with sidco_read_diag
+ * (sidco_get_diag is exported as another name of the same function).
  */
 int sidco_compress(void *stream, const float *grad, float *residual, int64_t d,
                    double delta, int dist, int stages,
