@@ -258,10 +258,9 @@ void launch_gather_batched(const BatchArgs& a, uint32_t blocks, hipStream_t s);
 void launch_clear_u32(uint32_t* p, hipStream_t s);
 void launch_scatter_add(float* dense, int64_t d, const int32_t* idx, const float* val, const int32_t* count,
                         int64_t capacity, float scale, uint32_t* bad, hipStream_t s);
-// batches of 4 tiles that a dense stage's waves load before their threshold is known (long vectors only), and
-// whether they then keep one batch in flight while they process the one before it (see compact_dense)
+// batches of 4 tiles that a dense stage's waves load before their threshold is known and then stay ahead of
+// the batch they process (long vectors only; see compact_dense)
 constexpr int kCompactPrefetch = 1;
-constexpr bool kCompactPipeline = true;
 // k_fit's shape for large vectors (see k_fit_flat): one float4 per thread, 256-thread blocks; from the
 // length at which the faster sweep pays for the extra kernel that folds its partial sums
 constexpr int kFlatBlock = 256;

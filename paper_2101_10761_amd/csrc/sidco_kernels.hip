@@ -625,7 +625,7 @@ __device__ __forceinline__ void load_tiles(f4 (&a)[U], const f4* __restrict__ x4
 // plus a few hundred dependent fp64 instructions, 4-5 us in which the memory pipes would otherwise run
 // dry after the first batch.  PRE is a template parameter and the caller's loads are unconditional:
 // loads under a run-time condition come with copies that the compiler waits for on the spot.
-// After them the wave stays one batch ahead (kCompactPipeline): the request for batch k + PRE goes out
+// After them the wave stays PRE batches ahead: the request for batch k + PRE goes out
 // before batch k is processed, into the last register batch, and the batches move up by register copies
 // once batch k is done - one copy of the loop body (two inlined copies cost more in code size and
 // registers than they gained).  Measured against load-then-process steps with two prefetched batches:
@@ -636,8 +636,8 @@ __device__ __forceinline__ uint32_t dense_batch_tile(const Params& p, uint32_t t
     return p.reverse ? tf - (k + 1) * U : t0 + k * U;
 }
 
-// register batches a wave holds: the PRE prefetched ones and, when pipelined, the one in flight behind them
-constexpr int dense_batches(int PRE) { return PRE > 0 ? PRE + (kCompactPipeline ? 1 : 0) : 1; }
+// register batches a wave holds: the PRE prefetched ones and the one in flight behind them
+constexpr int dense_batches(int PRE) { return PRE > 0 ? PRE + 1 : 1; }
 
 template <bool STATS, bool WRITE, int U, int PRE>
 __device__ __forceinline__ void compact_dense(const Params& p, f4 (&a)[dense_batches(PRE) * U], uint32_t t0, uint32_t t1,
@@ -651,7 +651,7 @@ __device__ __forceinline__ void compact_dense(const Params& p, f4 (&a)[dense_bat
 #pragma unroll 1  // unrolled, the batches' loads pile up in registers and halve the occupancy
         for (uint32_t k = 0; k < nb; ++k) {
             const uint32_t t = dense_batch_tile(p, t0, tf, U, k);
-            if constexpr (PRE > 0 && kCompactPipeline) {
+            if constexpr (PRE > 0) {
                 // Batch k + PRE is requested before batch k is processed, so the wave keeps a batch in flight
                 // while it computes (per-wave time max(latency, arithmetic) instead of their sum).  The load is
                 // unconditional - the last batches are requested again, from L2, instead of a load under a
@@ -664,17 +664,9 @@ __device__ __forceinline__ void compact_dense(const Params& p, f4 (&a)[dense_bat
 #pragma unroll
                 for (int u = 0; u < PRE * U; ++u) a[u] = a[u + U];
             } else {
-                if (k >= (uint32_t)PRE) {
 #pragma unroll
-                    for (int u = 0; u < U; ++u) a[u] = x4[(size_t)(t + u) * 64 + lane];
-                }
+                for (int u = 0; u < U; ++u) a[u] = x4[(size_t)(t + u) * 64 + lane];
                 compact_loaded<STATS, WRITE, U>(a, t, lane, eta_s, eta_w, lw, ns, sy, syy);
-                if constexpr (PRE > 1) {
-                    if (k + 1 < (uint32_t)PRE) {  // the next prefetched batch moves up
-#pragma unroll
-                        for (int u = 0; u < (PRE - 1) * U; ++u) a[u] = a[u + U];
-                    }
-                }
             }
         }
         const uint32_t tr = p.reverse ? t0 : t0 + nb * U;
@@ -1342,9 +1334,11 @@ static void launch_compact_pre(const Params& p, bool stats, bool write, hipStrea
 
 void launch_compact(const Params& p, bool stats, bool write, hipStream_t s)
 {
-    // prefetch before the prologue only where every wave has that many complete tiles to itself
+    // Prefetch before the prologue only where every wave has that many complete tiles to itself: a wave owns
+    // at least floor(nfull / nwaves) tiles, and the last wave's last tile may be the incomplete one, which a
+    // whole-tile load must not touch - hence one tile more than the prefetched batches hold.
     const uint32_t per_wave = p.nwaves ? p.nfull / p.nwaves : 0;
-    if (p.vec_ok && p.nwaves == (uint32_t)kMaxWaves && per_wave >= (uint32_t)(kCompactPrefetch * 4))
+    if (p.vec_ok && p.nwaves == (uint32_t)kMaxWaves && per_wave >= (uint32_t)(kCompactPrefetch * 4 + 1))
         launch_compact_pre<kCompactPrefetch>(p, stats, write, s);
     else
         launch_compact_pre<0>(p, stats, write, s);

@@ -37,6 +37,20 @@ def test_small_sizes_all_laws(oracle, d, dist):
             check_parity(oracle, g, res_in, dist, ratios, out, label=f"d={d} dist={dist} M={stages} ec={res_in is not None}")
 
 
+@pytest.mark.parametrize("tiles_per_wave,tail", [(4, 100), (5, 0), (5, 100), (5, 255), (6, 1), (9, 17)])
+def test_lengths_around_the_prefetching_dense_stage(oracle, tiles_per_wave, tail):
+    """From 5 complete 256-element tiles per wave (4096 waves) the dense stages request their first tiles before
+    the threshold is known and stay one batch ahead; the ragged last tile belongs to the last wave and is never
+    part of such a request.  Ratios 0.25, 0.63, 0.63 make both directions run (stage 1 walks back, stage 2 forward)."""
+    d = tiles_per_wave * 4096 * 256 + tail
+    g, r = _inputs(d, 40 + tiles_per_wave + tail)
+    for dist, ratios in ((0, oracle.schedule(0.1, 3, 0.25)), (2, oracle.schedule(0.001, 3, 0.25))):
+        for res_in in (r, None):
+            out = run_gpu(g, res_in, dist, ratios)
+            check_parity(oracle, g, res_in, dist, ratios, out,
+                         label=f"tiles/wave {tiles_per_wave} tail {tail} dist {dist} ec={res_in is not None}")
+
+
 @pytest.mark.parametrize("goff,roff", [(1, 0), (0, 3), (1, 1), (2, 3)])
 def test_unaligned_slices(oracle, goff, roff):
     """Per-tensor slices of a flat buffer start at any 4-byte boundary."""
