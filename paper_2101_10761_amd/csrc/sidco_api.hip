@@ -788,6 +788,7 @@ struct BatchPlan {
     std::vector<uint16_t> map, fmap;
     uint32_t blocks = 0, final_blocks = 0;
     uint64_t slots = 0;  // survivor-list slots of all vectors
+    uint32_t flat_gx = 0;  // > 0: the first pass runs in the flat shape with this many chunks per block (see below)
 };
 
 // Splits the 512 blocks of a launch over the vectors in proportion to their lengths (at least one each).
@@ -832,6 +833,29 @@ int plan_batch(const int64_t* offsets, int n, const int64_t* out_offsets, BatchP
     pl.blocks = fb;
     pl.final_blocks = ff;
     pl.slots = slot;
+    // The flat first pass (k_fit_flat_batched) launches, for every block of the dense grid, as many chunks of
+    // 4 tiles as the block with the most tiles needs.  It pays from the same total length as for a single vector,
+    // and only while most of the launched chunks exist: with a few long vectors among many short ones (whose one
+    // block has few tiles) the grid would be mostly empty.
+    uint64_t total = 0, chunks = 0, most = 0;
+    for (int t = 0; t < n; ++t) {
+        const TensorDesc& ds = pl.desc[t];
+        const uint64_t ntiles = (uint64_t)((ds.d + kTile - 1) / kTile);
+        const uint64_t nwaves = (uint64_t)ds.nblocks * kWavesPerBlock < ntiles ? (uint64_t)ds.nblocks * kWavesPerBlock : ntiles;
+        total += (uint64_t)ds.d;
+        for (uint32_t b = 0; b < ds.nblocks; ++b) {
+            const uint64_t w0 = (uint64_t)b * kWavesPerBlock;
+            const uint64_t w1 = w0 + kWavesPerBlock < nwaves ? w0 + kWavesPerBlock : nwaves;
+            const uint64_t tiles = (w1 * ntiles) / nwaves - (w0 * ntiles) / nwaves;
+            const uint64_t c = (tiles + kFlatBlock / 64 - 1) / (kFlatBlock / 64);
+            chunks += c;
+            if (c > most) most = c;
+        }
+    }
+    pl.flat_gx = 0;
+    if ((int64_t)total >= kFlatMinD && most * fb <= 2 * chunks && most <= 0x7fffffffull / fb &&
+        3 * most * fb <= slot)  // the partial sums borrow the second list buffer
+        pl.flat_gx = (uint32_t)most;
     return SIDCO_OK;
 }
 
@@ -980,10 +1004,24 @@ int sidco_compress_batched_typed(void* stream, const void* grad, int grad_dtype,
     for (int m = 0; m < M; ++m) a.L[m] = log(1.0 / ratios[m]);
     a.use_hint = same_shape ? 1 : 0;
 
+    // The dense stages may prefetch (see launch_compact) if that is safe for every vector: its accumulated values
+    // start on a 16-byte boundary (and its gradient on the boundary the vector path needs), each of its blocks
+    // runs all its waves, and every wave owns the prefetched tiles complete.
+    bool prefetch = true;
+    for (int t = 0; t < n && prefetch; ++t) {
+        const TensorDesc& ds = pl.desc[t];
+        const uint64_t ntiles = (uint64_t)((ds.d + kTile - 1) / kTile), nfull = (uint64_t)(ds.d / kTile);
+        const uint64_t nwaves = (uint64_t)ds.nblocks * kWavesPerBlock;
+        const uintptr_t g = (uintptr_t)grad + (uintptr_t)ds.offset * (gt == kGradF32 ? 4u : 2u);
+        const float* accp = residual ? residual + ds.offset : (a.acc_own ? a.acc_own + ds.offset : nullptr);
+        prefetch = nwaves <= ntiles && nfull / nwaves >= (uint64_t)(kCompactPrefetch * 4 + 1) &&
+                   (g & (gt == kGradF32 ? 15u : 7u)) == 0 && ((uintptr_t)accp & 15u) == 0;
+    }
+
     // same sequence as a single call (see run), every kernel once for all vectors
     a.in = 1;
     a.out = 0;
-    launch_fit_batched(a, residual != nullptr, pl.blocks, s);
+    launch_fit_batched(a, residual != nullptr, pl.blocks, pl.flat_gx, (double*)a.seg[1], s);  // seg[1] is free until the first stage kernel writes it
     bool lists = false, cand = false, reverse = true;
     double cum = 1.0;
     int sel = 0;
@@ -1006,7 +1044,7 @@ int sidco_compress_batched_typed(void* stream, const void* grad, int grad_dtype,
             }
             a.reverse = reverse ? 1 : 0;
             reverse = !reverse;
-            launch_compact_batched(a, /*stats=*/true, write, pl.blocks, s);
+            launch_compact_batched(a, /*stats=*/true, write, prefetch, pl.blocks, s);
             if (write) {
                 lists = true;
                 cand = theta > 0.0;
@@ -1020,7 +1058,7 @@ int sidco_compress_batched_typed(void* stream, const void* grad, int grad_dtype,
     bind(M);
     if (!lists) {
         a.reverse = reverse ? 1 : 0;
-        launch_compact_batched(a, /*stats=*/false, /*write=*/true, pl.blocks, s);
+        launch_compact_batched(a, /*stats=*/false, /*write=*/true, prefetch, pl.blocks, s);
         a.in = sel;  // the gather reads what the compaction just wrote
         launch_gather_batched(a, pl.blocks, s);
     } else {

@@ -249,8 +249,8 @@ struct BatchArgs {
     int use_hint, prev_cand;
 };
 
-void launch_fit_batched(const BatchArgs& a, bool ec, uint32_t blocks, hipStream_t s);
-void launch_compact_batched(const BatchArgs& a, bool stats, bool write, uint32_t blocks, hipStream_t s);
+void launch_fit_batched(const BatchArgs& a, bool ec, uint32_t blocks, uint32_t flat_gx, double* scratch, hipStream_t s);
+void launch_compact_batched(const BatchArgs& a, bool stats, bool write, bool prefetch, uint32_t blocks, hipStream_t s);
 void launch_lists_batched(const BatchArgs& a, uint32_t blocks, hipStream_t s);
 void launch_final_lists_batched(const BatchArgs& a, uint32_t final_blocks, hipStream_t s);
 void launch_gather_batched(const BatchArgs& a, uint32_t blocks, hipStream_t s);

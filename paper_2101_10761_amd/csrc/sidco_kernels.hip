@@ -1177,9 +1177,9 @@ __device__ __forceinline__ Blk whole_grid() { return Blk{blockIdx.x, gridDim.x};
 
 // Arguments of this block's vector in a batched launch.  final_grid: the launch uses the last stage's
 // (smaller) grid.
-__device__ __forceinline__ Params batch_params(const BatchArgs& a, bool final_grid, Blk& b)
+__device__ __forceinline__ Params batch_params(const BatchArgs& a, bool final_grid, Blk& b, uint32_t gb = blockIdx.x)
 {
-    const uint32_t t = __builtin_amdgcn_readfirstlane((uint32_t)(final_grid ? a.tb->fmap[blockIdx.x] : a.tb->map[blockIdx.x]));
+    const uint32_t t = __builtin_amdgcn_readfirstlane((uint32_t)(final_grid ? a.tb->fmap[gb] : a.tb->map[gb]));
     const TensorDesc& ds = a.tb->desc[t];
     Params p = {};
     p.grad = reinterpret_cast<const char*>(a.grad) + ds.offset * (a.gt == kGradF32 ? 4 : 2);
@@ -1218,9 +1218,18 @@ __device__ __forceinline__ Params batch_params(const BatchArgs& a, bool final_gr
     p.out_count = a.out_counts + ds.index;
     p.out_eta = a.out_etas + ds.index;
     p.out_cap = ds.out_cap;
-    b.id = blockIdx.x - (final_grid ? ds.first_final : ds.first_block);
+    b.id = gb - (final_grid ? ds.first_final : ds.first_block);
     b.n = final_grid ? ds.nfinal : ds.nblocks;
     return p;
+}
+
+// Tiles of block b of a vector's dense grid: those of its (at most) kWavesPerBlock waves.
+__device__ __forceinline__ void block_tiles(const Params& p, Blk b, uint32_t& T0, uint32_t& T1)
+{
+    const uint32_t w0 = b.id * kWavesPerBlock;
+    const uint32_t w1 = w0 + kWavesPerBlock < p.nwaves ? w0 + kWavesPerBlock : p.nwaves;
+    T0 = w0 < p.nwaves ? tile_begin(w0, p.ntiles, p.nwaves) : 0;
+    T1 = w0 < p.nwaves ? tile_begin(w1, p.ntiles, p.nwaves) : 0;
 }
 
 template <int DIST, bool EC, int GT>
@@ -1238,12 +1247,93 @@ __global__ __launch_bounds__(kBlock) void k_fit_batched(BatchArgs a)
     const Params p = batch_params(a, false, b);
     fit_body<DIST, EC, GT>(p, b);
 }
-template <bool STATS, bool WRITE>
+// The first pass of a batch in the flat shape (see k_fit_flat): blockIdx.y is a block of the batch's dense grid
+// - it names the vector and, within it, the tiles that block's waves own - and blockIdx.x a chunk of
+// kFlatBlock / 64 = 4 of those tiles, one tile per wave.  Blocks run in the order x first, then y: address
+// order.  Chunks past the end of a y's tiles exit at once (the host launches the flat shape only when few
+// are).  A vector that does not start on a 16-byte boundary (8 for a 16-bit gradient) takes guarded scalar
+// accesses, like the incomplete last tile.
+template <int DIST, bool EC, int GT>
+__global__ __launch_bounds__(kFlatBlock) void k_fit_flat_batched(BatchArgs a, double* __restrict__ flat_part,
+                                                                  uint32_t stride)
+{
+    __shared__ double sh[kFlatBlock / 64][4];
+    Blk b;
+    const Params p = batch_params(a, false, b, blockIdx.y);
+    uint32_t T0, T1;
+    block_tiles(p, b, T0, T1);
+    const uint32_t first = T0 + blockIdx.x * (kFlatBlock / 64);
+    if (first >= T1) return;  // the whole block
+    const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+    const uint32_t t = first + wib;
+    double s1 = 0.0, s2 = 0.0, sl = 0.0;
+    int se = 0;
+    if (t < T1) {
+        if (p.vec_ok && t < p.nfull) {
+            fit_tiles<DIST, EC, GT, 1>(p.grad, reinterpret_cast<f4*>(p.acc_w), t, lane, s1, s2, sl, se);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int64_t i = (int64_t)t * kTile + lane * 4 + j;
+                if (i < p.d) fit_one<DIST, EC, GT>(p, i, s1, s2, sl, se);
+            }
+        }
+    }
+    double v[3] = {s1, s2, sl + (double)se};
+    v[0] = wave_sum(v[0]);
+    v[1] = wave_sum(v[1]);
+    v[2] = wave_sum(v[2]);
+    if (lane == 0) {
+        sh[wib][0] = v[0];
+        sh[wib][1] = v[1];
+        sh[wib][2] = v[2];
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        double tot = 0.0;
+#pragma unroll
+        for (int w = 0; w < kFlatBlock / 64; ++w) tot += sh[w][threadIdx.x];
+        flat_part[(size_t)threadIdx.x * stride + (size_t)blockIdx.y * gridDim.x + blockIdx.x] = tot;
+    }
+}
+
+// Folds the chunks' partial sums of every block y of the batch's dense grid into that block's slot, in a
+// fixed order: one wave per y.  `gx` is the x extent of k_fit_flat_batched's grid, `nb` its y extent.
+__global__ __launch_bounds__(kBlock) void k_fit_reduce_batched(BatchArgs a, const double* __restrict__ flat_part,
+                                                               uint32_t gx, uint32_t nb)
+{
+    const int lane = threadIdx.x & 63;
+    const uint32_t y = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+    if (y >= nb) return;  // the whole wave; no block-wide synchronisation below
+    Blk b;
+    const Params p = batch_params(a, false, b, y);
+    uint32_t T0, T1;
+    block_tiles(p, b, T0, T1);
+    const uint32_t nchunk = (T1 - T0 + kFlatBlock / 64 - 1) / (kFlatBlock / 64);
+    const size_t stride = (size_t)gx * nb, base = (size_t)y * gx;
+    double v[3] = {0.0, 0.0, 0.0};
+    for (uint32_t c = lane; c < nchunk; c += 64) {
+        v[0] += flat_part[base + c];
+        if (p.dist == kDistGpd) v[1] += flat_part[stride + base + c];
+        if (p.dist == kDistGamma) v[2] += flat_part[2 * stride + base + c];
+    }
+    v[0] = wave_sum(v[0]);
+    v[1] = wave_sum(v[1]);
+    v[2] = wave_sum(v[2]);
+    if (lane == 0) {
+        p.part_out[0 * kMaxBlocks + b.id] = v[0];
+        p.part_out[1 * kMaxBlocks + b.id] = v[1];
+        p.part_out[2 * kMaxBlocks + b.id] = v[2];
+        if (b.id == 0) fit_reset_state(p);
+    }
+}
+
+template <bool STATS, bool WRITE, int PRE>
 __global__ __launch_bounds__(kBlock, 4) void k_compact_batched(BatchArgs a)
 {
     Blk b;
     const Params p = batch_params(a, false, b);
-    compact_body<STATS, WRITE, 0>(p, b);
+    compact_body<STATS, WRITE, PRE>(p, b);
 }
 __global__ __launch_bounds__(kBlock, 4) void k_lists_batched(BatchArgs a)
 {
@@ -1362,10 +1452,30 @@ void launch_gather(const Params& p, hipStream_t s)
     hipLaunchKernelGGL(k_gather, dim3(p.nblocks), dim3(kBlock), 0, s, p);
 }
 
-// batched: `blocks` is the sum of the vectors' grids (the last stage's own, smaller sum for launch_final)
+// batched: `blocks` is the sum of the vectors' grids (the last stage's own, smaller sum for launch_final).
+// `flat_gx` > 0: the first pass in the flat shape, `flat_gx` chunks of 4 tiles per block of the dense grid, with
+// `scratch` holding 3 * flat_gx * blocks doubles; a second kernel folds them.
 template <bool EC, int GT>
-static void launch_fit_batched_as(const BatchArgs& a, uint32_t blocks, hipStream_t s)
+static void launch_fit_batched_as(const BatchArgs& a, uint32_t blocks, uint32_t flat_gx, double* scratch, hipStream_t s)
 {
+    if (flat_gx > 0) {
+        const dim3 grid(flat_gx, blocks), block(kFlatBlock);
+        const uint32_t stride = flat_gx * blocks;
+        switch (a.dist) {
+            case kDistExp:
+                hipLaunchKernelGGL((k_fit_flat_batched<kDistExp, EC, GT>), grid, block, 0, s, a, scratch, stride);
+                break;
+            case kDistGamma:
+                hipLaunchKernelGGL((k_fit_flat_batched<kDistGamma, EC, GT>), grid, block, 0, s, a, scratch, stride);
+                break;
+            default:
+                hipLaunchKernelGGL((k_fit_flat_batched<kDistGpd, EC, GT>), grid, block, 0, s, a, scratch, stride);
+                break;
+        }
+        hipLaunchKernelGGL(k_fit_reduce_batched, dim3((blocks + kWavesPerBlock - 1) / kWavesPerBlock), dim3(kBlock), 0, s,
+                           a, scratch, flat_gx, blocks);
+        return;
+    }
     const dim3 grid(blocks), block(kBlock);
     switch (a.dist) {
         case kDistExp: hipLaunchKernelGGL((k_fit_batched<kDistExp, EC, GT>), grid, block, 0, s, a); break;
@@ -1375,27 +1485,37 @@ static void launch_fit_batched_as(const BatchArgs& a, uint32_t blocks, hipStream
 }
 
 template <int GT>
-static void launch_fit_batched_type(const BatchArgs& a, bool ec, uint32_t blocks, hipStream_t s)
+static void launch_fit_batched_type(const BatchArgs& a, bool ec, uint32_t blocks, uint32_t flat_gx, double* scratch,
+                                    hipStream_t s)
 {
-    if (ec) launch_fit_batched_as<true, GT>(a, blocks, s);
-    else launch_fit_batched_as<false, GT>(a, blocks, s);
+    if (ec) launch_fit_batched_as<true, GT>(a, blocks, flat_gx, scratch, s);
+    else launch_fit_batched_as<false, GT>(a, blocks, flat_gx, scratch, s);
 }
 
-void launch_fit_batched(const BatchArgs& a, bool ec, uint32_t blocks, hipStream_t s)
+void launch_fit_batched(const BatchArgs& a, bool ec, uint32_t blocks, uint32_t flat_gx, double* scratch, hipStream_t s)
 {
     switch (a.gt) {
-        case kGradF16: launch_fit_batched_type<kGradF16>(a, ec, blocks, s); break;
-        case kGradBf16: launch_fit_batched_type<kGradBf16>(a, ec, blocks, s); break;
-        default: launch_fit_batched_type<kGradF32>(a, ec, blocks, s); break;
+        case kGradF16: launch_fit_batched_type<kGradF16>(a, ec, blocks, flat_gx, scratch, s); break;
+        case kGradBf16: launch_fit_batched_type<kGradBf16>(a, ec, blocks, flat_gx, scratch, s); break;
+        default: launch_fit_batched_type<kGradF32>(a, ec, blocks, flat_gx, scratch, s); break;
     }
 }
 
-void launch_compact_batched(const BatchArgs& a, bool stats, bool write, uint32_t blocks, hipStream_t s)
+template <int PRE>
+static void launch_compact_batched_pre(const BatchArgs& a, bool stats, bool write, uint32_t blocks, hipStream_t s)
 {
     const dim3 grid(blocks), block(kBlock);
-    if (stats && write) hipLaunchKernelGGL((k_compact_batched<true, true>), grid, block, 0, s, a);
-    else if (stats) hipLaunchKernelGGL((k_compact_batched<true, false>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((k_compact_batched<false, true>), grid, block, 0, s, a);
+    if (stats && write) hipLaunchKernelGGL((k_compact_batched<true, true, PRE>), grid, block, 0, s, a);
+    else if (stats) hipLaunchKernelGGL((k_compact_batched<true, false, PRE>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((k_compact_batched<false, true, PRE>), grid, block, 0, s, a);
+}
+
+// `prefetch`: every vector of the batch meets launch_compact's condition (aligned, all waves of its blocks in
+// use, enough complete tiles per wave), so the dense stage may request tiles before its threshold is known
+void launch_compact_batched(const BatchArgs& a, bool stats, bool write, bool prefetch, uint32_t blocks, hipStream_t s)
+{
+    if (prefetch) launch_compact_batched_pre<kCompactPrefetch>(a, stats, write, blocks, s);
+    else launch_compact_batched_pre<0>(a, stats, write, blocks, s);
 }
 
 void launch_lists_batched(const BatchArgs& a, uint32_t blocks, hipStream_t s)

@@ -93,6 +93,35 @@ def test_config4_full_size_per_tensor(oracle):
     check_batched(oracle, w.grad, w.residual, offs, w.delta, w.dist, w.stages, out, "cfg4 full per tensor")
 
 
+@pytest.mark.parametrize("base_offset", [0, 3])
+def test_long_batches_take_the_flat_first_pass(oracle, base_offset):
+    """From 12 M elements in all the first pass runs as a grid in address order (chunks of four tiles per block of
+    the dense grid): long and tiny tensors side by side, ragged ends, and - with an odd base offset - tensors that
+    do not start on a 16-byte boundary and take the guarded element-wise accesses."""
+    rng = np.random.default_rng(21 + base_offset)
+    sizes = [1, 5_000_003, 17, 7_000_001, 256, 3_000_000, 63, 1025, 2_000_000]
+    offs = [0] + [int(x) for x in np.cumsum(sizes)]
+    g = rng.laplace(0, 1e-3, size=offs[-1]).astype(np.float32)
+    r = rng.laplace(0, 3e-4, size=offs[-1]).astype(np.float32)
+    for dist, stages, delta in ((0, 3, 0.01), (1, 2, 0.001), (2, 3, 0.001)):
+        for res_in in (r, None):
+            out = run_batched(g, res_in, offs, delta, dist, stages, base_offset=base_offset)
+            check_batched(oracle, g, res_in, offs, delta, dist, stages, out,
+                          f"flat batched dist={dist} M={stages} ec={res_in is not None} offset={base_offset}")
+
+
+def test_one_long_tensor_among_many_short_ones_keeps_the_per_wave_first_pass(oracle):
+    """400 short tensors leave the long one a fifth of the blocks: a flat grid would be mostly empty chunks, so the
+    per-wave shape stays; the result does not depend on the choice."""
+    rng = np.random.default_rng(23)
+    sizes = [300] * 200 + [13_000_001] + [500] * 200
+    offs = [0] + [int(x) for x in np.cumsum(sizes)]
+    g = rng.laplace(0, 1e-3, size=offs[-1]).astype(np.float32)
+    r = rng.laplace(0, 3e-4, size=offs[-1]).astype(np.float32)
+    out = run_batched(g, r, offs, 0.01, 0, 2)
+    check_batched(oracle, g, r, offs, 0.01, 0, 2, out, "one long among 400 short")
+
+
 def test_sizes_from_one_element_to_millions(oracle):
     rng = np.random.default_rng(8)
     sizes = [1, 2, 63, 64, 255, 256, 257, 1000, 4099, 1, 70_001, 300_000, 5, 2_000_003, 17]

@@ -181,6 +181,21 @@ def test_batched_ragged_tensors(oracle, kind, with_residual):
 
 
 @pytest.mark.parametrize("kind", ["f16", "bf16"])
+def test_batched_flat_first_pass(oracle, kind):
+    """Long batches (12 M elements and more) take the first pass in address order; 16-bit tensors that start on an
+    8-byte boundary are read four elements at a time there, the others element by element."""
+    from test_gpu_batched import run_batched, check_batched
+    rng = np.random.default_rng(31)
+    sizes = [6_000_001, 2, 4_000_000, 1023, 3_000_004]
+    offs = [0] + [int(x) for x in np.cumsum(sizes)]
+    g16, gw = narrow(rng.laplace(0, 1e-2, size=offs[-1]).astype(np.float32), kind)
+    r = rng.laplace(0, 3e-3, size=offs[-1]).astype(np.float32)
+    for res_in, base in ((r, 0), (None, 0), (r, 1)):
+        out = run_batched(g16, res_in, offs, 0.001, 2, 3, base_offset=base)
+        check_batched(oracle, gw, res_in, offs, 0.001, 2, 3, out, f"{kind} flat batched ec={res_in is not None} base={base}")
+
+
+@pytest.mark.parametrize("kind", ["f16", "bf16"])
 def test_batched_small_tensors(oracle, kind):
     from test_gpu_batched import run_batched, check_batched
     rng = np.random.default_rng(8)
