@@ -67,6 +67,14 @@ int main()
     EXPECT(sidco_compress_batched(nullptr, g, r, offs_bad, 2, 0.5, 0, 1, oi, ov, out_offs, oc, oe) == SIDCO_ERR_SIZE);
     EXPECT(sidco_compress_batched(nullptr, g, r, offs_ok, 600, 0.5, 0, 1, oi, ov, out_offs, oc, oe) == SIDCO_ERR_SIZE);
     EXPECT(sidco_compress_batched(nullptr, g, nullptr, nullptr, 2, 0.5, 0, 1, oi, ov, out_offs, oc, oe) == SIDCO_ERR_NULL);
+    EXPECT(sidco_compress_batched_typed(nullptr, g, 9, r, offs_ok, 2, 0.5, 0, 1, oi, ov, out_offs, oc, oe) == SIDCO_ERR_ARG);
+    EXPECT(sidco_compress_batched_typed(nullptr, (const char*)g + 1, SIDCO_GRAD_F16, r, offs_ok, 2, 0.5, 0, 1, oi, ov, out_offs, oc, oe) == SIDCO_ERR_ALIGN);
+    EXPECT(sidco_workspace_bytes_batched_typed(offs_ok, 2, SIDCO_GRAD_F16, 0) > sidco_workspace_bytes_batched_typed(offs_ok, 2, SIDCO_GRAD_F16, 1));
+    EXPECT(sidco_workspace_bytes_batched_typed(offs_ok, 2, 9, 0) == 0);
+    EXPECT(sidco_topk_typed(nullptr, g, 9, r, 16, 4, oi, ov, oc, oe) == SIDCO_ERR_ARG);
+    EXPECT(sidco_topk_typed(nullptr, (const char*)g + 2, SIDCO_GRAD_F32, r, 8, 4, oi, ov, oc, oe) == SIDCO_ERR_ALIGN);
+    EXPECT(sidco_dgc_typed(nullptr, g, -1, r, 16, 0.01, 0.01, 1, oi, ov, oc, oe) == SIDCO_ERR_ARG);
+    EXPECT(sidco_dgc_typed(nullptr, (const char*)g + 1, SIDCO_GRAD_BF16, r, 8, 0.01, 0.01, 1, oi, ov, oc, oe) == SIDCO_ERR_ALIGN);
     EXPECT(sidco_workspace_bytes_batched(offs_ok, 2) > 0);
     EXPECT(sidco_workspace_bytes_batched(offs_bad, 2) == 0);
 
@@ -99,6 +107,7 @@ int main()
     EXPECT(sidco_controller_create(&c, 0.01, 0, 1, 4, 5, 0.2, 0.2, 0.25) == SIDCO_OK && c != nullptr);
     EXPECT(sidco_controller_stages(c) == 1 && sidco_controller_iteration(c) == 0 && sidco_controller_disturbed(c) == 0);
     EXPECT(sidco_controller_compress(c, nullptr, nullptr, r, 16, oi, ov, oc, oe) == SIDCO_ERR_NULL);
+    EXPECT(sidco_controller_compress_typed(c, nullptr, g, 9, r, 16, oi, ov, oc, oe) == SIDCO_ERR_ARG);
     sidco_controller_destroy(c);
     EXPECT(sidco_controller_create(&c, 0.01, 0, 5, 4, 5, 0.2, 0.2, 0.25) == SIDCO_ERR_STAGES && c == nullptr);
     EXPECT(sidco_controller_create(nullptr, 0.01, 0, 1, 4, 5, 0.2, 0.2, 0.25) == SIDCO_ERR_NULL);
