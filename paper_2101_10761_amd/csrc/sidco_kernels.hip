@@ -9,15 +9,21 @@
 //                folds the per-block sums into the 512 slots the next kernel expects (long vectors,
 //                whose operands come from HBM: that shape streams 15 % faster there).
 //                The gradient may be fp16 / bf16; it is widened as it is read.
-//   k_compact<m> m = 1..M.  Prologue: every block reduces the previous kernel's partial sums in a
-//                fixed order and evaluates the closed-form threshold eta_m in fp64 (identical bits
-//                in every block).  Body: exceedances {|x| > eta_m} of the source (the dense acc
-//                for m = 1, the previous survivor lists afterwards) are appended to per-wave
-//                survivor lists; for m < M the sums of (|x| - eta_m) and its square are formed for
-//                the next stage's fit.
-//                The last stage differs: for M >= 2 its source lists are short, and k_final_lists
-//                selects, writes the contiguous (index, value) output and zeroes the residual at
-//                those indices in one kernel, each block reserving its output range with one atomic.
+//   stage m      m = 1..M, one kernel each.  Prologue: every block reduces the previous kernel's partial
+//                sums in a fixed order and its first wave evaluates the closed-form threshold eta_m in
+//                fp64 (the same arithmetic, hence identical bits, in every block).
+//                k_compact: the stage whose source is the dense acc (m = 1; also later stages while the
+//                exceedances are still a large part of the vector).  It forms n and the sums of
+//                (|x| - eta_m) and its square over the exceedances for the next stage's fit, and writes
+//                per-wave lists of the entries above a candidate threshold at or above eta_m - high enough
+//                that the lists stay short, low enough (judged from the fit and from where the previous
+//                call's next threshold fell) that the next stage can select from them alone.  On long
+//                vectors a wave requests tiles before its threshold is known and stays a batch ahead.
+//                k_lists: a middle stage whose source is those lists (or, if they turn out not to reach
+//                down to its threshold, the dense acc again): same sums, exact exceedance lists out.
+//                k_final_lists: the last stage for M >= 2; it selects, writes the contiguous
+//                (index, value) output and zeroes the residual at those indices in one kernel, each
+//                block reserving its output range with one atomic.
 //   k_gather     M = 1 only (last stage read the dense vector): exclusive prefix over the per-block
 //                survivor counts, copy of the lists into the output, residual zeroing.
 //
@@ -26,6 +32,8 @@
 // neither.  Kernel boundaries are the only global synchronisation; every wave owns a contiguous
 // range of 256-element tiles and a survivor list at the same offset, so list positions need no
 // atomics, and thresholds, selected set and values are deterministic.
+// The *_batched kernels run the same bodies for the vectors of a batch, each block on the vector that a
+// table on the device assigns to it.
 //
 // All floating-point accumulation is fp64 (full rate on CDNA4 vector ALUs); comparisons are fp32
 // against the fp32 threshold, so the decision |x| > eta is the same one an fp32 reference takes.
